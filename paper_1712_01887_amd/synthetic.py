@@ -1,0 +1,197 @@
+"""Seeded synthetic gradient sets shaped like the paper's models.
+
+This module only lists tensor shapes and draws random numbers.  It holds none
+of the method's arithmetic, so both the HIP path's callers and the CPU oracle's
+callers may feed from it.  The gradients stand in for those of the paper's
+ImageNet, Penn Treebank and LibriSpeech runs (Tables 3 and 4), whose data and
+trained weights are not available: shapes and sizes follow the models named
+there, values are heavy-tailed noise (Student-t, 3 degrees of freedom) with a
+per-tensor scale drawn log-uniformly in [1e-5, 1e-2].
+"""
+
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class TensorSpec:
+    name: str
+    shape: Tuple[int, ...]
+
+    @property
+    def numel(self) -> int:
+        return int(math.prod(self.shape))
+
+
+@dataclass(frozen=True)
+class GradientSet:
+    name: str
+    tensors: Tuple[TensorSpec, ...]
+
+    @property
+    def sizes(self) -> List[int]:
+        return [t.numel for t in self.tensors]
+
+    @property
+    def offsets(self) -> np.ndarray:
+        return np.concatenate([[0], np.cumsum(self.sizes)]).astype(np.int64)
+
+    @property
+    def numel(self) -> int:
+        return int(sum(self.sizes))
+
+
+# ---------------------------------------------------------------------------
+# Manifests
+# ---------------------------------------------------------------------------
+def toy_set(n: int = 1 << 20) -> GradientSet:
+    return GradientSet("toy", (TensorSpec("w", (n,)),))
+
+
+def resnet50_set() -> GradientSet:
+    """161 tensors, 25,557,032 parameters = 97.49 MiB (Table 3's baseline size)."""
+    ts: List[TensorSpec] = []
+
+    def bn(prefix: str, c: int) -> None:
+        ts.append(TensorSpec(prefix + ".weight", (c,)))
+        ts.append(TensorSpec(prefix + ".bias", (c,)))
+
+    ts.append(TensorSpec("conv1.weight", (64, 3, 7, 7)))
+    bn("bn1", 64)
+    inplanes = 64
+    for stage, (planes, blocks) in enumerate(zip((64, 128, 256, 512), (3, 4, 6, 3)), 1):
+        for b in range(blocks):
+            p = f"layer{stage}.{b}"
+            ts.append(TensorSpec(p + ".conv1.weight", (planes, inplanes, 1, 1)))
+            bn(p + ".bn1", planes)
+            ts.append(TensorSpec(p + ".conv2.weight", (planes, planes, 3, 3)))
+            bn(p + ".bn2", planes)
+            ts.append(TensorSpec(p + ".conv3.weight", (planes * 4, planes, 1, 1)))
+            bn(p + ".bn3", planes * 4)
+            if b == 0:
+                ts.append(TensorSpec(p + ".downsample.0.weight", (planes * 4, inplanes, 1, 1)))
+                bn(p + ".downsample.1", planes * 4)
+            inplanes = planes * 4
+    ts.append(TensorSpec("fc.weight", (1000, 2048)))
+    ts.append(TensorSpec("fc.bias", (1000,)))
+    return GradientSet("resnet50", tuple(ts))
+
+
+LSTM_EMBED_ROWS = 10000
+LSTM_EMBED_DIM = 1500
+LSTM_ACTIVE_ROWS = 700
+
+
+def lstm_lm_set() -> GradientSet:
+    """Untied 2-layer LSTM-1500 language model, 66,034,000 parameters."""
+    ts = [TensorSpec("encoder.weight", (LSTM_EMBED_ROWS, LSTM_EMBED_DIM))]
+    for l in range(2):
+        ts.append(TensorSpec(f"rnn.weight_ih_l{l}", (6000, 1500)))
+        ts.append(TensorSpec(f"rnn.weight_hh_l{l}", (6000, 1500)))
+        ts.append(TensorSpec(f"rnn.bias_ih_l{l}", (6000,)))
+        ts.append(TensorSpec(f"rnn.bias_hh_l{l}", (6000,)))
+    ts.append(TensorSpec("decoder.weight", (10000, 1500)))
+    ts.append(TensorSpec("decoder.bias", (10000,)))
+    return GradientSet("lstm_lm", tuple(ts))
+
+
+def speech_set() -> GradientSet:
+    """Two convolutions, seven bidirectional GRU layers of 1200 units
+    (Section 4.1's speech model), one output layer: 122,153,069 parameters."""
+    ts = [TensorSpec("conv.0.weight", (32, 1, 41, 11)), TensorSpec("conv.0.bias", (32,)),
+          TensorSpec("conv.1.weight", (32, 32, 21, 11)), TensorSpec("conv.1.bias", (32,))]
+    hidden = 1200
+    for l in range(7):
+        inp = 1312 if l == 0 else hidden
+        for d in ("", "_reverse"):
+            ts.append(TensorSpec(f"gru.{l}.weight_ih{d}", (3 * hidden, inp)))
+            ts.append(TensorSpec(f"gru.{l}.weight_hh{d}", (3 * hidden, hidden)))
+            ts.append(TensorSpec(f"gru.{l}.bias_ih{d}", (3 * hidden,)))
+            ts.append(TensorSpec(f"gru.{l}.bias_hh{d}", (3 * hidden,)))
+    ts.append(TensorSpec("fc.weight", (29, hidden)))
+    ts.append(TensorSpec("fc.bias", (29,)))
+    return GradientSet("speech", tuple(ts))
+
+
+def ragged_set(seed: int = 0, tensors: int = 23, max_numel: int = 70000) -> GradientSet:
+    """Small set with odd sizes (tiny, unaligned and multi-tile tensors)."""
+    rng = np.random.Generator(np.random.Philox(key=seed + 77))
+    sizes = [1, 3, 29, 64, 4097, 5000, 16384, 33333]
+    while len(sizes) < tensors:
+        sizes.append(int(math.exp(rng.uniform(0.0, math.log(max_numel)))))
+    order = rng.permutation(len(sizes))
+    return GradientSet("ragged", tuple(TensorSpec(f"t{i}", (int(sizes[i]),)) for i in order))
+
+
+# ---------------------------------------------------------------------------
+# Values
+# ---------------------------------------------------------------------------
+def _rng(base_seed: int, worker: int, iteration: int, salt: int = 0) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(
+        key=[(int(base_seed) * 1000003 + salt) & 0xFFFFFFFFFFFFFFFF,
+             ((int(worker) & 0xFFFFFFFF) << 32) | (int(iteration) & 0xFFFFFFFF)]))
+
+
+def tensor_scales(gs: GradientSet, base_seed: int, fixed: Optional[float] = None) -> np.ndarray:
+    """Per-tensor standard deviation, log-uniform in [1e-5, 1e-2], drawn once per set."""
+    if fixed is not None:
+        return np.full(len(gs.tensors), fixed, dtype=np.float64)
+    rng = _rng(base_seed, 0xFFFF, 0xFFFF, salt=1)
+    return np.exp(rng.uniform(math.log(1e-5), math.log(1e-2), size=len(gs.tensors)))
+
+
+def _student_t3(rng: np.random.Generator, n: int) -> np.ndarray:
+    return rng.standard_t(3.0, size=n)
+
+
+def gradient(gs: GradientSet, base_seed: int, worker: int, iteration: int,
+             scales: Optional[np.ndarray] = None, out: Optional[np.ndarray] = None) -> np.ndarray:
+    """Flat fp32 gradient of worker `worker` at `iteration`: sigma_j * t(3) per tensor."""
+    if scales is None:
+        scales = tensor_scales(gs, base_seed)
+    rng = _rng(base_seed, worker, iteration)
+    offs = gs.offsets
+    if out is None:
+        out = np.empty(gs.numel, dtype=np.float32)
+    for j, sz in enumerate(gs.sizes):
+        out[offs[j]:offs[j + 1]] = (scales[j] * _student_t3(rng, sz)).astype(np.float32)
+    return out
+
+
+def toy_gradient(n: int, base_seed: int, worker: int, iteration: int) -> np.ndarray:
+    """Toy configuration: 1e-3 * t(3)."""
+    rng = _rng(base_seed, worker, iteration)
+    return (1e-3 * _student_t3(rng, n)).astype(np.float32)
+
+
+def lstm_gradient(gs: GradientSet, base_seed: int, worker: int, iteration: int,
+                  scales: Optional[np.ndarray] = None) -> np.ndarray:
+    """As `gradient`, but the embedding gradient is zero outside 700 seeded rows."""
+    g = gradient(gs, base_seed, worker, iteration, scales)
+    rng = _rng(base_seed, worker, iteration, salt=2)
+    rows = rng.choice(LSTM_EMBED_ROWS, size=LSTM_ACTIVE_ROWS, replace=False)
+    keep = np.zeros(LSTM_EMBED_ROWS, dtype=bool)
+    keep[rows] = True
+    emb = g[: LSTM_EMBED_ROWS * LSTM_EMBED_DIM].reshape(LSTM_EMBED_ROWS, LSTM_EMBED_DIM)
+    emb[~keep] = 0.0
+    return g
+
+
+def correlated_gradient(gs: GradientSet, base_seed: int, worker: int, iteration: int,
+                        shared: np.ndarray, mix: float = 0.55) -> np.ndarray:
+    """Worker gradient = mix * shared + (1 - mix) * private, both heavy-tailed, so
+    that different workers' largest elements partly coincide."""
+    private = gradient(gs, base_seed, worker + 1000, iteration)
+    return (np.float32(mix) * shared + np.float32(1.0 - mix) * private).astype(np.float32)
+
+
+def topk_overlap(idx_a: np.ndarray, idx_b: np.ndarray) -> float:
+    """Fraction of a's indices also present in b."""
+    if idx_a.size == 0:
+        return 0.0
+    return float(np.intersect1d(idx_a, idx_b).size) / float(idx_a.size)
