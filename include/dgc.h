@@ -1,0 +1,225 @@
+/*
+ * libdgc -- the per-worker hot path of Deep Gradient Compression
+ * (arXiv 1712.01887) as HIP kernels for gfx950 behind a C ABI.
+ *
+ * One call of dgc_compress is one iteration of Algorithm 3 (Appendix D) on one
+ * worker, from the clipping line to the mask lines, for a whole gradient set
+ * stored flat; dgc_decompress_accumulate is the sum in its all-reduce line.
+ *
+ * Conventions
+ *   - Every function returns a dgc_status (0 = success, negative = error).
+ *     No exception or abort crosses this boundary.
+ *   - "device" pointers address GPU memory of the current HIP device, "host"
+ *     pointers address ordinary process memory.  The library never takes
+ *     ownership of a buffer and never frees one.
+ *   - All device work is enqueued on the caller's stream (a hipStream_t passed
+ *     as void*, NULL = the default stream) and is asynchronous; only
+ *     dgc_get_diagnostics waits for the stream.
+ *   - Flat layout: tensor j of the set occupies elements
+ *     [offsets[j], offsets[j+1]) of g, u, v and of the dense aggregate.
+ *     Element type is IEEE binary32; indices are int32 (n < 2^31).
+ *   - Arithmetic is binary32 with one rounding per operation (no fused
+ *     multiply-add, denormals kept); the clipping norm is accumulated in
+ *     binary64.
+ */
+#ifndef DGC_H_
+#define DGC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t dgc_status;
+enum {
+  DGC_OK = 0,
+  DGC_ERR_INVALID_ARG = -1, /* null pointer, value out of range                */
+  DGC_ERR_ALIGNMENT = -2,   /* g, u, v or dense not 16-byte aligned            */
+  DGC_ERR_CAPACITY = -3,    /* workspace too small, too many payloads/tensors  */
+  DGC_ERR_HIP = -4,         /* a HIP runtime call failed                       */
+  DGC_ERR_STATE = -5        /* call order violated                             */
+};
+
+/* dgc_config.flags */
+enum {
+  DGC_FLAG_NESTEROV = 1u << 0,          /* Algorithm 4: U <- m(U+G); V <- V+U+G          */
+  DGC_FLAG_NO_FACTOR_MASKING = 1u << 1, /* leave U untouched (Section 3.3 switched off)   */
+  DGC_FLAG_EXACT_SELECT = 1u << 2,      /* threshold from the whole tensor, not a sample  */
+  DGC_FLAG_DETERMINISTIC_ACCUMULATE = 1u << 3 /* receive side adds workers in order       */
+};
+
+/* dgc_diagnostics.flags */
+enum {
+  DGC_DIAG_OVERFLOW = 1u << 0,   /* some tensor had more passes than payload capacity */
+  DGC_DIAG_NONFINITE = 1u << 1,  /* the clipping norm was not finite                  */
+  DGC_DIAG_BAD_INDEX = 1u << 2   /* a payload index fell outside [0, n): skipped      */
+};
+
+/*
+ * Arguments of the method (Algorithm 3 "Require": momentum m, node count N;
+ * Appendix C: global clipping threshold; Section 4.1: density = 1 - sparsity;
+ * Section 5: the threshold is estimated on a sample of 0.1 % .. 1 %).
+ */
+typedef struct dgc_config {
+  float momentum;        /* m                                                        */
+  float clip_threshold;  /* thr_G; the local one is thr_G / sqrt(N); <= 0: no clip   */
+  int32_t num_workers;   /* N >= 1                                                   */
+  uint32_t flags;        /* DGC_FLAG_*                                               */
+  double density;        /* d in (0, 1]; k_j = clamp(ceil(d * n_j), 1, n_j)          */
+  double sample_ratio;   /* wanted sample size as a fraction of n_j (0.01)           */
+  int32_t sample_min;    /* lower clamp of the sample size (4096)                    */
+  int32_t sample_max;    /* upper clamp of the sample size (32768)                   */
+  int32_t sample_block;  /* consecutive elements per draw, power of two <= 64 (16)   */
+  float scale_override;  /* test hook: NaN = unused, else replaces the clip scale    */
+  uint64_t seed;         /* seed of the counter-based sample positions               */
+} dgc_config;
+
+typedef struct dgc_diagnostics {
+  double norm;     /* L2 norm of g over the whole set (NaN when clipping is off) */
+  float scale;     /* factor applied to g                                         */
+  uint32_t flags;  /* DGC_DIAG_*                                                  */
+} dgc_diagnostics;
+
+typedef struct dgc_handle dgc_handle;
+
+/* Fill *cfg with m = 0.9, no clipping, N = 1, d = 0.001, sampling 1 % clamped to
+ * [4096, 32768] in blocks of 16, seed 0. */
+dgc_status dgc_config_default(dgc_config* cfg);
+
+/* Text for a status code (static storage). */
+const char* dgc_status_string(dgc_status s);
+
+/*
+ * Create the host-side description of a gradient set.
+ *   offsets_host: host, num_tensors + 1 ascending element offsets, offsets[0] = 0,
+ *                 every tensor non-empty, offsets[num_tensors] = n < 2^31.
+ * Allocates host memory only.  The handle is not thread-safe.
+ */
+dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tensors,
+                      const int64_t* offsets_host);
+dgc_status dgc_destroy(dgc_handle* h);
+
+/*
+ * Density control (Section 3.3 "warm-up training"; Section 4.1 lists the
+ * sparsities 75 %, 93.75 %, 98.4375 %, 99.6 %, 99.9 %).  Host only: recomputes
+ * k_j and the sample plan; the next dgc_compress uploads the new plan.
+ */
+dgc_status dgc_set_density(dgc_handle* h, double density);
+/* Replace the warm-up table (host, len >= 1 densities in (0, 1]).  The default
+ * table is {0.25, 0.0625, 0.015625, 0.004, 0.001}. */
+dgc_status dgc_set_warmup_schedule(dgc_handle* h, const double* densities_host, int32_t len);
+/* density <- table[min(iteration, len - 1)]. */
+dgc_status dgc_set_iteration_density(dgc_handle* h, int64_t iteration);
+
+/*
+ * Host arithmetic of tensor j under the current density (any pointer may be NULL):
+ *   k            = clamp(ceil(d * n_j), 1, n_j)
+ *   sample_count = candidates the threshold is selected from (n_j when the whole
+ *                  tensor is used, else draws * sample_block)
+ *   rank         = 0-based descending rank whose magnitude becomes the threshold
+ *   draws        = number of sampled blocks (0 when the whole tensor is used)
+ */
+dgc_status dgc_query_plan(const dgc_handle* h, int32_t j, int64_t* k, int64_t* sample_count,
+                          int64_t* rank, int64_t* draws);
+
+/* Bytes of device workspace dgc_compress needs for this set (any density). */
+dgc_status dgc_workspace_bytes(const dgc_handle* h, size_t* bytes);
+
+/*
+ * A payload layout for `density`: out_offsets_host (host, num_tensors + 1) receives
+ * the start of each tensor's pair region, capacity_j = min(n_j, max(4 k_j, k_j + 256)).
+ */
+dgc_status dgc_recommended_payload_layout(const dgc_handle* h, double density,
+                                          int64_t* out_offsets_host);
+
+/*
+ * One iteration on one worker (Algorithm 3, or Algorithm 4 with DGC_FLAG_NESTEROV):
+ *   scale  = clip ? min(1, (thr_G / sqrt N) / ||g||_2) : 1          (Appendix C)
+ *   u'     = m u + scale g ;  v' = v + u'                            (equation 7)
+ *   thr_j  = magnitude of descending rank r_j among the sampled |v'| of tensor j,
+ *            or of the whole tensor when it is small or EXACT_SELECT (Section 5)
+ *   keep   = |v'| > thr_j  (strict)                                  (Algorithm 3)
+ *   emit (global flat index, v') for kept elements; v <- keep ? 0 : v';
+ *   u <- keep ? 0 : u'                                               (Section 3.3)
+ *
+ *   g          device, n floats, read only (clipping is folded into `scale`)
+ *   u, v       device, n floats, updated in place; zero them before iteration 0
+ *   out_idx    device, int32[out_offsets_host[num_tensors]]
+ *   out_val    device, float[same]
+ *   out_offsets_host  host, num_tensors + 1 ascending starts of each tensor's pair
+ *              region; read during the call (the caller may reuse it afterwards)
+ *   out_counts device, int32[num_tensors]: elements of tensor j that passed the
+ *              mask.  Pairs [out_offsets[j], out_offsets[j] + min(count_j, capacity_j))
+ *              are valid, in unspecified order.  An element that passed but found the
+ *              region full is neither emitted nor cleared (it stays in u, v) and
+ *              DGC_DIAG_OVERFLOW is raised.
+ *   out_thr    device, float[num_tensors], or NULL
+ *   iteration  t: with the seed and the tensor index it fixes the sample positions
+ *   workspace  device, >= dgc_workspace_bytes, 256-byte aligned; it must not be
+ *              shared by calls that may overlap in time
+ * Errors: INVALID_ARG (null, bad layout), ALIGNMENT, CAPACITY (workspace), HIP.
+ */
+dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32_t* out_idx,
+                        float* out_val, const int64_t* out_offsets_host, int32_t* out_counts,
+                        float* out_thr, uint64_t iteration, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
+/* Copy norm, scale and flags of the last dgc_compress that used `workspace` to the
+ * host.  Waits for `stream`. */
+dgc_status dgc_get_diagnostics(dgc_handle* h, const void* workspace, dgc_diagnostics* out_host,
+                               void* stream);
+
+/*
+ * Receive side (the sum of Algorithm 3's all-reduce line; no division by N, the
+ * 1/(N b) factor is already inside every worker's gradient):
+ *   for each payload w, each pair p < pair_counts_host[w]:
+ *       dense[idx_w[p]] += val_w[p]
+ *   dense        device, n floats, accumulated into (zero it for a fresh sum)
+ *   num_payloads 1 .. 64
+ *   idx_ptrs_host, val_ptrs_host   host arrays of num_payloads device pointers
+ *   pair_counts_host               host, pairs in each payload (>= 0)
+ * Pairs with an index outside [0, n) are skipped and flagged in *diag_flags_dev
+ * (device uint32, may be NULL).  Without DGC_FLAG_DETERMINISTIC_ACCUMULATE the
+ * additions are hardware float atomics in arbitrary order; with it, workers are
+ * added in the order given and every index of one payload must be distinct.
+ */
+dgc_status dgc_decompress_accumulate(dgc_handle* h, float* dense, int64_t n, int32_t num_payloads,
+                                     const int32_t* const* idx_ptrs_host,
+                                     const float* const* val_ptrs_host,
+                                     const int64_t* pair_counts_host, uint32_t* diag_flags_dev,
+                                     void* stream);
+
+/*
+ * The same sum taken straight from dgc_compress outputs, with no host round trip:
+ * payload w is (idx_w, val_w, counts_w) in the per-tensor region layout
+ * `out_offsets_host`; counts_w is the device int32[num_tensors] written by
+ * dgc_compress (clamped to each region's capacity here).
+ *   workspace    device workspace of this handle (holds the layout copy)
+ */
+dgc_status dgc_decompress_accumulate_regions(dgc_handle* h, float* dense, int32_t num_payloads,
+                                             const int32_t* const* idx_ptrs_host,
+                                             const float* const* val_ptrs_host,
+                                             const int32_t* const* count_ptrs_host,
+                                             const int64_t* out_offsets_host, void* workspace,
+                                             size_t workspace_bytes, void* stream);
+
+/*
+ * dense[idx] = 0 for every pair of the given region-layout payloads: returns a
+ * dense aggregate to all-zero after it has been consumed at the cost of the
+ * payload size instead of a full fill.  Arguments as above.
+ */
+dgc_status dgc_dense_clear_regions(dgc_handle* h, float* dense, int32_t num_payloads,
+                                   const int32_t* const* idx_ptrs_host,
+                                   const int32_t* const* count_ptrs_host,
+                                   const int64_t* out_offsets_host, void* workspace,
+                                   size_t workspace_bytes, void* stream);
+
+/* Library version, major * 1000 + minor. */
+int32_t dgc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DGC_H_ */

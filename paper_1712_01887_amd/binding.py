@@ -1,0 +1,288 @@
+"""ctypes binding of libdgc: argument marshalling only.
+
+The function names mirror the C ABI declared in include/dgc.h.  torch is used
+for device memory and streams; every step of the path runs in the library's
+HIP kernels.  There is no fallback: if libdgc.so has not been built, `load()`
+raises.
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import math
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libdgc.so")
+
+DGC_OK = 0
+DGC_ERR_INVALID_ARG = -1
+DGC_ERR_ALIGNMENT = -2
+DGC_ERR_CAPACITY = -3
+DGC_ERR_HIP = -4
+DGC_ERR_STATE = -5
+
+DGC_FLAG_NESTEROV = 1 << 0
+DGC_FLAG_NO_FACTOR_MASKING = 1 << 1
+DGC_FLAG_EXACT_SELECT = 1 << 2
+DGC_FLAG_DETERMINISTIC_ACCUMULATE = 1 << 3
+
+DGC_DIAG_OVERFLOW = 1 << 0
+DGC_DIAG_NONFINITE = 1 << 1
+DGC_DIAG_BAD_INDEX = 1 << 2
+
+EXPORTS = [
+    "dgc_config_default", "dgc_status_string", "dgc_create", "dgc_destroy", "dgc_set_density",
+    "dgc_set_warmup_schedule", "dgc_set_iteration_density", "dgc_query_plan", "dgc_workspace_bytes",
+    "dgc_recommended_payload_layout", "dgc_compress", "dgc_get_diagnostics",
+    "dgc_decompress_accumulate", "dgc_decompress_accumulate_regions", "dgc_dense_clear_regions",
+    "dgc_version",
+]
+
+
+class DgcConfig(C.Structure):
+    _fields_ = [
+        ("momentum", C.c_float),
+        ("clip_threshold", C.c_float),
+        ("num_workers", C.c_int32),
+        ("flags", C.c_uint32),
+        ("density", C.c_double),
+        ("sample_ratio", C.c_double),
+        ("sample_min", C.c_int32),
+        ("sample_max", C.c_int32),
+        ("sample_block", C.c_int32),
+        ("scale_override", C.c_float),
+        ("seed", C.c_uint64),
+    ]
+
+
+class DgcDiagnostics(C.Structure):
+    _fields_ = [("norm", C.c_double), ("scale", C.c_float), ("flags", C.c_uint32)]
+
+
+class DgcError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: status {status}")
+        self.status = status
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Open libdgc.so and declare its prototypes.  Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is not built; run `python -m paper_1712_01887_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64, u64, dbl = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_double
+    P = C.POINTER
+    lib.dgc_version.restype = i32
+    lib.dgc_version.argtypes = []
+    lib.dgc_status_string.restype = C.c_char_p
+    lib.dgc_status_string.argtypes = [i32]
+    lib.dgc_config_default.restype = i32
+    lib.dgc_config_default.argtypes = [P(DgcConfig)]
+    lib.dgc_create.restype = i32
+    lib.dgc_create.argtypes = [P(vp), P(DgcConfig), i32, P(i64)]
+    lib.dgc_destroy.restype = i32
+    lib.dgc_destroy.argtypes = [vp]
+    lib.dgc_set_density.restype = i32
+    lib.dgc_set_density.argtypes = [vp, dbl]
+    lib.dgc_set_warmup_schedule.restype = i32
+    lib.dgc_set_warmup_schedule.argtypes = [vp, P(dbl), i32]
+    lib.dgc_set_iteration_density.restype = i32
+    lib.dgc_set_iteration_density.argtypes = [vp, i64]
+    lib.dgc_query_plan.restype = i32
+    lib.dgc_query_plan.argtypes = [vp, i32, P(i64), P(i64), P(i64), P(i64)]
+    lib.dgc_workspace_bytes.restype = i32
+    lib.dgc_workspace_bytes.argtypes = [vp, P(C.c_size_t)]
+    lib.dgc_recommended_payload_layout.restype = i32
+    lib.dgc_recommended_payload_layout.argtypes = [vp, dbl, P(i64)]
+    lib.dgc_compress.restype = i32
+    lib.dgc_compress.argtypes = [vp, vp, vp, vp, vp, vp, P(i64), vp, vp, u64, vp, C.c_size_t, vp]
+    lib.dgc_get_diagnostics.restype = i32
+    lib.dgc_get_diagnostics.argtypes = [vp, vp, P(DgcDiagnostics), vp]
+    lib.dgc_decompress_accumulate.restype = i32
+    lib.dgc_decompress_accumulate.argtypes = [vp, vp, i64, i32, P(vp), P(vp), P(i64), vp, vp]
+    lib.dgc_decompress_accumulate_regions.restype = i32
+    lib.dgc_decompress_accumulate_regions.argtypes = [vp, vp, i32, P(vp), P(vp), P(vp), P(i64), vp,
+                                                      C.c_size_t, vp]
+    lib.dgc_dense_clear_regions.restype = i32
+    lib.dgc_dense_clear_regions.argtypes = [vp, vp, i32, P(vp), P(vp), P(i64), vp, C.c_size_t, vp]
+    _lib = lib
+    return lib
+
+
+def _check(status: int, what: str) -> None:
+    if status != DGC_OK:
+        raise DgcError(status, f"{what}: {load().dgc_status_string(status).decode()}")
+
+
+def dgc_config_default() -> DgcConfig:
+    cfg = DgcConfig()
+    _check(load().dgc_config_default(C.byref(cfg)), "dgc_config_default")
+    return cfg
+
+
+def make_config(**kw) -> DgcConfig:
+    cfg = dgc_config_default()
+    for k, v in kw.items():
+        if not hasattr(cfg, k):
+            raise AttributeError(k)
+        setattr(cfg, k, v)
+    return cfg
+
+
+def _i64_array(values: Sequence[int]):
+    arr = (C.c_int64 * len(values))(*[int(x) for x in values])
+    return arr
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else int(t.data_ptr())
+
+
+def _stream() -> int:
+    import torch
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr_array(tensors) -> "C.Array":
+    return (C.c_void_p * len(tensors))(*[_ptr(t) for t in tensors])
+
+
+class Dgc:
+    """One gradient set on one worker: the handle of the C ABI plus its workspace."""
+
+    def __init__(self, cfg: DgcConfig, offsets: Sequence[int]):
+        self.lib = load()
+        self.cfg = cfg
+        self.offsets = [int(x) for x in offsets]
+        self.num_tensors = len(self.offsets) - 1
+        self.n = self.offsets[-1]
+        self._h = C.c_void_p()
+        _check(self.lib.dgc_create(C.byref(self._h), C.byref(cfg), self.num_tensors,
+                                   _i64_array(self.offsets)), "dgc_create")
+        self.workspace = None
+        self._layout = None
+        self._layout_c = None
+
+    def close(self) -> None:
+        if self._h:
+            self.lib.dgc_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- host-only calls ---------------------------------------------------
+    def dgc_set_density(self, density: float) -> None:
+        _check(self.lib.dgc_set_density(self._h, float(density)), "dgc_set_density")
+
+    def dgc_set_warmup_schedule(self, densities: Sequence[float]) -> None:
+        arr = (C.c_double * len(densities))(*[float(d) for d in densities])
+        _check(self.lib.dgc_set_warmup_schedule(self._h, arr, len(densities)), "dgc_set_warmup_schedule")
+
+    def dgc_set_iteration_density(self, iteration: int) -> None:
+        _check(self.lib.dgc_set_iteration_density(self._h, int(iteration)), "dgc_set_iteration_density")
+
+    def dgc_query_plan(self, j: int):
+        k, s, r, d = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
+        _check(self.lib.dgc_query_plan(self._h, int(j), C.byref(k), C.byref(s), C.byref(r), C.byref(d)),
+               "dgc_query_plan")
+        return k.value, s.value, r.value, d.value
+
+    def dgc_workspace_bytes(self) -> int:
+        b = C.c_size_t()
+        _check(self.lib.dgc_workspace_bytes(self._h, C.byref(b)), "dgc_workspace_bytes")
+        return int(b.value)
+
+    def dgc_recommended_payload_layout(self, density: float) -> List[int]:
+        arr = (C.c_int64 * (self.num_tensors + 1))()
+        _check(self.lib.dgc_recommended_payload_layout(self._h, float(density), arr),
+               "dgc_recommended_payload_layout")
+        return list(arr)
+
+    # -- device memory (torch is the allocator) -----------------------------------
+    def set_layout(self, out_offsets: Sequence[int]) -> None:
+        self._layout = [int(x) for x in out_offsets]
+        self._layout_c = _i64_array(self._layout)
+
+    def ensure_workspace(self, device="cuda"):
+        import torch
+        if self.workspace is None:
+            nbytes = self.dgc_workspace_bytes()
+            self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+            base = self.workspace.data_ptr()
+            self._ws_ptr = (base + 255) // 256 * 256
+            self._ws_bytes = nbytes
+        return self.workspace
+
+    def alloc_payload(self, device="cuda"):
+        """(out_idx, out_val, out_counts, out_thr) sized for the current layout."""
+        import torch
+        total = max(1, self._layout[-1])
+        return (torch.empty(total, dtype=torch.int32, device=device),
+                torch.empty(total, dtype=torch.float32, device=device),
+                torch.zeros(self.num_tensors, dtype=torch.int32, device=device),
+                torch.empty(self.num_tensors, dtype=torch.float32, device=device))
+
+    # -- the hot path --------------------------------------------------------------
+    def dgc_compress(self, g, u, v, out_idx, out_val, out_counts, out_thr, iteration: int) -> None:
+        self.ensure_workspace(g.device)
+        _check(self.lib.dgc_compress(self._h, _ptr(g), _ptr(u), _ptr(v), _ptr(out_idx), _ptr(out_val),
+                                     self._layout_c, _ptr(out_counts), _ptr(out_thr), int(iteration),
+                                     self._ws_ptr, self._ws_bytes, _stream()), "dgc_compress")
+
+    def dgc_get_diagnostics(self) -> DgcDiagnostics:
+        d = DgcDiagnostics()
+        _check(self.lib.dgc_get_diagnostics(self._h, self._ws_ptr, C.byref(d), _stream()),
+               "dgc_get_diagnostics")
+        return d
+
+    def dgc_decompress_accumulate(self, dense, idx_list, val_list, counts: Sequence[int],
+                                  diag_flags=None) -> None:
+        n = len(idx_list)
+        _check(self.lib.dgc_decompress_accumulate(self._h, _ptr(dense), int(dense.numel()), n,
+                                                  _ptr_array(idx_list), _ptr_array(val_list),
+                                                  _i64_array(counts), _ptr(diag_flags), _stream()),
+               "dgc_decompress_accumulate")
+
+    def dgc_decompress_accumulate_regions(self, dense, idx_list, val_list, count_list) -> None:
+        self.ensure_workspace(dense.device)
+        _check(self.lib.dgc_decompress_accumulate_regions(
+            self._h, _ptr(dense), len(idx_list), _ptr_array(idx_list), _ptr_array(val_list),
+            _ptr_array(count_list), self._layout_c, self._ws_ptr, self._ws_bytes, _stream()),
+            "dgc_decompress_accumulate_regions")
+
+    def dgc_dense_clear_regions(self, dense, idx_list, count_list) -> None:
+        self.ensure_workspace(dense.device)
+        _check(self.lib.dgc_dense_clear_regions(
+            self._h, _ptr(dense), len(idx_list), _ptr_array(idx_list), _ptr_array(count_list),
+            self._layout_c, self._ws_ptr, self._ws_bytes, _stream()), "dgc_dense_clear_regions")
+
+
+def gather_payload(layout: Sequence[int], out_idx, out_val, out_counts):
+    """Host copy of a region-layout payload as per-tensor (indices, values) sorted by index.
+    Test/report helper: it waits for the device."""
+    idx = out_idx.cpu().numpy()
+    val = out_val.cpu().numpy()
+    cnt = out_counts.cpu().numpy()
+    per_idx, per_val = [], []
+    for j in range(len(layout) - 1):
+        lo = layout[j]
+        c = min(int(cnt[j]), layout[j + 1] - lo)
+        i = idx[lo:lo + c]
+        order = np.argsort(i, kind="stable")
+        per_idx.append(i[order].copy())
+        per_val.append(val[lo:lo + c][order].copy())
+    return per_idx, per_val, cnt

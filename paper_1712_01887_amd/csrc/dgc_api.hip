@@ -1,0 +1,494 @@
+// Host side of libdgc: argument checks, the host arithmetic of the method
+// (k_j, sample plan, warm-up table), workspace management and launch order.
+// Every step of the path itself runs in the kernels of dgc_kernels.hip.
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "dgc_internal.h"
+
+using namespace dgc;
+
+struct dgc_handle {
+  dgc_config cfg;
+  int32_t num_tensors = 0;
+  int64_t n = 0;
+  std::vector<int64_t> offsets;      // T + 1
+  std::vector<double> warmup;        // densities
+  // plan under cfg.density
+  std::vector<TensorPlan> plans;     // T
+  std::vector<int64_t> k;            // T
+  std::vector<int64_t> draws;        // T
+  std::vector<int32_t> tile_first;   // ceil(n / kWaveTile)
+  WorkspaceLayout lay{};
+  // what the bound workspace currently holds
+  void* ws = nullptr;
+  bool ws_static_valid = false;      // offsets + tile table
+  bool ws_plan_valid = false;
+  bool ws_layout_valid = false;
+  std::vector<int64_t> ws_out_offsets;
+};
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+bool valid_density(double d) { return d > 0.0 && d <= 1.0; }
+
+// paper: Section 4.1 lists the warm-up sparsities 75 %, 93.75 %, 98.4375 %, 99.6 %, 99.9 %.
+const double kDefaultWarmup[5] = {0.25, 0.0625, 0.015625, 0.004, 0.001};
+
+int64_t topk_count(double density, int64_t n) {
+  int64_t k = (int64_t)std::ceil(density * (double)n);
+  if (k < 1) k = 1;
+  if (k > n) k = n;
+  return k;
+}
+
+// Host arithmetic of the sampled threshold (paper: Section 5).  The wanted
+// sample size is ratio * n clamped to [sample_min, sample_max]; a tensor no
+// larger than that is used whole.  Otherwise ceil(s / B) aligned blocks of B
+// consecutive elements are drawn and the threshold is the magnitude of
+// descending rank ceil(d * draws * B) in the sample.
+void build_plan(dgc_handle* h) {
+  const dgc_config& c = h->cfg;
+  const int64_t B = c.sample_block;
+  for (int32_t j = 0; j < h->num_tensors; ++j) {
+    const int64_t n = h->offsets[j + 1] - h->offsets[j];
+    TensorPlan& p = h->plans[j];
+    p.offset = h->offsets[j];
+    p.n = n;
+    const int64_t k = topk_count(c.density, n);
+    h->k[j] = k;
+    int64_t want = (int64_t)std::ceil(c.sample_ratio * (double)n);
+    if (want > c.sample_max) want = c.sample_max;
+    if (want < c.sample_min) want = c.sample_min;
+    const int64_t s = want < n ? want : n;
+    if ((c.flags & DGC_FLAG_EXACT_SELECT) || s >= n || n / B < 1) {
+      p.exact = 1;
+      p.count = (int32_t)n;
+      p.rank = (int32_t)k;
+      p.nblocks = 0;
+      h->draws[j] = 0;
+    } else {
+      const int64_t draws = (s + B - 1) / B;
+      const int64_t count = draws * B;
+      int64_t rank = (int64_t)std::ceil(c.density * (double)count);
+      if (rank < 1) rank = 1;
+      p.exact = 0;
+      p.count = (int32_t)count;
+      p.rank = (int32_t)rank;
+      p.nblocks = (uint32_t)(n / B);
+      h->draws[j] = draws;
+    }
+  }
+  h->ws_plan_valid = false;
+}
+
+void build_layout(dgc_handle* h) {
+  const size_t T = (size_t)h->num_tensors;
+  const size_t tiles = (size_t)((h->n + kWaveTile - 1) / kWaveTile);
+  WorkspaceLayout& l = h->lay;
+  size_t off = 0;
+  l.state = off;        off = align_up(off + sizeof(DeviceState));
+  l.partials = off;     off = align_up(off + sizeof(double) * kNormMaxBlocks);
+  l.offsets = off;      off = align_up(off + sizeof(int64_t) * (T + 1));
+  l.out_offsets = off;  off = align_up(off + sizeof(int64_t) * (T + 1));
+  l.plans = off;        off = align_up(off + sizeof(TensorPlan) * T);
+  l.thr = off;          off = align_up(off + sizeof(float) * T);
+  l.tile_first = off;   off = align_up(off + sizeof(int32_t) * tiles);
+  l.total = off;
+}
+
+template <typename T>
+T* at(void* ws, size_t off) {
+  return reinterpret_cast<T*>(static_cast<char*>(ws) + off);
+}
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+dgc_status check_layout(const dgc_handle* h, const int64_t* oo) {
+  if (!oo || oo[0] != 0) return DGC_ERR_INVALID_ARG;
+  for (int32_t j = 0; j < h->num_tensors; ++j)
+    if (oo[j + 1] < oo[j]) return DGC_ERR_INVALID_ARG;
+  if (oo[h->num_tensors] >= (int64_t)1 << 31) return DGC_ERR_INVALID_ARG;
+  return DGC_OK;
+}
+
+// Make the workspace hold the static tables, the current plan and the payload
+// layout.  Copies are stream-ordered; the sources are host vectors that stay
+// alive in the handle (the runtime stages pageable memory before returning).
+dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_t* out_offsets,
+                          bool need_plan, hipStream_t stream) {
+  if (!ws) return DGC_ERR_INVALID_ARG;
+  if (!aligned(ws, kAlign)) return DGC_ERR_ALIGNMENT;
+  if (ws_bytes < h->lay.total) return DGC_ERR_CAPACITY;
+  const size_t T = (size_t)h->num_tensors;
+  if (ws != h->ws) {
+    h->ws = ws;
+    h->ws_static_valid = h->ws_plan_valid = h->ws_layout_valid = false;
+  }
+  if (!h->ws_static_valid) {
+    if (hipMemsetAsync(at<char>(ws, h->lay.state), 0, sizeof(DeviceState), stream) != hipSuccess)
+      return DGC_ERR_HIP;
+    if (hipMemcpyAsync(at<char>(ws, h->lay.offsets), h->offsets.data(), sizeof(int64_t) * (T + 1),
+                       hipMemcpyHostToDevice, stream) != hipSuccess)
+      return DGC_ERR_HIP;
+    if (hipMemcpyAsync(at<char>(ws, h->lay.tile_first), h->tile_first.data(),
+                       sizeof(int32_t) * h->tile_first.size(), hipMemcpyHostToDevice,
+                       stream) != hipSuccess)
+      return DGC_ERR_HIP;
+    h->ws_static_valid = true;
+  }
+  if (need_plan && !h->ws_plan_valid) {
+    if (hipMemcpyAsync(at<char>(ws, h->lay.plans), h->plans.data(), sizeof(TensorPlan) * T,
+                       hipMemcpyHostToDevice, stream) != hipSuccess)
+      return DGC_ERR_HIP;
+    h->ws_plan_valid = true;
+  }
+  if (out_offsets) {
+    const bool same = h->ws_layout_valid &&
+                      std::memcmp(h->ws_out_offsets.data(), out_offsets, sizeof(int64_t) * (T + 1)) == 0;
+    if (!same) {
+      h->ws_out_offsets.assign(out_offsets, out_offsets + T + 1);
+      if (hipMemcpyAsync(at<char>(ws, h->lay.out_offsets), h->ws_out_offsets.data(),
+                         sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, stream) != hipSuccess)
+        return DGC_ERR_HIP;
+      h->ws_layout_valid = true;
+    }
+  }
+  return DGC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t dgc_version(void) { return 1000; }
+
+const char* dgc_status_string(dgc_status s) {
+  switch (s) {
+    case DGC_OK: return "ok";
+    case DGC_ERR_INVALID_ARG: return "invalid argument";
+    case DGC_ERR_ALIGNMENT: return "buffer not aligned";
+    case DGC_ERR_CAPACITY: return "capacity exceeded";
+    case DGC_ERR_HIP: return "HIP runtime error";
+    case DGC_ERR_STATE: return "invalid state";
+    default: return "unknown status";
+  }
+}
+
+dgc_status dgc_config_default(dgc_config* cfg) {
+  if (!cfg) return DGC_ERR_INVALID_ARG;
+  std::memset(cfg, 0, sizeof(*cfg));
+  cfg->momentum = 0.9f;
+  cfg->clip_threshold = 0.0f;
+  cfg->num_workers = 1;
+  cfg->flags = 0;
+  cfg->density = 0.001;
+  cfg->sample_ratio = 0.01;
+  cfg->sample_min = 4096;
+  cfg->sample_max = 32768;
+  cfg->sample_block = 16;
+  cfg->scale_override = std::nanf("");
+  cfg->seed = 0;
+  return DGC_OK;
+}
+
+dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tensors,
+                      const int64_t* offsets_host) {
+  if (!out) return DGC_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (!cfg || !offsets_host || num_tensors < 1) return DGC_ERR_INVALID_ARG;
+  if (!valid_density(cfg->density) || cfg->num_workers < 1) return DGC_ERR_INVALID_ARG;
+  if (!(cfg->momentum >= 0.0f) || !(cfg->momentum <= 1.0f)) return DGC_ERR_INVALID_ARG;
+  if (!(cfg->sample_ratio > 0.0) || !(cfg->sample_ratio <= 1.0)) return DGC_ERR_INVALID_ARG;
+  const int32_t B = cfg->sample_block;
+  if (B < 1 || B > 64 || (B & (B - 1)) != 0) return DGC_ERR_INVALID_ARG;
+  if (cfg->sample_min < B || cfg->sample_max < cfg->sample_min) return DGC_ERR_INVALID_ARG;
+  if (cfg->clip_threshold != cfg->clip_threshold) return DGC_ERR_INVALID_ARG;
+  if (offsets_host[0] != 0) return DGC_ERR_INVALID_ARG;
+  for (int32_t j = 0; j < num_tensors; ++j)
+    if (offsets_host[j + 1] <= offsets_host[j]) return DGC_ERR_INVALID_ARG;
+  if (offsets_host[num_tensors] > ((int64_t)1 << 31) - 65536) return DGC_ERR_CAPACITY;
+
+  dgc_handle* h = new (std::nothrow) dgc_handle();
+  if (!h) return DGC_ERR_CAPACITY;
+  try {
+    h->cfg = *cfg;
+    h->num_tensors = num_tensors;
+    h->offsets.assign(offsets_host, offsets_host + num_tensors + 1);
+    h->n = offsets_host[num_tensors];
+    h->warmup.assign(kDefaultWarmup, kDefaultWarmup + 5);
+    h->plans.resize(num_tensors);
+    h->k.resize(num_tensors);
+    h->draws.resize(num_tensors);
+    const int64_t tiles = (h->n + kWaveTile - 1) / kWaveTile;
+    h->tile_first.resize((size_t)tiles);
+    int32_t j = 0;
+    for (int64_t t = 0; t < tiles; ++t) {
+      const int64_t first = t * kWaveTile;
+      while (h->offsets[j + 1] <= first) ++j;
+      h->tile_first[(size_t)t] = j;
+    }
+    h->ws_out_offsets.resize(num_tensors + 1);
+  } catch (...) {
+    delete h;
+    return DGC_ERR_CAPACITY;
+  }
+  build_plan(h);
+  build_layout(h);
+  *out = h;
+  return DGC_OK;
+}
+
+dgc_status dgc_destroy(dgc_handle* h) {
+  delete h;
+  return DGC_OK;
+}
+
+dgc_status dgc_set_density(dgc_handle* h, double density) {
+  if (!h || !valid_density(density)) return DGC_ERR_INVALID_ARG;
+  if (density != h->cfg.density) {
+    h->cfg.density = density;
+    build_plan(h);
+  }
+  return DGC_OK;
+}
+
+dgc_status dgc_set_warmup_schedule(dgc_handle* h, const double* densities_host, int32_t len) {
+  if (!h || !densities_host || len < 1) return DGC_ERR_INVALID_ARG;
+  for (int32_t i = 0; i < len; ++i)
+    if (!valid_density(densities_host[i])) return DGC_ERR_INVALID_ARG;
+  h->warmup.assign(densities_host, densities_host + len);
+  return DGC_OK;
+}
+
+dgc_status dgc_set_iteration_density(dgc_handle* h, int64_t iteration) {
+  if (!h || iteration < 0) return DGC_ERR_INVALID_ARG;
+  const size_t last = h->warmup.size() - 1;
+  const size_t i = (uint64_t)iteration < last ? (size_t)iteration : last;
+  return dgc_set_density(h, h->warmup[i]);
+}
+
+dgc_status dgc_query_plan(const dgc_handle* h, int32_t j, int64_t* k, int64_t* sample_count,
+                          int64_t* rank, int64_t* draws) {
+  if (!h || j < 0 || j >= h->num_tensors) return DGC_ERR_INVALID_ARG;
+  if (k) *k = h->k[j];
+  if (sample_count) *sample_count = h->plans[j].count;
+  if (rank) *rank = h->plans[j].rank;
+  if (draws) *draws = h->draws[j];
+  return DGC_OK;
+}
+
+dgc_status dgc_workspace_bytes(const dgc_handle* h, size_t* bytes) {
+  if (!h || !bytes) return DGC_ERR_INVALID_ARG;
+  *bytes = h->lay.total;
+  return DGC_OK;
+}
+
+dgc_status dgc_recommended_payload_layout(const dgc_handle* h, double density,
+                                          int64_t* out_offsets_host) {
+  if (!h || !out_offsets_host || !valid_density(density)) return DGC_ERR_INVALID_ARG;
+  int64_t off = 0;
+  for (int32_t j = 0; j < h->num_tensors; ++j) {
+    out_offsets_host[j] = off;
+    const int64_t n = h->offsets[j + 1] - h->offsets[j];
+    const int64_t k = topk_count(density, n);
+    int64_t cap = 4 * k > k + 256 ? 4 * k : k + 256;
+    if (cap > n) cap = n;
+    off += cap;
+  }
+  out_offsets_host[h->num_tensors] = off;
+  if (off >= (int64_t)1 << 31) return DGC_ERR_CAPACITY;
+  return DGC_OK;
+}
+
+dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32_t* out_idx,
+                        float* out_val, const int64_t* out_offsets_host, int32_t* out_counts,
+                        float* out_thr, uint64_t iteration, void* workspace,
+                        size_t workspace_bytes, void* stream_) {
+  if (!h || !g || !u || !v || !out_idx || !out_val || !out_counts) return DGC_ERR_INVALID_ARG;
+  if (!aligned(g, 16) || !aligned(u, 16) || !aligned(v, 16)) return DGC_ERR_ALIGNMENT;
+  if (!aligned(out_idx, 4) || !aligned(out_val, 4) || !aligned(out_counts, 4)) return DGC_ERR_ALIGNMENT;
+  dgc_status st = check_layout(h, out_offsets_host);
+  if (st != DGC_OK) return st;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  st = sync_workspace(h, workspace, workspace_bytes, out_offsets_host, true, stream);
+  if (st != DGC_OK) return st;
+
+  const dgc_config& c = h->cfg;
+  const bool clip = c.clip_threshold > 0.0f;
+  const bool have_override = c.scale_override == c.scale_override;
+  DeviceState* state = at<DeviceState>(workspace, h->lay.state);
+
+  // paper: Appendix C equation 12 -- the local threshold is N^-1/2 times the global one.
+  if (clip) {
+    const double thr_local = (double)c.clip_threshold / std::sqrt((double)c.num_workers);
+    if (launch_norm(g, h->n, state, at<double>(workspace, h->lay.partials), thr_local,
+                    c.scale_override, stream) != hipSuccess)
+      return DGC_ERR_HIP;
+  }
+  const float scale_const = have_override ? c.scale_override : 1.0f;
+
+  SelectArgs sa{};
+  sa.g = g;
+  sa.u = u;
+  sa.v = v;
+  sa.plans = at<TensorPlan>(workspace, h->lay.plans);
+  sa.state = state;
+  sa.thr = at<float>(workspace, h->lay.thr);
+  sa.out_thr = out_thr;
+  sa.out_counts = out_counts;
+  sa.momentum = c.momentum;
+  sa.scale_const = scale_const;
+  sa.scale_from_state = clip ? 1 : 0;
+  sa.nesterov = (c.flags & DGC_FLAG_NESTEROV) ? 1 : 0;
+  int shift = 0;
+  while ((1 << shift) < c.sample_block) ++shift;
+  sa.block_shift = shift;
+  sa.seed_lo = (uint32_t)(c.seed & 0xFFFFFFFFu);
+  sa.seed_hi = (uint32_t)(c.seed >> 32);
+  sa.iter_lo = (uint32_t)(iteration & 0xFFFFFFFFu);
+  sa.iter_hi = (uint32_t)(iteration >> 32);
+  if (launch_select(sa, h->num_tensors, stream) != hipSuccess) return DGC_ERR_HIP;
+
+  StreamArgs ta{};
+  ta.g = g;
+  ta.u = u;
+  ta.v = v;
+  ta.out_idx = out_idx;
+  ta.out_val = out_val;
+  ta.offsets = at<int64_t>(workspace, h->lay.offsets);
+  ta.out_offsets = at<int64_t>(workspace, h->lay.out_offsets);
+  ta.thr = sa.thr;
+  ta.out_counts = out_counts;
+  ta.tile_first = at<int32_t>(workspace, h->lay.tile_first);
+  ta.state = state;
+  ta.n = h->n;
+  ta.num_tensors = h->num_tensors;
+  ta.momentum = c.momentum;
+  ta.scale_const = scale_const;
+  ta.scale_from_state = sa.scale_from_state;
+  ta.nesterov = sa.nesterov;
+  ta.factor_masking = (c.flags & DGC_FLAG_NO_FACTOR_MASKING) ? 0 : 1;
+  if (launch_stream(ta, stream) != hipSuccess) return DGC_ERR_HIP;
+  return DGC_OK;
+}
+
+dgc_status dgc_get_diagnostics(dgc_handle* h, const void* workspace, dgc_diagnostics* out_host,
+                               void* stream_) {
+  if (!h || !workspace || !out_host) return DGC_ERR_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  DeviceState s;
+  if (hipMemcpyAsync(&s, static_cast<const char*>(workspace) + h->lay.state, sizeof(s),
+                     hipMemcpyDeviceToHost, stream) != hipSuccess)
+    return DGC_ERR_HIP;
+  if (hipStreamSynchronize(stream) != hipSuccess) return DGC_ERR_HIP;
+  out_host->norm = s.norm;
+  out_host->scale = s.scale;
+  out_host->flags = s.flags;
+  return DGC_OK;
+}
+
+dgc_status dgc_decompress_accumulate(dgc_handle* h, float* dense, int64_t n, int32_t num_payloads,
+                                     const int32_t* const* idx_ptrs_host,
+                                     const float* const* val_ptrs_host,
+                                     const int64_t* pair_counts_host, uint32_t* diag_flags_dev,
+                                     void* stream_) {
+  if (!h || !dense || !idx_ptrs_host || !val_ptrs_host || !pair_counts_host) return DGC_ERR_INVALID_ARG;
+  if (n < 1 || n >= (int64_t)1 << 31) return DGC_ERR_INVALID_ARG;
+  if (num_payloads < 1) return DGC_ERR_INVALID_ARG;
+  if (num_payloads > kMaxPayloads) return DGC_ERR_CAPACITY;
+  if (!aligned(dense, 4)) return DGC_ERR_ALIGNMENT;
+  PairPayloads p{};
+  int64_t max_count = 0;
+  for (int32_t w = 0; w < num_payloads; ++w) {
+    const int64_t c = pair_counts_host[w];
+    if (c < 0 || c >= (int64_t)1 << 31) return DGC_ERR_INVALID_ARG;
+    if (c > 0 && (!idx_ptrs_host[w] || !val_ptrs_host[w])) return DGC_ERR_INVALID_ARG;
+    p.idx[w] = idx_ptrs_host[w];
+    p.val[w] = val_ptrs_host[w];
+    p.count[w] = c;
+    if (c > max_count) max_count = c;
+  }
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  if (h->cfg.flags & DGC_FLAG_DETERMINISTIC_ACCUMULATE) {
+    // one launch per worker, in order: within a payload every index is distinct
+    for (int32_t w = 0; w < num_payloads; ++w)
+      if (launch_scatter_pairs(dense, n, p, w, 1, p.count[w], kScatterPlainAdd, diag_flags_dev,
+                               stream) != hipSuccess)
+        return DGC_ERR_HIP;
+  } else {
+    if (launch_scatter_pairs(dense, n, p, 0, num_payloads, max_count, kScatterAtomicAdd,
+                             diag_flags_dev, stream) != hipSuccess)
+      return DGC_ERR_HIP;
+  }
+  return DGC_OK;
+}
+
+static dgc_status scatter_regions(dgc_handle* h, float* dense, int32_t num_payloads,
+                                  const int32_t* const* idx_ptrs_host,
+                                  const float* const* val_ptrs_host,
+                                  const int32_t* const* count_ptrs_host,
+                                  const int64_t* out_offsets_host, void* workspace,
+                                  size_t workspace_bytes, void* stream_, bool clear) {
+  if (!h || !dense || !idx_ptrs_host || !count_ptrs_host) return DGC_ERR_INVALID_ARG;
+  if (!clear && !val_ptrs_host) return DGC_ERR_INVALID_ARG;
+  if (num_payloads < 1) return DGC_ERR_INVALID_ARG;
+  if (num_payloads > kMaxPayloads) return DGC_ERR_CAPACITY;
+  dgc_status st = check_layout(h, out_offsets_host);
+  if (st != DGC_OK) return st;
+  RegionPayloads p{};
+  for (int32_t w = 0; w < num_payloads; ++w) {
+    if (!idx_ptrs_host[w] || !count_ptrs_host[w] || (!clear && !val_ptrs_host[w]))
+      return DGC_ERR_INVALID_ARG;
+    p.idx[w] = idx_ptrs_host[w];
+    p.val[w] = clear ? nullptr : val_ptrs_host[w];
+    p.counts[w] = count_ptrs_host[w];
+  }
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  st = sync_workspace(h, workspace, workspace_bytes, out_offsets_host, false, stream);
+  if (st != DGC_OK) return st;
+  const int64_t* oo = at<int64_t>(workspace, h->lay.out_offsets);
+  const int64_t total = out_offsets_host[h->num_tensors];
+  if (clear) {
+    if (launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, total,
+                               kScatterClear, nullptr, stream) != hipSuccess)
+      return DGC_ERR_HIP;
+  } else if (h->cfg.flags & DGC_FLAG_DETERMINISTIC_ACCUMULATE) {
+    for (int32_t w = 0; w < num_payloads; ++w)
+      if (launch_scatter_regions(dense, h->n, p, w, 1, oo, h->num_tensors, total, kScatterPlainAdd,
+                                 nullptr, stream) != hipSuccess)
+        return DGC_ERR_HIP;
+  } else {
+    if (launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, total,
+                               kScatterAtomicAdd, nullptr, stream) != hipSuccess)
+      return DGC_ERR_HIP;
+  }
+  return DGC_OK;
+}
+
+dgc_status dgc_decompress_accumulate_regions(dgc_handle* h, float* dense, int32_t num_payloads,
+                                             const int32_t* const* idx_ptrs_host,
+                                             const float* const* val_ptrs_host,
+                                             const int32_t* const* count_ptrs_host,
+                                             const int64_t* out_offsets_host, void* workspace,
+                                             size_t workspace_bytes, void* stream) {
+  return scatter_regions(h, dense, num_payloads, idx_ptrs_host, val_ptrs_host, count_ptrs_host,
+                         out_offsets_host, workspace, workspace_bytes, stream, false);
+}
+
+dgc_status dgc_dense_clear_regions(dgc_handle* h, float* dense, int32_t num_payloads,
+                                   const int32_t* const* idx_ptrs_host,
+                                   const int32_t* const* count_ptrs_host,
+                                   const int64_t* out_offsets_host, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+  return scatter_regions(h, dense, num_payloads, idx_ptrs_host, nullptr, count_ptrs_host,
+                         out_offsets_host, workspace, workspace_bytes, stream, true);
+}
+
+}  // extern "C"

@@ -1,0 +1,125 @@
+// Shared between the host side of libdgc and its kernels: workspace layout,
+// kernel argument blocks and launch geometry.  Nothing here is visible through
+// the C ABI.
+#ifndef DGC_INTERNAL_H_
+#define DGC_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dgc.h"
+
+namespace dgc {
+
+// ---- launch geometry -------------------------------------------------------
+// Streaming pass: one wavefront owns a contiguous run of kWaveTile elements and
+// reads it as kStreamUnroll rounds of one float4 per lane (64 lanes x 16 B =
+// 1 KiB per round, fully coalesced).
+constexpr int kStreamUnroll = 4;
+constexpr int kWaveTile = 64 * 4 * kStreamUnroll;  // 1024 elements
+constexpr int kStreamThreads = 256;                 // 4 wavefronts per workgroup
+constexpr int kStreamWaves = kStreamThreads / 64;
+constexpr int kTileShift = 10;                      // first-tensor table granularity: 1024 elements
+static_assert((1 << kTileShift) == kWaveTile, "tile table granularity must equal the wave tile");
+
+// Threshold selection: one workgroup per tensor.
+constexpr int kSelectThreads = 1024;
+constexpr int kSelectKeyCap = 32768;  // candidate keys kept in LDS (128 KiB of the 160 KiB)
+constexpr int kSelectBins = 2048;     // 11-bit digits
+
+// Clipping norm: a fixed number of partial sums keeps the result reproducible.
+constexpr int kNormThreads = 256;
+constexpr int kNormMaxBlocks = 2048;
+
+constexpr int kMaxPayloads = 64;
+
+// ---- device-resident state (start of the workspace) ------------------------
+struct DeviceState {
+  double norm;           // L2 norm of g (clipping on)
+  float scale;           // factor applied to g
+  uint32_t flags;        // DGC_DIAG_*
+  uint32_t norm_ticket;  // workgroups of the norm kernel that have finished
+  uint32_t pad[3];
+};
+
+// Per-tensor selection plan (host arithmetic, uploaded when the density changes).
+struct TensorPlan {
+  int64_t offset;   // first element of the tensor in the flat buffers
+  int64_t n;        // elements
+  int32_t count;    // candidates: n (whole tensor) or draws * block
+  int32_t rank;     // 0-based descending rank that becomes the threshold
+  uint32_t nblocks; // aligned sample blocks in the tensor (sampled mode)
+  int32_t exact;    // 1: candidates are elements 0..n-1
+};
+
+struct WorkspaceLayout {
+  size_t state, partials, offsets, out_offsets, plans, thr, tile_first, total;
+};
+
+struct SelectArgs {
+  const float* g;
+  const float* u;
+  const float* v;
+  const TensorPlan* plans;
+  DeviceState* state;
+  float* thr;
+  float* out_thr;       // may be null
+  int32_t* out_counts;  // zeroed here for the streaming pass
+  float momentum;
+  float scale_const;
+  int32_t scale_from_state;  // 1: the norm kernel ran and left the scale in `state`
+  int32_t nesterov;
+  int32_t block_shift;  // log2(sample_block)
+  uint32_t seed_lo, seed_hi, iter_lo, iter_hi;
+};
+
+struct StreamArgs {
+  const float* g;
+  float* u;
+  float* v;
+  int32_t* out_idx;
+  float* out_val;
+  const int64_t* offsets;      // device, T + 1
+  const int64_t* out_offsets;  // device, T + 1
+  const float* thr;            // device, T
+  int32_t* out_counts;         // device, T
+  const int32_t* tile_first;   // device, ceil(n / 1024)
+  DeviceState* state;
+  int64_t n;
+  int32_t num_tensors;
+  float momentum;
+  float scale_const;
+  int32_t scale_from_state;
+  int32_t nesterov;
+  int32_t factor_masking;
+};
+
+struct PairPayloads {
+  const int32_t* idx[kMaxPayloads];
+  const float* val[kMaxPayloads];
+  int64_t count[kMaxPayloads];
+};
+
+struct RegionPayloads {
+  const int32_t* idx[kMaxPayloads];
+  const float* val[kMaxPayloads];
+  const int32_t* counts[kMaxPayloads];
+};
+
+enum ScatterMode : int32_t { kScatterAtomicAdd = 0, kScatterPlainAdd = 1, kScatterClear = 2 };
+
+// ---- launchers (dgc_kernels.hip) ---------------------------------------------
+hipError_t launch_norm(const float* g, int64_t n, DeviceState* state, double* partials,
+                       double thr_local, float scale_override, hipStream_t stream);
+hipError_t launch_select(const SelectArgs& a, int32_t num_tensors, hipStream_t stream);
+hipError_t launch_stream(const StreamArgs& a, hipStream_t stream);
+hipError_t launch_scatter_pairs(float* dense, int64_t n, const PairPayloads& p, int32_t first,
+                                int32_t num, int64_t max_count, ScatterMode mode,
+                                uint32_t* diag_flags, hipStream_t stream);
+hipError_t launch_scatter_regions(float* dense, int64_t n, const RegionPayloads& p, int32_t first,
+                                  int32_t num, const int64_t* out_offsets_dev, int32_t num_tensors,
+                                  int64_t total_slots, ScatterMode mode, uint32_t* diag_flags,
+                                  hipStream_t stream);
+
+}  // namespace dgc
+#endif  // DGC_INTERNAL_H_

@@ -1,0 +1,499 @@
+// HIP kernels of the DGC hot path for gfx950 (wave64, CDNA4).
+//
+// The path is memory-bound: one streaming pass reads g, u, v and writes u, v
+// (20 bytes per element); everything else touches a sample or the sparse
+// payload only.  No kernel here is a contraction, so no MFMA is used.
+//
+// Arithmetic contract (shared with nothing, stated for the reader): binary32,
+// one rounding per operation, in this order
+//     gs = g * scale;  t = m * u;  u' = t + gs;  v' = v + u'          (vanilla)
+//     gs = g * scale;  s = u + gs; u' = m * s;   w = v + u'; v' = w + gs  (Nesterov)
+// The file must be compiled with -ffp-contract=off so that no pair of these is
+// fused; the threshold pass and the streaming pass evaluate v' with the same
+// inline function, which makes the sampled threshold an exact member of the
+// values the streaming pass later compares against it.
+
+#include "dgc_internal.h"
+
+namespace dgc {
+namespace {
+
+// ---------------------------------------------------------------------------
+// Momentum correction (paper: equation 7; Algorithm 3 / Algorithm 4 update lines)
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void momentum_update(float g, float u, float v, float m, float scale,
+                                                bool nesterov, float& u1, float& v1) {
+  const float gs = g * scale;
+  if (!nesterov) {
+    const float t = m * u;
+    u1 = t + gs;
+    v1 = v + u1;
+  } else {
+    const float s = u + gs;
+    u1 = m * s;
+    const float w = v + u1;
+    v1 = w + gs;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Clipping norm (paper: Section 3.2 "Local Gradient Clipping"; Appendix C eq. 12)
+// ---------------------------------------------------------------------------
+// Every workgroup accumulates squares in binary64 over a grid-stride range and
+// stores one partial; the workgroup that finishes last adds the partials in
+// index order, so the result does not depend on scheduling.
+__global__ __launch_bounds__(kNormThreads) void norm_kernel(const float* __restrict__ g, int64_t n,
+                                                            DeviceState* state, double* partials,
+                                                            double thr_local, float scale_override) {
+  __shared__ double red[kNormThreads / 64];
+  __shared__ int is_last;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int64_t nvec = n >> 2;
+  const float4* __restrict__ g4 = reinterpret_cast<const float4*>(g);
+  double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+  const int64_t stride = (int64_t)gridDim.x * kNormThreads;
+  for (int64_t i = (int64_t)blockIdx.x * kNormThreads + tid; i < nvec; i += stride) {
+    const float4 x = g4[i];
+    a0 += (double)x.x * (double)x.x;
+    a1 += (double)x.y * (double)x.y;
+    a2 += (double)x.z * (double)x.z;
+    a3 += (double)x.w * (double)x.w;
+  }
+  if (blockIdx.x == 0 && tid < (int)(n & 3)) {
+    const double x = (double)g[(nvec << 2) + tid];
+    a0 += x * x;
+  }
+  double acc = (a0 + a1) + (a2 + a3);
+  for (int d = 32; d >= 1; d >>= 1) acc += __shfl_down(acc, d);
+  if (lane == 0) red[wave] = acc;
+  __syncthreads();
+  if (tid == 0) {
+    double s = 0.0;
+    for (int w = 0; w < kNormThreads / 64; ++w) s += red[w];
+    partials[blockIdx.x] = s;
+    __threadfence();
+    const uint32_t ticket = atomicAdd(&state->norm_ticket, 1u);
+    is_last = (ticket == gridDim.x - 1);
+  }
+  __syncthreads();
+  if (!is_last) return;
+  __threadfence();
+  double s = 0.0;
+  for (int i = tid; i < (int)gridDim.x; i += kNormThreads)
+    s += __hip_atomic_load(&partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (int d = 32; d >= 1; d >>= 1) s += __shfl_down(s, d);
+  __syncthreads();
+  if (lane == 0) red[wave] = s;
+  __syncthreads();
+  if (tid == 0) {
+    double total = 0.0;
+    for (int w = 0; w < kNormThreads / 64; ++w) total += red[w];
+    const double norm = sqrt(total);
+    float scale = 1.0f;
+    if (norm > thr_local) scale = (float)(thr_local / norm);
+    uint32_t flags = 0;
+    if (!(norm <= 1.79769313486231570e308)) flags |= DGC_DIAG_NONFINITE;  // NaN or infinity
+    if (scale_override == scale_override) scale = scale_override;
+    state->norm = norm;
+    state->scale = scale;
+    state->flags = flags;
+    state->norm_ticket = 0;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Sampled threshold (paper: Section 5 -- top-k on a sample estimates the
+// threshold of the whole tensor; Algorithm 3 "thr <- s% of |V[j]|")
+// ---------------------------------------------------------------------------
+// 32-bit xorshift-multiply finaliser; a bijection on 32-bit words.
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {
+  x ^= x >> 16;
+  x *= 0x7FEB352Du;
+  x ^= x >> 15;
+  x *= 0x846CA68Bu;
+  x ^= x >> 16;
+  return x;
+}
+
+struct Candidates {
+  const float* g;
+  const float* u;
+  const float* v;
+  int64_t offset;
+  uint32_t key;      // folded (seed, iteration, tensor)
+  uint32_t nblocks;
+  int32_t block_shift;
+  int32_t exact;
+  float m, scale;
+  bool nesterov;
+
+  // Position (relative to the tensor) of candidate p.
+  __device__ __forceinline__ int64_t position(int32_t p) const {
+    if (exact) return p;
+    const uint32_t draw = (uint32_t)p >> block_shift;
+    const uint32_t r = mix32(key ^ (draw * 0x9E3779B1u));
+    const uint32_t blk = __umulhi(r, nblocks);
+    return ((int64_t)blk << block_shift) + (p & ((1 << block_shift) - 1));
+  }
+  // Bit pattern of |v'| at candidate p: order-isomorphic to the magnitude.
+  __device__ __forceinline__ uint32_t key_at(int32_t p) const {
+    const int64_t e = offset + position(p);
+    float u1, v1;
+    momentum_update(g[e], u[e], v[e], m, scale, nesterov, u1, v1);
+    return __float_as_uint(v1) & 0x7FFFFFFFu;
+  }
+};
+
+// One workgroup per tensor.  Three histogram passes (11 + 11 + 9 bits, most
+// significant first) over the candidate keys find the key of a given
+// descending rank exactly.  Keys are computed once and kept in LDS when they
+// fit; otherwise every pass recomputes them from g, u, v.
+__global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
+  __shared__ uint32_t keys[kSelectKeyCap];
+  __shared__ uint32_t hist[kSelectBins];
+  __shared__ uint32_t wave_tot[kSelectThreads / 64];
+  __shared__ uint32_t sel_bin, sel_above;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int j = blockIdx.x;
+  const TensorPlan plan = a.plans[j];
+
+  if (tid == 0) a.out_counts[j] = 0;
+  if (tid == 0 && j == 0 && !a.scale_from_state) {  // no norm kernel ran: start a clean record
+    a.state->norm = __longlong_as_double(0x7FF8000000000000ll);
+    a.state->scale = a.scale_const;
+    a.state->flags = 0;
+  }
+  if (plan.rank >= plan.count) {  // the strict comparison then passes everything
+    if (tid == 0) {
+      a.thr[j] = -1.0f;
+      if (a.out_thr) a.out_thr[j] = -1.0f;
+    }
+    return;
+  }
+
+  Candidates c;
+  c.g = a.g;
+  c.u = a.u;
+  c.v = a.v;
+  c.offset = plan.offset;
+  c.nblocks = plan.nblocks;
+  c.block_shift = a.block_shift;
+  c.exact = plan.exact;
+  c.m = a.momentum;
+  c.scale = a.scale_from_state ? a.state->scale : a.scale_const;
+  c.nesterov = a.nesterov != 0;
+  {
+    uint32_t h = mix32(a.seed_lo ^ 0x9E3779B9u);
+    h = mix32(h ^ a.seed_hi);
+    h = mix32(h ^ a.iter_lo);
+    h = mix32(h ^ a.iter_hi);
+    c.key = mix32(h ^ (uint32_t)j);
+  }
+
+  const int32_t count = plan.count;
+  const bool cached = count <= kSelectKeyCap;
+  uint32_t prefix = 0;
+  uint32_t rank = (uint32_t)plan.rank;
+
+#pragma unroll 1
+  for (int pass = 0; pass < 3; ++pass) {
+    const int shift = pass == 0 ? 20 : (pass == 1 ? 9 : 0);
+    const int bits = pass == 2 ? 9 : 11;
+    const uint32_t digit_mask = (1u << bits) - 1u;
+    for (int i = tid; i < kSelectBins; i += kSelectThreads) hist[i] = 0;
+    __syncthreads();
+    if (pass == 0 || !cached) {
+      // four candidates per thread in flight: the gathers are latency-bound
+      for (int32_t p0 = tid; p0 < count; p0 += 4 * kSelectThreads) {
+        uint32_t k[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int32_t p = p0 + q * kSelectThreads;
+          k[q] = p < count ? c.key_at(p) : 0u;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int32_t p = p0 + q * kSelectThreads;
+          if (p < count) {
+            if (cached) keys[p] = k[q];
+            if (pass == 0 || (k[q] >> (shift + bits)) == prefix)
+              atomicAdd(&hist[(k[q] >> shift) & digit_mask], 1u);
+          }
+        }
+      }
+    } else {
+      for (int32_t p = tid; p < count; p += kSelectThreads) {
+        const uint32_t k = keys[p];
+        if ((k >> (shift + bits)) == prefix) atomicAdd(&hist[(k >> shift) & digit_mask], 1u);
+      }
+    }
+    __syncthreads();
+    // Suffix sums over the bins, two bins per thread, highest bins first in rank order.
+    const uint32_t h0 = hist[2 * tid];
+    const uint32_t h1 = hist[2 * tid + 1];
+    const uint32_t local = h0 + h1;
+    uint32_t incl = local;
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t t = __shfl_down(incl, d);
+      if (lane + d < 64) incl += t;
+    }
+    if (lane == 0) wave_tot[wave] = incl;
+    __syncthreads();
+    uint32_t above = incl - local;  // candidates in bins above this thread's pair
+    for (int w = wave + 1; w < kSelectThreads / 64; ++w) above += wave_tot[w];
+    if (above <= rank && rank < above + h1) {
+      sel_bin = 2 * tid + 1;
+      sel_above = above;
+    } else if (above + h1 <= rank && rank < above + local) {
+      sel_bin = 2 * tid;
+      sel_above = above + h1;
+    }
+    __syncthreads();
+    prefix = (prefix << bits) | sel_bin;
+    rank -= sel_above;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    const float thr = __uint_as_float(prefix);
+    a.thr[j] = thr;
+    if (a.out_thr) a.out_thr[j] = thr;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Fused update + mask + compaction + factor masking
+// (paper: Algorithm 3 from the U, V update to the two masking lines)
+// ---------------------------------------------------------------------------
+// A wavefront owns kWaveTile consecutive elements.  Kept elements of each
+// tensor that the tile touches are ranked inside the wavefront by a prefix sum
+// over lanes; lane 0 reserves the slots with one atomic on that tensor's count.
+__global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int64_t tile = (int64_t)blockIdx.x * kStreamWaves + wave;
+  const int64_t base = tile * kWaveTile;
+  if (base >= a.n) return;
+  const int64_t end = base + kWaveTile < a.n ? base + kWaveTile : a.n;
+  const bool full = base + kWaveTile <= a.n;
+  const float scale = a.scale_from_state ? a.state->scale : a.scale_const;
+  const float m = a.momentum;
+  const bool nesterov = a.nesterov != 0;
+
+  float u1[kStreamUnroll * 4], v1[kStreamUnroll * 4];
+  {
+    float gg[kStreamUnroll * 4], uu[kStreamUnroll * 4], vv[kStreamUnroll * 4];
+#pragma unroll
+    for (int it = 0; it < kStreamUnroll; ++it) {
+      const int64_t e = base + it * 256 + lane * 4;
+      if (full || e + 4 <= a.n) {
+        const float4 x = *reinterpret_cast<const float4*>(a.g + e);
+        const float4 y = *reinterpret_cast<const float4*>(a.u + e);
+        const float4 z = *reinterpret_cast<const float4*>(a.v + e);
+        gg[it * 4 + 0] = x.x; gg[it * 4 + 1] = x.y; gg[it * 4 + 2] = x.z; gg[it * 4 + 3] = x.w;
+        uu[it * 4 + 0] = y.x; uu[it * 4 + 1] = y.y; uu[it * 4 + 2] = y.z; uu[it * 4 + 3] = y.w;
+        vv[it * 4 + 0] = z.x; vv[it * 4 + 1] = z.y; vv[it * 4 + 2] = z.z; vv[it * 4 + 3] = z.w;
+      } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const bool in = e + c < a.n;
+          gg[it * 4 + c] = in ? a.g[e + c] : 0.0f;
+          uu[it * 4 + c] = in ? a.u[e + c] : 0.0f;
+          vv[it * 4 + c] = in ? a.v[e + c] : 0.0f;
+        }
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < kStreamUnroll * 4; ++q)
+      momentum_update(gg[q], uu[q], vv[q], m, scale, nesterov, u1[q], v1[q]);
+  }
+
+  // Tensors touched by this tile (usually one).
+  int32_t j = a.tile_first[base >> kTileShift];
+  while (a.offsets[j + 1] <= base) ++j;
+  uint32_t sent = 0;  // bit q: element q of this lane was written to the payload
+  bool overflow = false;
+  for (; j < a.num_tensors; ++j) {
+    const int64_t lo = a.offsets[j];
+    if (lo >= end) break;
+    const int64_t hi = a.offsets[j + 1];
+    const float thr = a.thr[j];
+    uint32_t cand = 0;
+#pragma unroll
+    for (int q = 0; q < kStreamUnroll * 4; ++q) {
+      const int64_t e = base + (q >> 2) * 256 + lane * 4 + (q & 3);
+      const bool in = e >= lo && e < hi;
+      if (in && fabsf(v1[q]) > thr) cand |= 1u << q;
+    }
+    if (__ballot(cand != 0) == 0ull) continue;
+    const int c = __popc(cand);
+    int incl = c;
+    for (int d = 1; d < 64; d <<= 1) {
+      const int t = __shfl_up(incl, d);
+      if (lane >= d) incl += t;
+    }
+    const int total = __shfl(incl, 63);
+    int slot0 = 0;
+    if (lane == 0) slot0 = atomicAdd(&a.out_counts[j], total);
+    slot0 = __shfl(slot0, 0);
+    const int64_t region = a.out_offsets[j];
+    const int64_t cap = a.out_offsets[j + 1] - region;
+    int64_t slot = (int64_t)slot0 + (incl - c);
+#pragma unroll
+    for (int q = 0; q < kStreamUnroll * 4; ++q) {
+      if (cand & (1u << q)) {
+        if (slot < cap) {
+          const int64_t e = base + (q >> 2) * 256 + lane * 4 + (q & 3);
+          a.out_idx[region + slot] = (int32_t)e;
+          a.out_val[region + slot] = v1[q];
+          sent |= 1u << q;
+        } else {
+          overflow = true;
+        }
+        ++slot;
+      }
+    }
+  }
+  if (overflow) atomicOr(&a.state->flags, (uint32_t)DGC_DIAG_OVERFLOW);
+
+  // Momentum factor masking: the same mask clears v and u (paper: Section 3.3).
+#pragma unroll
+  for (int q = 0; q < kStreamUnroll * 4; ++q) {
+    if (sent & (1u << q)) {
+      v1[q] = 0.0f;
+      if (a.factor_masking) u1[q] = 0.0f;
+    }
+  }
+#pragma unroll
+  for (int it = 0; it < kStreamUnroll; ++it) {
+    const int64_t e = base + it * 256 + lane * 4;
+    if (full || e + 4 <= a.n) {
+      *reinterpret_cast<float4*>(a.u + e) =
+          make_float4(u1[it * 4 + 0], u1[it * 4 + 1], u1[it * 4 + 2], u1[it * 4 + 3]);
+      *reinterpret_cast<float4*>(a.v + e) =
+          make_float4(v1[it * 4 + 0], v1[it * 4 + 1], v1[it * 4 + 2], v1[it * 4 + 3]);
+    } else {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        if (e + c < a.n) {
+          a.u[e + c] = u1[it * 4 + c];
+          a.v[e + c] = v1[it * 4 + c];
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Receive side (paper: the sum in Algorithm 3's all-reduce line)
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void scatter_one(float* dense, int64_t n, int32_t i, float x,
+                                            ScatterMode mode, uint32_t* diag_flags) {
+  if (i < 0 || (int64_t)i >= n) {
+    if (diag_flags) atomicOr(diag_flags, (uint32_t)DGC_DIAG_BAD_INDEX);
+    return;
+  }
+  if (mode == kScatterAtomicAdd) {
+    unsafeAtomicAdd(dense + i, x);  // hardware float add at the L2 / memory side
+  } else if (mode == kScatterPlainAdd) {
+    dense[i] = dense[i] + x;
+  } else {
+    dense[i] = 0.0f;
+  }
+}
+
+// grid = (chunks, payloads)
+__global__ __launch_bounds__(256) void scatter_pairs_kernel(float* dense, int64_t n, PairPayloads p,
+                                                            int32_t first, ScatterMode mode,
+                                                            uint32_t* diag_flags) {
+  const int w = first + blockIdx.y;
+  const int64_t count = p.count[w];
+  const int32_t* __restrict__ idx = p.idx[w];
+  const float* __restrict__ val = p.val[w];
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < count; q += stride)
+    scatter_one(dense, n, idx[q], mode == kScatterClear ? 0.0f : val[q], mode, diag_flags);
+}
+
+// Payloads in the per-tensor region layout written by the streaming pass: a
+// thread per slot, the tensor found by bisection over the region starts.
+__global__ __launch_bounds__(256) void scatter_regions_kernel(float* dense, int64_t n,
+                                                              RegionPayloads p, int32_t first,
+                                                              const int64_t* __restrict__ out_offsets,
+                                                              int32_t num_tensors, int64_t total_slots,
+                                                              ScatterMode mode, uint32_t* diag_flags) {
+  const int w = first + blockIdx.y;
+  const int32_t* __restrict__ idx = p.idx[w];
+  const float* __restrict__ val = p.val[w];
+  const int32_t* __restrict__ counts = p.counts[w];
+  const int64_t stride = (int64_t)gridDim.x * 256;
+  for (int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x; s < total_slots; s += stride) {
+    int32_t lo = 0, hi = num_tensors;  // last j with out_offsets[j] <= s
+    while (hi - lo > 1) {
+      const int32_t mid = (lo + hi) >> 1;
+      if (out_offsets[mid] <= s) lo = mid; else hi = mid;
+    }
+    const int64_t local = s - out_offsets[lo];
+    if (local < (int64_t)counts[lo])
+      scatter_one(dense, n, idx[s], mode == kScatterClear ? 0.0f : val[s], mode, diag_flags);
+  }
+}
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// Launchers
+// ---------------------------------------------------------------------------
+hipError_t launch_norm(const float* g, int64_t n, DeviceState* state, double* partials,
+                       double thr_local, float scale_override, hipStream_t stream) {
+  int64_t blocks = ceil_div(n >> 2, (int64_t)kNormThreads * 8);
+  if (blocks < 1) blocks = 1;
+  if (blocks > kNormMaxBlocks) blocks = kNormMaxBlocks;
+  hipLaunchKernelGGL(norm_kernel, dim3((unsigned)blocks), dim3(kNormThreads), 0, stream, g, n, state,
+                     partials, thr_local, scale_override);
+  return hipGetLastError();
+}
+
+hipError_t launch_select(const SelectArgs& a, int32_t num_tensors, hipStream_t stream) {
+  hipLaunchKernelGGL(select_kernel, dim3((unsigned)num_tensors), dim3(kSelectThreads), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_stream(const StreamArgs& a, hipStream_t stream) {
+  const int64_t tiles = ceil_div(a.n, kWaveTile);
+  const int64_t blocks = ceil_div(tiles, kStreamWaves);
+  hipLaunchKernelGGL(stream_kernel, dim3((unsigned)blocks), dim3(kStreamThreads), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_scatter_pairs(float* dense, int64_t n, const PairPayloads& p, int32_t first,
+                                int32_t num, int64_t max_count, ScatterMode mode,
+                                uint32_t* diag_flags, hipStream_t stream) {
+  if (num <= 0 || max_count <= 0) return hipSuccess;
+  int64_t chunks = ceil_div(max_count, 256 * 4);
+  if (chunks > 4096) chunks = 4096;
+  hipLaunchKernelGGL(scatter_pairs_kernel, dim3((unsigned)chunks, (unsigned)num), dim3(256), 0, stream,
+                     dense, n, p, first, mode, diag_flags);
+  return hipGetLastError();
+}
+
+hipError_t launch_scatter_regions(float* dense, int64_t n, const RegionPayloads& p, int32_t first,
+                                  int32_t num, const int64_t* out_offsets_dev, int32_t num_tensors,
+                                  int64_t total_slots, ScatterMode mode, uint32_t* diag_flags,
+                                  hipStream_t stream) {
+  if (num <= 0 || total_slots <= 0) return hipSuccess;
+  int64_t chunks = ceil_div(total_slots, 256 * 2);
+  if (chunks > 8192) chunks = 8192;
+  hipLaunchKernelGGL(scatter_regions_kernel, dim3((unsigned)chunks, (unsigned)num), dim3(256), 0,
+                     stream, dense, n, p, first, out_offsets_dev, num_tensors, total_slots, mode,
+                     diag_flags);
+  return hipGetLastError();
+}
+
+}  // namespace dgc

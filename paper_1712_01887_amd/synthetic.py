@@ -12,6 +12,8 @@ per-tensor scale drawn log-uniformly in [1e-5, 1e-2].
 from __future__ import annotations
 
 import math
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass
 from typing import List, Optional, Sequence, Tuple
 
@@ -120,7 +122,7 @@ def speech_set() -> GradientSet:
 
 def ragged_set(seed: int = 0, tensors: int = 23, max_numel: int = 70000) -> GradientSet:
     """Small set with odd sizes (tiny, unaligned and multi-tile tensors)."""
-    rng = np.random.Generator(np.random.Philox(key=seed + 77))
+    rng = np.random.Generator(np.random.SFC64(np.random.SeedSequence([int(seed), 77])))
     sizes = [1, 3, 29, 64, 4097, 5000, 16384, 33333]
     while len(sizes) < tensors:
         sizes.append(int(math.exp(rng.uniform(0.0, math.log(max_numel)))))
@@ -131,22 +133,51 @@ def ragged_set(seed: int = 0, tensors: int = 23, max_numel: int = 70000) -> Grad
 # ---------------------------------------------------------------------------
 # Values
 # ---------------------------------------------------------------------------
-def _rng(base_seed: int, worker: int, iteration: int, salt: int = 0) -> np.random.Generator:
-    return np.random.Generator(np.random.Philox(
-        key=[(int(base_seed) * 1000003 + salt) & 0xFFFFFFFFFFFFFFFF,
-             ((int(worker) & 0xFFFFFFFF) << 32) | (int(iteration) & 0xFFFFFFFF)]))
+_CHUNK = 1 << 20
+
+
+def _chunk_rng(base_seed: int, worker: int, iteration: int, salt: int, chunk: int) -> np.random.Generator:
+    ss = np.random.SeedSequence([int(base_seed) & 0xFFFFFFFF, int(worker) & 0xFFFFFFFF,
+                                 int(iteration) & 0xFFFFFFFF, int(salt), int(chunk)])
+    return np.random.Generator(np.random.SFC64(ss))
+
+
+def _fill_chunk(out: np.ndarray, base_seed: int, worker: int, iteration: int, salt: int, chunk: int) -> None:
+    lo = chunk * _CHUNK
+    hi = min(out.size, lo + _CHUNK)
+    rng = _chunk_rng(base_seed, worker, iteration, salt, chunk)
+    z = rng.standard_normal(hi - lo, dtype=np.float32)
+    c = rng.standard_gamma(1.5, size=hi - lo, dtype=np.float32)
+    # Student-t with 3 degrees of freedom: normal / sqrt(chi-square_3 / 3), chi-square_3 = 2 Gamma(3/2)
+    np.maximum(c, np.float32(1e-20), out=c)      # keeps every draw finite
+    np.multiply(c, np.float32(2.0 / 3.0), out=c)
+    np.sqrt(c, out=c)
+    np.divide(z, c, out=out[lo:hi])
+
+
+def student_t3(n: int, base_seed: int, worker: int, iteration: int, salt: int = 0,
+               out: Optional[np.ndarray] = None) -> np.ndarray:
+    """n seeded fp32 draws of Student-t(3).  The stream is cut into fixed chunks with
+    one generator each, so the values do not depend on how many threads fill them."""
+    if out is None:
+        out = np.empty(n, dtype=np.float32)
+    chunks = (n + _CHUNK - 1) // _CHUNK
+    workers = max(1, min(16, os.cpu_count() or 1, chunks))
+    if workers == 1:
+        for c in range(chunks):
+            _fill_chunk(out, base_seed, worker, iteration, salt, c)
+    else:
+        with ThreadPoolExecutor(max_workers=workers) as pool:
+            list(pool.map(lambda c: _fill_chunk(out, base_seed, worker, iteration, salt, c), range(chunks)))
+    return out
 
 
 def tensor_scales(gs: GradientSet, base_seed: int, fixed: Optional[float] = None) -> np.ndarray:
     """Per-tensor standard deviation, log-uniform in [1e-5, 1e-2], drawn once per set."""
     if fixed is not None:
         return np.full(len(gs.tensors), fixed, dtype=np.float64)
-    rng = _rng(base_seed, 0xFFFF, 0xFFFF, salt=1)
+    rng = _chunk_rng(base_seed, 0xFFFF, 0xFFFF, 1, 0)
     return np.exp(rng.uniform(math.log(1e-5), math.log(1e-2), size=len(gs.tensors)))
-
-
-def _student_t3(rng: np.random.Generator, n: int) -> np.ndarray:
-    return rng.standard_t(3.0, size=n)
 
 
 def gradient(gs: GradientSet, base_seed: int, worker: int, iteration: int,
@@ -154,26 +185,25 @@ def gradient(gs: GradientSet, base_seed: int, worker: int, iteration: int,
     """Flat fp32 gradient of worker `worker` at `iteration`: sigma_j * t(3) per tensor."""
     if scales is None:
         scales = tensor_scales(gs, base_seed)
-    rng = _rng(base_seed, worker, iteration)
+    out = student_t3(gs.numel, base_seed, worker, iteration, 0, out)
     offs = gs.offsets
-    if out is None:
-        out = np.empty(gs.numel, dtype=np.float32)
-    for j, sz in enumerate(gs.sizes):
-        out[offs[j]:offs[j + 1]] = (scales[j] * _student_t3(rng, sz)).astype(np.float32)
+    for j in range(len(gs.tensors)):
+        out[offs[j]:offs[j + 1]] *= np.float32(scales[j])
     return out
 
 
 def toy_gradient(n: int, base_seed: int, worker: int, iteration: int) -> np.ndarray:
     """Toy configuration: 1e-3 * t(3)."""
-    rng = _rng(base_seed, worker, iteration)
-    return (1e-3 * _student_t3(rng, n)).astype(np.float32)
+    out = student_t3(n, base_seed, worker, iteration)
+    out *= np.float32(1e-3)
+    return out
 
 
 def lstm_gradient(gs: GradientSet, base_seed: int, worker: int, iteration: int,
                   scales: Optional[np.ndarray] = None) -> np.ndarray:
     """As `gradient`, but the embedding gradient is zero outside 700 seeded rows."""
     g = gradient(gs, base_seed, worker, iteration, scales)
-    rng = _rng(base_seed, worker, iteration, salt=2)
+    rng = _chunk_rng(base_seed, worker, iteration, 2, 0)
     rows = rng.choice(LSTM_EMBED_ROWS, size=LSTM_ACTIVE_ROWS, replace=False)
     keep = np.zeros(LSTM_EMBED_ROWS, dtype=bool)
     keep[rows] = True
@@ -183,11 +213,14 @@ def lstm_gradient(gs: GradientSet, base_seed: int, worker: int, iteration: int,
 
 
 def correlated_gradient(gs: GradientSet, base_seed: int, worker: int, iteration: int,
-                        shared: np.ndarray, mix: float = 0.55) -> np.ndarray:
+                        shared: np.ndarray, mix: float = 0.45,
+                        scales: Optional[np.ndarray] = None) -> np.ndarray:
     """Worker gradient = mix * shared + (1 - mix) * private, both heavy-tailed, so
     that different workers' largest elements partly coincide."""
-    private = gradient(gs, base_seed, worker + 1000, iteration)
-    return (np.float32(mix) * shared + np.float32(1.0 - mix) * private).astype(np.float32)
+    private = gradient(gs, base_seed, worker + 1000, iteration, scales)
+    private *= np.float32(1.0 - mix)
+    private += np.float32(mix) * shared
+    return private
 
 
 def topk_overlap(idx_a: np.ndarray, idx_b: np.ndarray) -> float:

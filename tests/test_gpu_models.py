@@ -1,0 +1,108 @@
+"""GPU parity at the full sizes of the paper-shaped gradient sets (ResNet-50,
+LSTM language model, speech model) and of the 16-worker receive side.
+Element-by-element against the oracle; run with `-m gpu` on an MI355X."""
+
+import numpy as np
+import pytest
+
+from oracle import dgc_oracle as O
+from paper_1712_01887_amd import binding as B
+from paper_1712_01887_amd import synthetic as S
+from tests.parity import Pair, say
+
+pytestmark = pytest.mark.gpu
+
+
+def test_resnet50_set_three_iterations():
+    gs = S.resnet50_set()
+    scales = S.tensor_scales(gs, 31)
+    p = Pair(gs.offsets, momentum=0.9, density=0.001, seed=31)
+    total = 0
+    for it in range(3):
+        say(f"[resnet50] iteration {it}")
+        res = p.step(S.gradient(gs, 31, 0, it, scales), it, label=f"resnet50 it{it}")
+        total = int(res.counts.sum())
+        # 108 of the 161 tensors are small enough to be selected exactly
+        for j, n in enumerate(gs.sizes):
+            if n <= 4096:
+                assert int(res.counts[j]) == O.topk_count(0.001, n)
+    ratio8 = O.compression_ratio(gs.numel, total, 8)
+    ratio6 = O.compression_ratio(gs.numel, total, 6)
+    say(f"[resnet50] pairs={total} ratio(8 B/pair)={ratio8:.0f}x ratio(6 B/pair)={ratio6:.0f}x "
+        f"(paper, Table 3: 277x)")
+    assert 0.5 * 25670 < total < 2.0 * 25670
+    p.close()
+
+
+def test_lstm_set_with_clipping_two_iterations():
+    gs = S.lstm_lm_set()
+    scales = S.tensor_scales(gs, 41)
+    p = Pair(gs.offsets, momentum=0.9, density=0.001, seed=41, clip_threshold=0.25, num_workers=4)
+    for it in range(2):
+        say(f"[lstm] iteration {it}")
+        res = p.step(S.lstm_gradient(gs, 41, 0, it, scales), it, label=f"lstm it{it}")
+        say(f"[lstm] norm={res.norm:.4f} scale={float(res.scale):.6f} embedding pairs={int(res.counts[0])}")
+    p.close()
+
+
+def test_speech_set_warmup_schedule_six_iterations():
+    gs = S.speech_set()
+    scales = S.tensor_scales(gs, 51)
+    p = Pair(gs.offsets, layout_density=0.25, momentum=0.9, density=0.25, seed=51, num_workers=8)
+    for it in range(6):
+        d = O.warmup_density(O.WARMUP_DENSITIES, it)
+        p.dgc.dgc_set_iteration_density(it)
+        p.ocfg.density = d
+        say(f"[speech] iteration {it} density {d}")
+        res = p.step(S.gradient(gs, 51, 0, it, scales), it, check_state=(it in (0, 5)),
+                     label=f"speech it{it}")
+        say(f"[speech] pairs={int(res.counts.sum())} expected~{int(d * gs.numel)}")
+    p.close()
+
+
+def test_sixteen_worker_accumulate_resnet50_shape():
+    import torch
+    gs = S.resnet50_set()
+    N = 16
+    scales = S.tensor_scales(gs, 61)
+    shared = S.gradient(gs, 61, 999, 0, scales)
+    kw = dict(momentum=0.9, density=0.001, seed=61, num_workers=N)
+    pairs = []
+    payloads = []
+    for w in range(N):
+        say(f"[accumulate] worker {w}")
+        p = Pair(gs.offsets, **kw)
+        res = p.step(S.correlated_gradient(gs, 61, w, 0, shared, scales=scales), 0, check_state=False,
+                     label=f"acc w{w}")
+        p.u = p.v = None                                 # keep only the payload on the device
+        p.ou = p.ov = None
+        payloads.append(O.flatten_payload(res))
+        pairs.append(p)
+    overlap = S.topk_overlap(payloads[0][0], payloads[1][0])
+    say(f"[accumulate] pairs/worker ~{payloads[0][0].size}, pairwise index overlap {overlap:.2f}")
+    assert 0.15 < overlap < 0.5
+    expect = np.zeros(gs.numel, np.float32)
+    O.decompress_accumulate(expect, payloads)
+    torch.cuda.empty_cache()
+    acc = B.Dgc(B.make_config(**kw), gs.offsets)
+    acc.set_layout(pairs[0].layout)
+    dense = torch.zeros(gs.numel, dtype=torch.float32, device="cuda")
+    idx = [p.out_idx for p in pairs]
+    val = [p.out_val for p in pairs]
+    cnt = [p.out_counts for p in pairs]
+    acc.dgc_decompress_accumulate_regions(dense, idx, val, cnt)
+    got = dense.cpu().numpy()
+    # any order of the additions stays within 1e-6 of the sum of magnitudes at each index
+    mags = np.zeros(gs.numel, np.float32)
+    O.decompress_accumulate(mags, [(i, np.abs(x)) for i, x in payloads])
+    assert np.all(np.abs(got.astype(np.float64) - expect) <= 1e-6 * mags)
+    assert not got[mags == 0].any()
+    det = B.Dgc(B.make_config(flags=B.DGC_FLAG_DETERMINISTIC_ACCUMULATE, **kw), gs.offsets)
+    det.set_layout(pairs[0].layout)
+    dense.zero_()
+    det.dgc_decompress_accumulate_regions(dense, idx, val, cnt)
+    assert np.array_equal(dense.cpu().numpy().view(np.uint32), expect.view(np.uint32))
+    acc.dgc_dense_clear_regions(dense, idx, cnt)
+    assert int(torch.count_nonzero(dense).item()) == 0
+    for p in pairs:
+        p.close()

@@ -1,0 +1,192 @@
+"""GPU parity: the HIP library against the CPU oracle, through the C ABI, on the
+same seeded inputs.  Run with `-m gpu` on an MI355X."""
+
+import math
+
+import numpy as np
+import pytest
+
+from oracle import dgc_oracle as O
+from paper_1712_01887_amd import binding as B
+from paper_1712_01887_amd import synthetic as S
+from tests.parity import Pair, check_overflow_invariants, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _gpu(dgc_lib):
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    say(f"[gpu] {torch.cuda.get_device_name(0)}")
+    yield
+    torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------------------
+# Toy configuration: 2**20 elements, 4 workers x 4 iterations, clipping on,
+# then the receive side over the 4 payloads.
+# ---------------------------------------------------------------------------
+def test_toy_four_workers_compress_then_accumulate():
+    import torch
+    n = 1 << 20
+    N = 4
+    kw = dict(momentum=0.9, density=0.001, clip_threshold=1.0, num_workers=N, seed=2024)
+    pairs = [Pair([0, n], **kw) for _ in range(N)]
+    acc = B.Dgc(B.make_config(**kw), [0, n])
+    acc.set_layout(pairs[0].layout)
+    det = B.Dgc(B.make_config(flags=B.DGC_FLAG_DETERMINISTIC_ACCUMULATE, **kw), [0, n])
+    det.set_layout(pairs[0].layout)
+    for it in range(4):
+        payloads = []
+        for w in range(N):
+            g = S.toy_gradient(n, 7, w, it)
+            res = pairs[w].step(g, it, label=f"toy w{w} it{it}")
+            assert res.scale < 1.0                       # clipping is active in this configuration
+            assert 300 < int(res.counts[0]) < 3500       # sampled estimate of k = 1049
+            payloads.append(O.flatten_payload(res))
+        expect = np.zeros(n, np.float32)
+        O.decompress_accumulate(expect, payloads)
+        # (a) region layout straight from the compress outputs, atomics
+        dense = torch.zeros(n, dtype=torch.float32, device="cuda")
+        acc.dgc_decompress_accumulate_regions(dense, [p.out_idx for p in pairs], [p.out_val for p in pairs],
+                                              [p.out_counts for p in pairs])
+        got = dense.cpu().numpy()
+        mags = np.zeros(n, np.float32)
+        O.decompress_accumulate(mags, [(i, np.abs(x)) for i, x in payloads])
+        assert np.all(np.abs(got.astype(np.float64) - expect) <= 1e-6 * mags)   # any order of additions
+        assert not got[mags == 0].any()
+        # (b) the same, workers added in order: bit-exact
+        dense.zero_()
+        det.dgc_decompress_accumulate_regions(dense, [p.out_idx for p in pairs], [p.out_val for p in pairs],
+                                              [p.out_counts for p in pairs])
+        assert np.array_equal(dense.cpu().numpy().view(np.uint32), expect.view(np.uint32))
+        # (c) clearing by payload returns the aggregate to all-zero
+        acc.dgc_dense_clear_regions(dense, [p.out_idx for p in pairs], [p.out_counts for p in pairs])
+        assert not dense.cpu().numpy().any()
+        # (d) contiguous pair lists with host counts
+        counts = [int(p.out_counts.item()) for p in pairs]
+        acc.dgc_decompress_accumulate(dense, [p.out_idx for p in pairs], [p.out_val for p in pairs], counts)
+        assert np.all(np.abs(dense.cpu().numpy().astype(np.float64) - expect) <= 1e-6 * mags)
+        dense.zero_()
+        det.dgc_decompress_accumulate(dense, [p.out_idx for p in pairs], [p.out_val for p in pairs], counts)
+        assert np.array_equal(dense.cpu().numpy().view(np.uint32), expect.view(np.uint32))
+    for p in pairs:
+        p.close()
+
+
+# ---------------------------------------------------------------------------
+# Ragged set: tiny, unaligned and multi-tile tensors, every flag, several densities
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("flags", [0, B.DGC_FLAG_NESTEROV, B.DGC_FLAG_NO_FACTOR_MASKING,
+                                   B.DGC_FLAG_EXACT_SELECT,
+                                   B.DGC_FLAG_NESTEROV | B.DGC_FLAG_NO_FACTOR_MASKING | B.DGC_FLAG_EXACT_SELECT])
+@pytest.mark.parametrize("density", [0.001, 0.05, 1.0])
+def test_ragged_set_flags_and_densities(flags, density):
+    gs = S.ragged_set(3)
+    p = Pair(gs.offsets, momentum=0.9, density=density, flags=flags, seed=11, sample_min=256,
+             sample_max=2048, sample_block=16)
+    for it in range(3):
+        g = S.gradient(gs, 21, 0, it)
+        p.step(g, it, label=f"ragged flags={flags} d={density} it{it}")
+    p.close()
+
+
+@pytest.mark.parametrize("block", [1, 4, 64])
+def test_ragged_set_sample_block_sizes(block):
+    gs = S.ragged_set(4, tensors=12)
+    p = Pair(gs.offsets, momentum=0.5, density=0.01, seed=5, sample_min=128, sample_max=1024,
+             sample_block=block, clip_threshold=0.05, num_workers=8)
+    for it in range(2):
+        p.step(S.gradient(gs, 22, 1, it), it, label=f"block={block} it{it}")
+    p.close()
+
+
+def test_edge_sizes_single_elements_and_tails():
+    # one-element set, a set one short of / one past a wave tile, and a 3-element tail
+    for sizes in ([1], [1023], [1024], [1025], [4096, 3], [5, 1019, 1, 2047, 7]):
+        offsets = np.concatenate([[0], np.cumsum(sizes)])
+        p = Pair(offsets, momentum=0.9, density=0.3, seed=1, sample_min=64, sample_max=256)
+        rng = np.random.default_rng(sum(sizes))
+        for it in range(2):
+            p.step(rng.standard_normal(offsets[-1]).astype(np.float32), it, label=f"sizes={sizes} it{it}")
+        p.close()
+
+
+def test_special_values_zeros_ties_denormals():
+    n = 5000
+    p = Pair([0, 100, n], momentum=0.9, density=0.01, seed=3, sample_min=4096, sample_max=4096)
+    g = np.zeros(n, np.float32)
+    p.step(g, 0, label="all zero")                    # thr = 0, nothing passes the strict comparison
+    assert int(p.last[3].sum()) == 0
+    g[::7] = 1.0                                      # massive ties: nothing above the tied threshold
+    g[3] = -np.float32(1e-45)                         # denormal magnitude is kept, not flushed
+    g[4] = np.float32(-0.0)
+    p.step(g, 1, label="ties")
+    g = np.full(n, np.float32(1e-42), np.float32)     # all denormal
+    g[17] = np.float32(3e-42)
+    res = p.step(g, 2, label="denormals")
+    p.close()
+
+
+def test_capacity_overflow_keeps_conservation():
+    import torch
+    gs = S.ragged_set(6, tensors=10)
+    caps = [max(1, O.topk_count(0.05, s) // 2) for s in gs.sizes]          # half of what will pass
+    p = Pair(gs.offsets, capacities=caps, momentum=0.9, density=0.05, seed=9, flags=B.DGC_FLAG_EXACT_SELECT)
+    g = S.gradient(gs, 23, 0, 0)
+    u0 = (0.1 * S.gradient(gs, 23, 1, 0)).astype(np.float32)
+    v0 = (0.1 * S.gradient(gs, 23, 2, 0)).astype(np.float32)
+    p.set_state(u0, v0)
+    res = p.step(g, 0, label="overflow")
+    assert res.overflow
+    check_overflow_invariants(p, g, u0, v0)
+    p.close()
+
+
+def test_warmup_schedule_changes_plan_between_iterations():
+    gs = S.ragged_set(8, tensors=9, max_numel=200000)
+    p = Pair(gs.offsets, layout_density=0.25, momentum=0.9, density=0.25, seed=13, sample_min=512,
+             sample_max=4096)
+    for it in range(7):
+        d = O.warmup_density(O.WARMUP_DENSITIES, it)
+        p.dgc.dgc_set_iteration_density(it)
+        p.ocfg.density = d
+        p.step(S.gradient(gs, 24, 0, it), it, label=f"warmup it{it} d={d}")
+    p.close()
+
+
+def test_resume_with_a_new_handle_gives_identical_results():
+    import torch
+    gs = S.ragged_set(10, tensors=8)
+    kw = dict(momentum=0.9, density=0.01, seed=77, sample_min=256, sample_max=2048)
+    a = Pair(gs.offsets, **kw)
+    for it in range(4):
+        a.step(S.gradient(gs, 25, 0, it), it, label=f"straight it{it}")
+    b = Pair(gs.offsets, **kw)
+    for it in range(2):
+        b.step(S.gradient(gs, 25, 0, it), it, label=f"first half it{it}")
+    c = Pair(gs.offsets, **kw)                        # a fresh handle and workspace, state carried by u, v
+    c.set_state(b.u.cpu().numpy(), b.v.cpu().numpy())
+    for it in range(2, 4):
+        c.step(S.gradient(gs, 25, 0, it), it, label=f"second half it{it}")
+    assert torch.equal(a.u, c.u) and torch.equal(a.v, c.v)
+    for x in (a, b, c):
+        x.close()
+
+
+def test_bad_payload_index_is_skipped_and_flagged():
+    import torch
+    d = B.Dgc(B.dgc_config_default(), [0, 1000])
+    dense = torch.zeros(1000, dtype=torch.float32, device="cuda")
+    idx = torch.tensor([5, 1000, -1, 999, 5000000], dtype=torch.int32, device="cuda")
+    val = torch.tensor([1.0, 2.0, 3.0, 4.0, 5.0], dtype=torch.float32, device="cuda")
+    flags = torch.zeros(1, dtype=torch.int32, device="cuda")
+    d.dgc_decompress_accumulate(dense, [idx], [val], [5], diag_flags=flags)
+    out = dense.cpu().numpy()
+    assert out[5] == 1.0 and out[999] == 4.0 and out.sum() == 5.0
+    assert int(flags.item()) & B.DGC_DIAG_BAD_INDEX
+    # empty payloads are fine
+    d.dgc_decompress_accumulate(dense, [idx, idx], [val, val], [0, 0])
+    assert dense.cpu().numpy().sum() == 5.0
+    d.close()
