@@ -90,6 +90,9 @@ dgc_status dgc_config_default(dgc_config* cfg);
 
 /* Text for a status code (static storage). */
 const char* dgc_status_string(dgc_status s);
+/* Detail of the most recent DGC_ERR_HIP on the calling thread: which step failed and
+ * the runtime's message.  Thread-local storage, valid until the next failure. */
+const char* dgc_last_error_string(void);
 
 /*
  * Create the host-side description of a gradient set.

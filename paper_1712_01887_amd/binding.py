@@ -39,7 +39,7 @@ EXPORTS = [
     "dgc_set_warmup_schedule", "dgc_set_iteration_density", "dgc_query_plan", "dgc_workspace_bytes",
     "dgc_recommended_payload_layout", "dgc_compress", "dgc_get_diagnostics",
     "dgc_decompress_accumulate", "dgc_decompress_accumulate_regions", "dgc_dense_clear_regions",
-    "dgc_version",
+    "dgc_version", "dgc_last_error_string",
 ]
 
 
@@ -79,6 +79,9 @@ def load() -> C.CDLL:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is not built; run `python -m paper_1712_01887_amd.build`")
+    # torch ships its own HIP runtime under the same soname.  Importing torch first makes
+    # libdgc bind to that copy, so the tensors' device context and the kernels share one runtime.
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64, u64, dbl = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_double
     P = C.POINTER
@@ -86,6 +89,8 @@ def load() -> C.CDLL:
     lib.dgc_version.argtypes = []
     lib.dgc_status_string.restype = C.c_char_p
     lib.dgc_status_string.argtypes = [i32]
+    lib.dgc_last_error_string.restype = C.c_char_p
+    lib.dgc_last_error_string.argtypes = []
     lib.dgc_config_default.restype = i32
     lib.dgc_config_default.argtypes = [P(DgcConfig)]
     lib.dgc_create.restype = i32
@@ -121,7 +126,8 @@ def load() -> C.CDLL:
 
 def _check(status: int, what: str) -> None:
     if status != DGC_OK:
-        raise DgcError(status, f"{what}: {load().dgc_status_string(status).decode()}")
+        detail = load().dgc_last_error_string().decode() if status == DGC_ERR_HIP else ""
+        raise DgcError(status, f"{what}: {load().dgc_status_string(status).decode()} {detail}".rstrip())
 
 
 def dgc_config_default() -> DgcConfig:

@@ -3,6 +3,7 @@
 // Every step of the path itself runs in the kernels of dgc_kernels.hip.
 
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -32,6 +33,16 @@ struct dgc_handle {
 };
 
 namespace {
+
+// Text of the most recent failed HIP call on this thread (for dgc_last_error_string).
+thread_local char g_last_error[256] = "";
+
+bool hip_ok(hipError_t e, const char* what) {
+  if (e == hipSuccess) return true;
+  std::snprintf(g_last_error, sizeof(g_last_error), "%s: %s (%d)", what, hipGetErrorString(e), (int)e);
+  (void)hipGetLastError();  // clear the sticky launch error so later calls start clean
+  return false;
+}
 
 constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -132,20 +143,23 @@ dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_
     h->ws_static_valid = h->ws_plan_valid = h->ws_layout_valid = false;
   }
   if (!h->ws_static_valid) {
-    if (hipMemsetAsync(at<char>(ws, h->lay.state), 0, sizeof(DeviceState), stream) != hipSuccess)
+    if (!hip_ok(hipMemsetAsync(at<char>(ws, h->lay.state), 0, sizeof(DeviceState), stream),
+                "clear workspace state"))
       return DGC_ERR_HIP;
-    if (hipMemcpyAsync(at<char>(ws, h->lay.offsets), h->offsets.data(), sizeof(int64_t) * (T + 1),
-                       hipMemcpyHostToDevice, stream) != hipSuccess)
+    if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.offsets), h->offsets.data(),
+                               sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, stream),
+                "upload offsets"))
       return DGC_ERR_HIP;
-    if (hipMemcpyAsync(at<char>(ws, h->lay.tile_first), h->tile_first.data(),
-                       sizeof(int32_t) * h->tile_first.size(), hipMemcpyHostToDevice,
-                       stream) != hipSuccess)
+    if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.tile_first), h->tile_first.data(),
+                               sizeof(int32_t) * h->tile_first.size(), hipMemcpyHostToDevice, stream),
+                "upload tile table"))
       return DGC_ERR_HIP;
     h->ws_static_valid = true;
   }
   if (need_plan && !h->ws_plan_valid) {
-    if (hipMemcpyAsync(at<char>(ws, h->lay.plans), h->plans.data(), sizeof(TensorPlan) * T,
-                       hipMemcpyHostToDevice, stream) != hipSuccess)
+    if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.plans), h->plans.data(), sizeof(TensorPlan) * T,
+                               hipMemcpyHostToDevice, stream),
+                "upload selection plan"))
       return DGC_ERR_HIP;
     h->ws_plan_valid = true;
   }
@@ -154,8 +168,9 @@ dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_
                       std::memcmp(h->ws_out_offsets.data(), out_offsets, sizeof(int64_t) * (T + 1)) == 0;
     if (!same) {
       h->ws_out_offsets.assign(out_offsets, out_offsets + T + 1);
-      if (hipMemcpyAsync(at<char>(ws, h->lay.out_offsets), h->ws_out_offsets.data(),
-                         sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, stream) != hipSuccess)
+      if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.out_offsets), h->ws_out_offsets.data(),
+                                 sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, stream),
+                  "upload payload layout"))
         return DGC_ERR_HIP;
       h->ws_layout_valid = true;
     }
@@ -168,6 +183,8 @@ dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_
 extern "C" {
 
 int32_t dgc_version(void) { return 1000; }
+
+const char* dgc_last_error_string(void) { return g_last_error; }
 
 const char* dgc_status_string(dgc_status s) {
   switch (s) {
@@ -328,8 +345,9 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   // paper: Appendix C equation 12 -- the local threshold is N^-1/2 times the global one.
   if (clip) {
     const double thr_local = (double)c.clip_threshold / std::sqrt((double)c.num_workers);
-    if (launch_norm(g, h->n, state, at<double>(workspace, h->lay.partials), thr_local,
-                    c.scale_override, stream) != hipSuccess)
+    if (!hip_ok(launch_norm(g, h->n, state, at<double>(workspace, h->lay.partials), thr_local,
+                            c.scale_override, stream),
+                "launch norm kernel"))
       return DGC_ERR_HIP;
   }
   const float scale_const = have_override ? c.scale_override : 1.0f;
@@ -354,7 +372,7 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   sa.seed_hi = (uint32_t)(c.seed >> 32);
   sa.iter_lo = (uint32_t)(iteration & 0xFFFFFFFFu);
   sa.iter_hi = (uint32_t)(iteration >> 32);
-  if (launch_select(sa, h->num_tensors, stream) != hipSuccess) return DGC_ERR_HIP;
+  if (!hip_ok(launch_select(sa, h->num_tensors, stream), "launch select kernel")) return DGC_ERR_HIP;
 
   StreamArgs ta{};
   ta.g = g;
@@ -375,7 +393,7 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   ta.scale_from_state = sa.scale_from_state;
   ta.nesterov = sa.nesterov;
   ta.factor_masking = (c.flags & DGC_FLAG_NO_FACTOR_MASKING) ? 0 : 1;
-  if (launch_stream(ta, stream) != hipSuccess) return DGC_ERR_HIP;
+  if (!hip_ok(launch_stream(ta, stream), "launch stream kernel")) return DGC_ERR_HIP;
   return DGC_OK;
 }
 
@@ -384,10 +402,11 @@ dgc_status dgc_get_diagnostics(dgc_handle* h, const void* workspace, dgc_diagnos
   if (!h || !workspace || !out_host) return DGC_ERR_INVALID_ARG;
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   DeviceState s;
-  if (hipMemcpyAsync(&s, static_cast<const char*>(workspace) + h->lay.state, sizeof(s),
-                     hipMemcpyDeviceToHost, stream) != hipSuccess)
+  if (!hip_ok(hipMemcpyAsync(&s, static_cast<const char*>(workspace) + h->lay.state, sizeof(s),
+                             hipMemcpyDeviceToHost, stream),
+              "read diagnostics"))
     return DGC_ERR_HIP;
-  if (hipStreamSynchronize(stream) != hipSuccess) return DGC_ERR_HIP;
+  if (!hip_ok(hipStreamSynchronize(stream), "synchronize stream")) return DGC_ERR_HIP;
   out_host->norm = s.norm;
   out_host->scale = s.scale;
   out_host->flags = s.flags;
@@ -419,12 +438,12 @@ dgc_status dgc_decompress_accumulate(dgc_handle* h, float* dense, int64_t n, int
   if (h->cfg.flags & DGC_FLAG_DETERMINISTIC_ACCUMULATE) {
     // one launch per worker, in order: within a payload every index is distinct
     for (int32_t w = 0; w < num_payloads; ++w)
-      if (launch_scatter_pairs(dense, n, p, w, 1, p.count[w], kScatterPlainAdd, diag_flags_dev,
-                               stream) != hipSuccess)
+      if (!hip_ok(launch_scatter_pairs(dense, n, p, w, 1, p.count[w], kScatterPlainAdd, diag_flags_dev,
+                               stream), "launch scatter kernel"))
         return DGC_ERR_HIP;
   } else {
-    if (launch_scatter_pairs(dense, n, p, 0, num_payloads, max_count, kScatterAtomicAdd,
-                             diag_flags_dev, stream) != hipSuccess)
+    if (!hip_ok(launch_scatter_pairs(dense, n, p, 0, num_payloads, max_count, kScatterAtomicAdd,
+                             diag_flags_dev, stream), "launch scatter kernel"))
       return DGC_ERR_HIP;
   }
   return DGC_OK;
@@ -456,17 +475,17 @@ static dgc_status scatter_regions(dgc_handle* h, float* dense, int32_t num_paylo
   const int64_t* oo = at<int64_t>(workspace, h->lay.out_offsets);
   const int64_t total = out_offsets_host[h->num_tensors];
   if (clear) {
-    if (launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, total,
-                               kScatterClear, nullptr, stream) != hipSuccess)
+    if (!hip_ok(launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, total,
+                               kScatterClear, nullptr, stream), "launch scatter kernel"))
       return DGC_ERR_HIP;
   } else if (h->cfg.flags & DGC_FLAG_DETERMINISTIC_ACCUMULATE) {
     for (int32_t w = 0; w < num_payloads; ++w)
-      if (launch_scatter_regions(dense, h->n, p, w, 1, oo, h->num_tensors, total, kScatterPlainAdd,
-                                 nullptr, stream) != hipSuccess)
+      if (!hip_ok(launch_scatter_regions(dense, h->n, p, w, 1, oo, h->num_tensors, total, kScatterPlainAdd,
+                                 nullptr, stream), "launch scatter kernel"))
         return DGC_ERR_HIP;
   } else {
-    if (launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, total,
-                               kScatterAtomicAdd, nullptr, stream) != hipSuccess)
+    if (!hip_ok(launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, total,
+                               kScatterAtomicAdd, nullptr, stream), "launch scatter kernel"))
       return DGC_ERR_HIP;
   }
   return DGC_OK;

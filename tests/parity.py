@@ -53,7 +53,8 @@ class Pair:
         else:
             layout = self.dgc.dgc_recommended_payload_layout(
                 layout_density if layout_density is not None else self.ocfg.density)
-        self.capacities = capacities
+        # the oracle always sees the capacities the library was given
+        self.capacities = [int(layout[j + 1] - layout[j]) for j in range(self.T)]
         self.dgc.set_layout(layout)
         self.layout = layout
         dev = "cuda"

@@ -84,8 +84,9 @@ def test_toy_four_workers_compress_then_accumulate():
 @pytest.mark.parametrize("density", [0.001, 0.05, 1.0])
 def test_ragged_set_flags_and_densities(flags, density):
     gs = S.ragged_set(3)
-    p = Pair(gs.offsets, momentum=0.9, density=density, flags=flags, seed=11, sample_min=256,
-             sample_max=2048, sample_block=16)
+    # small samples over-select by a wide margin: give the payload room
+    p = Pair(gs.offsets, layout_density=max(density, 0.05), momentum=0.9, density=density, flags=flags,
+             seed=11, sample_min=256, sample_max=2048, sample_block=16)
     for it in range(3):
         g = S.gradient(gs, 21, 0, it)
         p.step(g, it, label=f"ragged flags={flags} d={density} it{it}")
@@ -95,8 +96,8 @@ def test_ragged_set_flags_and_densities(flags, density):
 @pytest.mark.parametrize("block", [1, 4, 64])
 def test_ragged_set_sample_block_sizes(block):
     gs = S.ragged_set(4, tensors=12)
-    p = Pair(gs.offsets, momentum=0.5, density=0.01, seed=5, sample_min=128, sample_max=1024,
-             sample_block=block, clip_threshold=0.05, num_workers=8)
+    p = Pair(gs.offsets, layout_density=0.2, momentum=0.5, density=0.01, seed=5, sample_min=128,
+             sample_max=1024, sample_block=block, clip_threshold=0.05, num_workers=8)
     for it in range(2):
         p.step(S.gradient(gs, 22, 1, it), it, label=f"block={block} it{it}")
     p.close()
@@ -106,7 +107,7 @@ def test_edge_sizes_single_elements_and_tails():
     # one-element set, a set one short of / one past a wave tile, and a 3-element tail
     for sizes in ([1], [1023], [1024], [1025], [4096, 3], [5, 1019, 1, 2047, 7]):
         offsets = np.concatenate([[0], np.cumsum(sizes)])
-        p = Pair(offsets, momentum=0.9, density=0.3, seed=1, sample_min=64, sample_max=256)
+        p = Pair(offsets, layout_density=1.0, momentum=0.9, density=0.3, seed=1, sample_min=64, sample_max=256)
         rng = np.random.default_rng(sum(sizes))
         for it in range(2):
             p.step(rng.standard_normal(offsets[-1]).astype(np.float32), it, label=f"sizes={sizes} it{it}")
@@ -115,7 +116,8 @@ def test_edge_sizes_single_elements_and_tails():
 
 def test_special_values_zeros_ties_denormals():
     n = 5000
-    p = Pair([0, 100, n], momentum=0.9, density=0.01, seed=3, sample_min=4096, sample_max=4096)
+    p = Pair([0, 100, n], layout_density=1.0, momentum=0.9, density=0.01, seed=3, sample_min=4096,
+             sample_max=4096)
     g = np.zeros(n, np.float32)
     p.step(g, 0, label="all zero")                    # thr = 0, nothing passes the strict comparison
     assert int(p.last[3].sum()) == 0
@@ -159,7 +161,7 @@ def test_warmup_schedule_changes_plan_between_iterations():
 def test_resume_with_a_new_handle_gives_identical_results():
     import torch
     gs = S.ragged_set(10, tensors=8)
-    kw = dict(momentum=0.9, density=0.01, seed=77, sample_min=256, sample_max=2048)
+    kw = dict(layout_density=0.2, momentum=0.9, density=0.01, seed=77, sample_min=256, sample_max=2048)
     a = Pair(gs.offsets, **kw)
     for it in range(4):
         a.step(S.gradient(gs, 25, 0, it), it, label=f"straight it{it}")
