@@ -1,0 +1,249 @@
+#!/usr/bin/env python3
+"""Benchmark of the DGC hot path on one MI355X.
+
+A step is one pass of the whole path for one worker of an N = 16 job on the
+ResNet-50-shaped gradient set (25,557,032 fp32 elements in 161 tensors, density
+0.1 %, momentum 0.9, no clipping): dgc_compress of the worker's gradient
+(sampled thresholds, fused update + mask + compaction + factor masking), then
+dgc_decompress_accumulate_regions of 16 payloads (the fresh one and 15 from
+other seeded, correlated streams) into the dense aggregate, then
+dgc_dense_clear_regions to return the aggregate to zero.  Four workers' states
+(g, u, v: 1.2 GB together) rotate so that no step finds its operands in the
+256 MB last-level cache.  Inputs are generated on the host once, seeded, and are
+resident in HBM before the timed region.
+
+Prints one JSON line: whole-job throughput in dense gradient elements per
+second, the roofline of the dominant kernel (the streaming pass, 20 bytes per
+element) from HIP events recorded on the launch stream, and the CPU oracle timed
+on a bounded sample of the same workload.
+"""
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0           # MI355X published peak
+BYTES_PER_ELEMENT = 20           # read g, u, v; write u, v (fp32)
+N_WORKERS = 16
+ROTATE = 4
+
+# HBM traffic of one streaming-kernel launch on this workload from rocprofv3 --pmc
+# (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); see
+# profiles/.  None until measured.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-only", action="store_true",
+                    help="skip the CPU baseline and the event-instrumented pass (for rocprofv3 runs)")
+    return ap.parse_args()
+
+
+def cpu_baseline(gs, scales, shared_seed):
+    """The oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle import dgc_oracle as O
+    from paper_1712_01887_amd import synthetic as S
+
+    cfg = O.OracleConfig(momentum=0.9, density=0.001, seed=1, num_workers=N_WORKERS)
+    u = np.zeros(gs.numel, np.float32)
+    v = np.zeros(gs.numel, np.float32)
+    grads = [S.gradient(gs, shared_seed, 0, it, scales) for it in range(4)]
+    O.compress(grads[0], u, v, gs.offsets, cfg, 0)                     # untimed: first touch of the buffers
+    t_comp = 0.0
+    iters = 0
+    res = None
+    while iters < 3 or (t_comp < 8.0 and iters < 12):
+        t0 = time.perf_counter()
+        res = O.compress(grads[(iters + 1) % 4], u, v, gs.offsets, cfg, iters + 1)
+        t_comp += time.perf_counter() - t0
+        iters += 1
+    payload = O.flatten_payload(res)
+    dense = np.zeros(gs.numel, np.float32)
+    reps = 5
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        O.decompress_accumulate(dense, [payload] * N_WORKERS)
+        dense[payload[0]] = 0.0                                        # sparse clear, as the GPU step does
+    t_acc = (time.perf_counter() - t0) / reps
+    per_step = t_comp / iters + t_acc
+    return {
+        "value": gs.numel / per_step,
+        "unit": "elements/s",
+        "cores": 1,
+        "kind": "oracle",
+        "sample": f"{iters} compress iterations of the full ResNet-50-shaped set "
+                  f"({t_comp / iters * 1e3:.0f} ms each) + accumulate/clear of {N_WORKERS} payloads "
+                  f"({t_acc * 1e3:.1f} ms), numpy, single thread",
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the path has no collective and this build runs on a "
+              "single MI355X; use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1712_01887_amd import binding as B
+    from paper_1712_01887_amd import synthetic as S
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    gs = S.resnet50_set()
+    n = gs.numel
+    seed = 2025
+    scales = S.tensor_scales(gs, seed)
+    kw = dict(momentum=0.9, density=0.001, seed=1, num_workers=N_WORKERS)
+
+    dgc = B.Dgc(B.make_config(**kw), gs.offsets)
+    layout = dgc.dgc_recommended_payload_layout(0.001)
+    dgc.set_layout(layout)
+
+    # ---- inputs, resident in HBM ----------------------------------------------
+    shared = S.gradient(gs, seed, 999, 0, scales)
+    g_pool = [torch.from_numpy(S.correlated_gradient(gs, seed, r, 0, shared, scales=scales)).to(dev)
+              for r in range(ROTATE)]
+    u = [torch.zeros(n, device=dev) for _ in range(ROTATE)]
+    v = [torch.zeros(n, device=dev) for _ in range(ROTATE)]
+    fresh = [dgc.alloc_payload(dev) for _ in range(ROTATE)]
+    # 15 payloads of other workers: one compress each of a correlated stream
+    others = []
+    tu = torch.zeros(n, device=dev)
+    tv = torch.zeros(n, device=dev)
+    for w in range(N_WORKERS - 1):
+        gw = torch.from_numpy(S.correlated_gradient(gs, seed, 100 + w, 0, shared, scales=scales)).to(dev)
+        tu.zero_()
+        tv.zero_()
+        pl = dgc.alloc_payload(dev)
+        dgc.dgc_compress(gw, tu, tv, pl[0], pl[1], pl[2], pl[3], 0)
+        others.append(pl)
+    torch.cuda.synchronize()
+    del tu, tv, gw
+    dense = torch.zeros(n, device=dev)
+
+    # every argument marshalled once: worker r with gradient slot q
+    prepared = {}
+    for r in range(ROTATE):
+        f = fresh[r]
+        plist = B.PayloadList([f[0]] + [o[0] for o in others], [f[1]] + [o[1] for o in others],
+                              [f[2]] + [o[2] for o in others])
+        for q in range(ROTATE):
+            prepared[(r, q)] = B.PreparedStep(dgc, g_pool[q], u[r], v[r], f, plist, dense)
+
+    def step(i):
+        r = i % ROTATE
+        it = i // ROTATE
+        p = prepared[(r, (r + it) % ROTATE)]
+        p.compress(it)
+        p.accumulate_and_clear()
+
+    # ---- warm-up, then the timed region -------------------------------------------
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.warmup, args.warmup + args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+
+    # ---- the same steps again with HIP events on the launch stream ----------------------
+    roofline = None
+    breakdown = {}
+    if not args.profile_only:
+        dgc.dgc_profile_enable(args.steps)
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+        base = args.warmup + args.steps
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for k in range(args.steps):
+            i = base + k
+            r = i % ROTATE
+            it = i // ROTATE
+            p = prepared[(r, (r + it) % ROTATE)]
+            ev[k][0].record()
+            p.compress(it)
+            ev[k][1].record()
+            p.accumulate_and_clear()
+            ev[k][2].record()
+        torch.cuda.synchronize()
+        profiled_ms = (time.perf_counter() - t1) / args.steps * 1e3
+        calls, norm_ms, select_ms, stream_ms, emit_ms = dgc.dgc_profile_collect()
+        dgc.dgc_profile_disable()
+        stream_avg_ms = stream_ms / calls
+        achieved = BYTES_PER_ELEMENT * n / (stream_avg_ms * 1e-3) / 1e9
+        roofline = {
+            "bound": "hbm",
+            "kernel": "stream_kernel",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "traffic": MEASURED_TRAFFIC_BYTES,
+            "algorithmic_bytes": BYTES_PER_ELEMENT * n,
+            "avg_kernel_us": round(stream_avg_ms * 1e3, 2),
+        }
+        comp = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
+        acc = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+        breakdown = {
+            "compress_us": round(comp * 1e3, 2),
+            "select_kernel_us": round(select_ms / calls * 1e3, 2),
+            "stream_kernel_us": round(stream_avg_ms * 1e3, 2),
+            "emit_kernel_us": round(emit_ms / calls * 1e3, 2),
+            "accumulate_and_clear_us": round(acc * 1e3, 2),
+            "ms_per_step_with_events": round(profiled_ms, 5),
+        }
+
+    counts = int(fresh[0][2].sum().item())
+    out = {
+        "metric": "dense gradient elements/s for compress+decompress",
+        "value": n / (ms_per_step * 1e-3),
+        "unit": "elements/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "ResNet-50-shaped gradient set, 161 fp32 tensors, 25,557,032 elements, density 0.001, "
+                        "m=0.9, no clipping; step = compress one worker + accumulate 16 payloads + sparse clear",
+            "elements": n,
+            "tensors": len(gs.sizes),
+            "workers_accumulated": N_WORKERS,
+            "rotating_states": ROTATE,
+            "pairs_per_payload": counts,
+        },
+        "algorithmic_GBps_whole_step": round(BYTES_PER_ELEMENT * n / (ms_per_step * 1e-3) / 1e9, 1),
+        "compression_ratio": {"ours_8B_pairs": round(4.0 * n / (8 * counts), 1),
+                              "ours_6B_entries": round(4.0 * n / (6 * counts), 1),
+                              "paper_resnet50": 277, "paper_range": "270-600"},
+        "breakdown": breakdown,
+        "roofline": roofline,
+    }
+    if not (args.no_cpu_baseline or args.profile_only):
+        out["cpu_baseline"] = cpu_baseline(gs, scales, seed)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -219,6 +219,20 @@ dgc_status dgc_dense_clear_regions(dgc_handle* h, float* dense, int32_t num_payl
                                    const int64_t* out_offsets_host, void* workspace,
                                    size_t workspace_bytes, void* stream);
 
+/*
+ * Kernel timing for measurement harnesses.  After dgc_profile_enable the next
+ * `max_calls` dgc_compress calls record HIP events on the caller's stream before
+ * the norm kernel, after it, after the select kernel, after the streaming kernel
+ * and after the emit kernel.  dgc_profile_collect waits for the recorded calls, returns how
+ * many there were and the summed durations (milliseconds) of the four kernels, and starts a
+ * new batch.  Enabling creates events (a runtime allocation); the hot path itself
+ * allocates nothing.  Errors: INVALID_ARG, STATE (collect without enable), HIP.
+ */
+dgc_status dgc_profile_enable(dgc_handle* h, int32_t max_calls);
+dgc_status dgc_profile_collect(dgc_handle* h, int32_t* calls, double* norm_ms, double* select_ms,
+                               double* stream_ms, double* emit_ms);
+dgc_status dgc_profile_disable(dgc_handle* h);
+
 /* Library version, major * 1000 + minor. */
 int32_t dgc_version(void);
 

@@ -39,7 +39,8 @@ EXPORTS = [
     "dgc_set_warmup_schedule", "dgc_set_iteration_density", "dgc_query_plan", "dgc_workspace_bytes",
     "dgc_recommended_payload_layout", "dgc_compress", "dgc_get_diagnostics",
     "dgc_decompress_accumulate", "dgc_decompress_accumulate_regions", "dgc_dense_clear_regions",
-    "dgc_version", "dgc_last_error_string",
+    "dgc_version", "dgc_last_error_string", "dgc_profile_enable", "dgc_profile_collect",
+    "dgc_profile_disable",
 ]
 
 
@@ -120,6 +121,12 @@ def load() -> C.CDLL:
                                                       C.c_size_t, vp]
     lib.dgc_dense_clear_regions.restype = i32
     lib.dgc_dense_clear_regions.argtypes = [vp, vp, i32, P(vp), P(vp), P(i64), vp, C.c_size_t, vp]
+    lib.dgc_profile_enable.restype = i32
+    lib.dgc_profile_enable.argtypes = [vp, i32]
+    lib.dgc_profile_collect.restype = i32
+    lib.dgc_profile_collect.argtypes = [vp, P(i32), P(dbl), P(dbl), P(dbl), P(dbl)]
+    lib.dgc_profile_disable.restype = i32
+    lib.dgc_profile_disable.argtypes = [vp]
     _lib = lib
     return lib
 
@@ -255,6 +262,19 @@ class Dgc:
                "dgc_get_diagnostics")
         return d
 
+    def dgc_profile_enable(self, max_calls: int) -> None:
+        _check(self.lib.dgc_profile_enable(self._h, int(max_calls)), "dgc_profile_enable")
+
+    def dgc_profile_collect(self):
+        """(calls, norm_ms, select_ms, stream_ms, emit_ms) summed over the recorded calls."""
+        calls, a, b, c, d = C.c_int32(), C.c_double(), C.c_double(), C.c_double(), C.c_double()
+        _check(self.lib.dgc_profile_collect(self._h, C.byref(calls), C.byref(a), C.byref(b), C.byref(c),
+                                            C.byref(d)), "dgc_profile_collect")
+        return calls.value, a.value, b.value, c.value, d.value
+
+    def dgc_profile_disable(self) -> None:
+        _check(self.lib.dgc_profile_disable(self._h), "dgc_profile_disable")
+
     def dgc_decompress_accumulate(self, dense, idx_list, val_list, counts: Sequence[int],
                                   diag_flags=None) -> None:
         n = len(idx_list)
@@ -275,6 +295,54 @@ class Dgc:
         _check(self.lib.dgc_dense_clear_regions(
             self._h, _ptr(dense), len(idx_list), _ptr_array(idx_list), _ptr_array(count_list),
             self._layout_c, self._ws_ptr, self._ws_bytes, _stream()), "dgc_dense_clear_regions")
+
+
+class PayloadList:
+    """Device pointers of several region-layout payloads, marshalled once so that a
+    measurement loop does not rebuild ctypes arrays every call.  Keeps the tensors alive."""
+
+    def __init__(self, idx_list, val_list, count_list):
+        self.tensors = (list(idx_list), list(val_list) if val_list is not None else None, list(count_list))
+        self.n = len(idx_list)
+        self.idx = _ptr_array(idx_list)
+        self.val = _ptr_array(val_list) if val_list is not None else None
+        self.counts = _ptr_array(count_list)
+
+
+class PreparedStep:
+    """One worker's compress call and the accumulate / clear calls that follow it, with every
+    argument marshalled ahead of time (pointers, layout, workspace, stream)."""
+
+    def __init__(self, dgc: "Dgc", g, u, v, payload, accumulate: PayloadList, dense):
+        dgc.ensure_workspace(g.device)
+        self.keep = (g, u, v, payload, accumulate, dense)
+        lib, h = dgc.lib, dgc._h
+        stream = C.c_void_p(_stream())
+        out_idx, out_val, out_counts, out_thr = payload
+        ws, wsb = C.c_void_p(dgc._ws_ptr), C.c_size_t(dgc._ws_bytes)
+        cargs = (h, C.c_void_p(_ptr(g)), C.c_void_p(_ptr(u)), C.c_void_p(_ptr(v)), C.c_void_p(_ptr(out_idx)),
+                 C.c_void_p(_ptr(out_val)), dgc._layout_c, C.c_void_p(_ptr(out_counts)),
+                 C.c_void_p(_ptr(out_thr)))
+        aargs = (h, C.c_void_p(_ptr(dense)), C.c_int32(accumulate.n), accumulate.idx, accumulate.val,
+                 accumulate.counts, dgc._layout_c, ws, wsb, stream)
+        kargs = (h, C.c_void_p(_ptr(dense)), C.c_int32(accumulate.n), accumulate.idx, accumulate.counts,
+                 dgc._layout_c, ws, wsb, stream)
+
+        def compress(iteration: int) -> None:
+            st = lib.dgc_compress(*cargs, C.c_uint64(iteration), ws, wsb, stream)
+            if st != DGC_OK:
+                _check(st, "dgc_compress")
+
+        def accumulate_and_clear() -> None:
+            st = lib.dgc_decompress_accumulate_regions(*aargs)
+            if st != DGC_OK:
+                _check(st, "dgc_decompress_accumulate_regions")
+            st = lib.dgc_dense_clear_regions(*kargs)
+            if st != DGC_OK:
+                _check(st, "dgc_dense_clear_regions")
+
+        self.compress = compress
+        self.accumulate_and_clear = accumulate_and_clear
 
 
 def gather_payload(layout: Sequence[int], out_idx, out_val, out_counts):

@@ -22,7 +22,8 @@ struct dgc_handle {
   std::vector<TensorPlan> plans;     // T
   std::vector<int64_t> k;            // T
   std::vector<int64_t> draws;        // T
-  std::vector<int32_t> tile_first;   // ceil(n / kWaveTile)
+  std::vector<uint32_t> tile_info;   // ceil(n / kWaveTile)
+  int64_t max_tiles_per_tensor = 0;  // grid width of the emit pass
   WorkspaceLayout lay{};
   // what the bound workspace currently holds
   void* ws = nullptr;
@@ -30,6 +31,11 @@ struct dgc_handle {
   bool ws_plan_valid = false;
   bool ws_layout_valid = false;
   std::vector<int64_t> ws_out_offsets;
+  // optional kernel timing: five events per dgc_compress call
+  // (start, after norm, after select, after stream, after emit)
+  std::vector<hipEvent_t> prof_events;
+  int32_t prof_capacity = 0;  // calls that can be recorded before a collect
+  int32_t prof_calls = 0;
 };
 
 namespace {
@@ -45,6 +51,7 @@ bool hip_ok(hipError_t e, const char* what) {
 }
 
 constexpr size_t kAlign = 256;
+constexpr int kProfEvents = 5;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 bool valid_density(double d) { return d > 0.0 && d <= 1.0; }
@@ -110,7 +117,8 @@ void build_layout(dgc_handle* h) {
   l.out_offsets = off;  off = align_up(off + sizeof(int64_t) * (T + 1));
   l.plans = off;        off = align_up(off + sizeof(TensorPlan) * T);
   l.thr = off;          off = align_up(off + sizeof(float) * T);
-  l.tile_first = off;   off = align_up(off + sizeof(int32_t) * tiles);
+  l.tile_info = off;    off = align_up(off + sizeof(uint32_t) * tiles);
+  l.mask = off;         off = align_up(off + sizeof(uint16_t) * 64 * tiles);
   l.total = off;
 }
 
@@ -150,8 +158,8 @@ dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_
                                sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, stream),
                 "upload offsets"))
       return DGC_ERR_HIP;
-    if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.tile_first), h->tile_first.data(),
-                               sizeof(int32_t) * h->tile_first.size(), hipMemcpyHostToDevice, stream),
+    if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.tile_info), h->tile_info.data(),
+                               sizeof(uint32_t) * h->tile_info.size(), hipMemcpyHostToDevice, stream),
                 "upload tile table"))
       return DGC_ERR_HIP;
     h->ws_static_valid = true;
@@ -244,12 +252,18 @@ dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tenso
     h->k.resize(num_tensors);
     h->draws.resize(num_tensors);
     const int64_t tiles = (h->n + kWaveTile - 1) / kWaveTile;
-    h->tile_first.resize((size_t)tiles);
+    h->tile_info.resize((size_t)tiles);
     int32_t j = 0;
     for (int64_t t = 0; t < tiles; ++t) {
       const int64_t first = t * kWaveTile;
+      const int64_t last = first + kWaveTile;  // one past the tile
       while (h->offsets[j + 1] <= first) ++j;
-      h->tile_first[(size_t)t] = j;
+      const bool whole = last <= h->n && last <= h->offsets[j + 1];
+      h->tile_info[(size_t)t] = (uint32_t)j | (whole ? 0u : kTileMixed);
+    }
+    for (int32_t t = 0; t < num_tensors; ++t) {
+      const int64_t nt = (h->offsets[t + 1] - 1) / kWaveTile - h->offsets[t] / kWaveTile + 1;
+      if (nt > h->max_tiles_per_tensor) h->max_tiles_per_tensor = nt;
     }
     h->ws_out_offsets.resize(num_tensors + 1);
   } catch (...) {
@@ -262,7 +276,10 @@ dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tenso
   return DGC_OK;
 }
 
+static void profile_release(dgc_handle* h);
+
 dgc_status dgc_destroy(dgc_handle* h) {
+  if (h) profile_release(h);
   delete h;
   return DGC_OK;
 }
@@ -342,6 +359,13 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   const bool have_override = c.scale_override == c.scale_override;
   DeviceState* state = at<DeviceState>(workspace, h->lay.state);
 
+  hipEvent_t* ev = nullptr;
+  if (h->prof_capacity > 0 && h->prof_calls < h->prof_capacity) {
+    ev = &h->prof_events[(size_t)h->prof_calls * kProfEvents];
+    ++h->prof_calls;
+    if (!hip_ok(hipEventRecord(ev[0], stream), "record event")) return DGC_ERR_HIP;
+  }
+
   // paper: Appendix C equation 12 -- the local threshold is N^-1/2 times the global one.
   if (clip) {
     const double thr_local = (double)c.clip_threshold / std::sqrt((double)c.num_workers);
@@ -350,6 +374,7 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
                 "launch norm kernel"))
       return DGC_ERR_HIP;
   }
+  if (ev && !hip_ok(hipEventRecord(ev[1], stream), "record event")) return DGC_ERR_HIP;
   const float scale_const = have_override ? c.scale_override : 1.0f;
 
   SelectArgs sa{};
@@ -373,18 +398,16 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   sa.iter_lo = (uint32_t)(iteration & 0xFFFFFFFFu);
   sa.iter_hi = (uint32_t)(iteration >> 32);
   if (!hip_ok(launch_select(sa, h->num_tensors, stream), "launch select kernel")) return DGC_ERR_HIP;
+  if (ev && !hip_ok(hipEventRecord(ev[2], stream), "record event")) return DGC_ERR_HIP;
 
   StreamArgs ta{};
   ta.g = g;
   ta.u = u;
   ta.v = v;
-  ta.out_idx = out_idx;
-  ta.out_val = out_val;
+  ta.mask = at<uint16_t>(workspace, h->lay.mask);
   ta.offsets = at<int64_t>(workspace, h->lay.offsets);
-  ta.out_offsets = at<int64_t>(workspace, h->lay.out_offsets);
   ta.thr = sa.thr;
-  ta.out_counts = out_counts;
-  ta.tile_first = at<int32_t>(workspace, h->lay.tile_first);
+  ta.tile_info = at<uint32_t>(workspace, h->lay.tile_info);
   ta.state = state;
   ta.n = h->n;
   ta.num_tensors = h->num_tensors;
@@ -392,8 +415,76 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   ta.scale_const = scale_const;
   ta.scale_from_state = sa.scale_from_state;
   ta.nesterov = sa.nesterov;
-  ta.factor_masking = (c.flags & DGC_FLAG_NO_FACTOR_MASKING) ? 0 : 1;
   if (!hip_ok(launch_stream(ta, stream), "launch stream kernel")) return DGC_ERR_HIP;
+  if (ev && !hip_ok(hipEventRecord(ev[3], stream), "record event")) return DGC_ERR_HIP;
+
+  EmitArgs ea{};
+  ea.u = u;
+  ea.v = v;
+  ea.mask = ta.mask;
+  ea.out_idx = out_idx;
+  ea.out_val = out_val;
+  ea.offsets = ta.offsets;
+  ea.out_offsets = at<int64_t>(workspace, h->lay.out_offsets);
+  ea.out_counts = out_counts;
+  ea.state = state;
+  ea.factor_masking = (c.flags & DGC_FLAG_NO_FACTOR_MASKING) ? 0 : 1;
+  if (!hip_ok(launch_emit(ea, h->num_tensors, h->max_tiles_per_tensor, stream), "launch emit kernel"))
+    return DGC_ERR_HIP;
+  if (ev && !hip_ok(hipEventRecord(ev[4], stream), "record event")) return DGC_ERR_HIP;
+  return DGC_OK;
+}
+
+static void profile_release(dgc_handle* h) {
+  for (hipEvent_t e : h->prof_events) (void)hipEventDestroy(e);
+  h->prof_events.clear();
+  h->prof_capacity = 0;
+  h->prof_calls = 0;
+}
+
+dgc_status dgc_profile_enable(dgc_handle* h, int32_t max_calls) {
+  if (!h || max_calls < 1 || max_calls > 65536) return DGC_ERR_INVALID_ARG;
+  profile_release(h);
+  h->prof_events.reserve((size_t)max_calls * kProfEvents);
+  for (int32_t i = 0; i < max_calls * kProfEvents; ++i) {
+    hipEvent_t e;
+    if (!hip_ok(hipEventCreate(&e), "create event")) {
+      profile_release(h);
+      return DGC_ERR_HIP;
+    }
+    h->prof_events.push_back(e);
+  }
+  h->prof_capacity = max_calls;
+  return DGC_OK;
+}
+
+dgc_status dgc_profile_collect(dgc_handle* h, int32_t* calls, double* norm_ms, double* select_ms,
+                               double* stream_ms, double* emit_ms) {
+  if (!h || !calls || !norm_ms || !select_ms || !stream_ms || !emit_ms) return DGC_ERR_INVALID_ARG;
+  if (h->prof_capacity < 1) return DGC_ERR_STATE;
+  *calls = h->prof_calls;
+  *norm_ms = *select_ms = *stream_ms = *emit_ms = 0.0;
+  for (int32_t i = 0; i < h->prof_calls; ++i) {
+    hipEvent_t* ev = &h->prof_events[(size_t)i * kProfEvents];
+    if (!hip_ok(hipEventSynchronize(ev[4]), "wait for event")) return DGC_ERR_HIP;
+    float a = 0.f, b = 0.f, c = 0.f, d = 0.f;
+    if (!hip_ok(hipEventElapsedTime(&a, ev[0], ev[1]), "event time") ||
+        !hip_ok(hipEventElapsedTime(&b, ev[1], ev[2]), "event time") ||
+        !hip_ok(hipEventElapsedTime(&c, ev[2], ev[3]), "event time") ||
+        !hip_ok(hipEventElapsedTime(&d, ev[3], ev[4]), "event time"))
+      return DGC_ERR_HIP;
+    *norm_ms += a;
+    *select_ms += b;
+    *stream_ms += c;
+    *emit_ms += d;
+  }
+  h->prof_calls = 0;
+  return DGC_OK;
+}
+
+dgc_status dgc_profile_disable(dgc_handle* h) {
+  if (!h) return DGC_ERR_INVALID_ARG;
+  profile_release(h);
   return DGC_OK;
 }
 
@@ -473,7 +564,9 @@ static dgc_status scatter_regions(dgc_handle* h, float* dense, int32_t num_paylo
   st = sync_workspace(h, workspace, workspace_bytes, out_offsets_host, false, stream);
   if (st != DGC_OK) return st;
   const int64_t* oo = at<int64_t>(workspace, h->lay.out_offsets);
-  const int64_t total = out_offsets_host[h->num_tensors];
+  int64_t total = 0;  // widest region
+  for (int32_t j = 0; j < h->num_tensors; ++j)
+    if (out_offsets_host[j + 1] - out_offsets_host[j] > total) total = out_offsets_host[j + 1] - out_offsets_host[j];
   if (clear) {
     if (!hip_ok(launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, total,
                                kScatterClear, nullptr, stream), "launch scatter kernel"))

@@ -15,12 +15,25 @@ namespace dgc {
 // Streaming pass: one wavefront owns a contiguous run of kWaveTile elements and
 // reads it as kStreamUnroll rounds of one float4 per lane (64 lanes x 16 B =
 // 1 KiB per round, fully coalesced).
-constexpr int kStreamUnroll = 4;
-constexpr int kWaveTile = 64 * 4 * kStreamUnroll;  // 1024 elements
+#ifndef DGC_STREAM_UNROLL
+#define DGC_STREAM_UNROLL 4
+#endif
+constexpr int kStreamUnroll = DGC_STREAM_UNROLL;
+constexpr int kWaveTile = 64 * 4 * kStreamUnroll;  // elements per wavefront
 constexpr int kStreamThreads = 256;                 // 4 wavefronts per workgroup
 constexpr int kStreamWaves = kStreamThreads / 64;
-constexpr int kTileShift = 10;                      // first-tensor table granularity: 1024 elements
-static_assert((1 << kTileShift) == kWaveTile, "tile table granularity must equal the wave tile");
+// Tile table: one int32 per wave tile = index of the tensor that holds the tile's
+// first element, with the top bit set when the tile is not wholly inside one
+// tensor or is the ragged last tile (such tiles take the general path).
+constexpr uint32_t kTileMixed = 0x80000000u;
+
+// Emit pass: a workgroup takes kEmitTiles consecutive wave tiles of one tensor.
+constexpr int kEmitThreads = 256;
+constexpr int kEmitTiles = 32;
+static_assert(kEmitTiles % (kEmitThreads / 64) == 0, "tiles are dealt round-robin to wavefronts");
+
+// Receive side: slots of one tensor region handled by one workgroup.
+constexpr int kScatterChunk = 2048;
 
 // Threshold selection: one workgroup per tensor.
 constexpr int kSelectThreads = 1024;
@@ -53,7 +66,7 @@ struct TensorPlan {
 };
 
 struct WorkspaceLayout {
-  size_t state, partials, offsets, out_offsets, plans, thr, tile_first, total;
+  size_t state, partials, offsets, out_offsets, plans, thr, tile_info, mask, total;
 };
 
 struct SelectArgs {
@@ -77,20 +90,29 @@ struct StreamArgs {
   const float* g;
   float* u;
   float* v;
-  int32_t* out_idx;
-  float* out_val;
+  uint16_t* mask;              // device, 64 words per wave tile
   const int64_t* offsets;      // device, T + 1
-  const int64_t* out_offsets;  // device, T + 1
   const float* thr;            // device, T
-  int32_t* out_counts;         // device, T
-  const int32_t* tile_first;   // device, ceil(n / 1024)
-  DeviceState* state;
+  const uint32_t* tile_info;   // device, ceil(n / kWaveTile), see kTileMixed
+  const DeviceState* state;
   int64_t n;
   int32_t num_tensors;
   float momentum;
   float scale_const;
   int32_t scale_from_state;
   int32_t nesterov;
+};
+
+struct EmitArgs {
+  float* u;
+  float* v;
+  const uint16_t* mask;
+  int32_t* out_idx;
+  float* out_val;
+  const int64_t* offsets;      // device, T + 1
+  const int64_t* out_offsets;  // device, T + 1
+  int32_t* out_counts;         // device, T
+  DeviceState* state;
   int32_t factor_masking;
 };
 
@@ -113,12 +135,14 @@ hipError_t launch_norm(const float* g, int64_t n, DeviceState* state, double* pa
                        double thr_local, float scale_override, hipStream_t stream);
 hipError_t launch_select(const SelectArgs& a, int32_t num_tensors, hipStream_t stream);
 hipError_t launch_stream(const StreamArgs& a, hipStream_t stream);
+hipError_t launch_emit(const EmitArgs& a, int32_t num_tensors, int64_t max_tiles_per_tensor,
+                       hipStream_t stream);
 hipError_t launch_scatter_pairs(float* dense, int64_t n, const PairPayloads& p, int32_t first,
                                 int32_t num, int64_t max_count, ScatterMode mode,
                                 uint32_t* diag_flags, hipStream_t stream);
 hipError_t launch_scatter_regions(float* dense, int64_t n, const RegionPayloads& p, int32_t first,
                                   int32_t num, const int64_t* out_offsets_dev, int32_t num_tensors,
-                                  int64_t total_slots, ScatterMode mode, uint32_t* diag_flags,
+                                  int64_t max_capacity, ScatterMode mode, uint32_t* diag_flags,
                                   hipStream_t stream);
 
 }  // namespace dgc

@@ -266,126 +266,229 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
 }
 
 // ---------------------------------------------------------------------------
-// Fused update + mask + compaction + factor masking
-// (paper: Algorithm 3 from the U, V update to the two masking lines)
+// Streaming pass: momentum correction + mask
+// (paper: Algorithm 3, the U and V update lines and the Mask line)
 // ---------------------------------------------------------------------------
-// A wavefront owns kWaveTile consecutive elements.  Kept elements of each
-// tensor that the tile touches are ranked inside the wavefront by a prefix sum
-// over lanes; lane 0 reserves the slots with one atomic on that tensor's count.
+// A wavefront owns kWaveTile consecutive elements, read as kStreamUnroll rounds
+// of one 16-byte vector per lane.  g, u and v are touched exactly once per
+// iteration, so they are loaded and stored with the non-temporal hint.  The
+// pass writes the pre-mask u', v' and one bit per element (|v'| > thr) and
+// nothing else: no atomics, no scattered stores, nothing that depends on how
+// many elements pass.  The emit pass below turns the bits into the payload and
+// applies the mask to u and v.
+//
+// Mask layout: lane l of the wavefront that owns tile t stores a 16-bit word at
+// mask[t * 64 + l]; bit q = r * 4 + c of it belongs to element
+// t * kWaveTile + r * 256 + l * 4 + c.
+//
+// Tiles that lie inside one tensor (all but a few hundred) take the fast path:
+// one threshold for the whole tile.  Tiles that straddle tensors, and the
+// ragged last tile, take the general path, which finds each element's tensor.
+typedef float vec4 __attribute__((ext_vector_type(4)));
+
+static_assert(kStreamUnroll >= 1 && kStreamUnroll <= 4, "mask words hold at most 16 bits per lane");
+
+__device__ __forceinline__ int64_t tile_element(int64_t tile, int lane, int q) {
+  return tile * kWaveTile + (q >> 2) * 256 + lane * 4 + (q & 3);
+}
+
+// General path for one round of 256 elements starting at `base` (16-byte aligned):
+// returns this lane's four mask bits.
+__device__ __forceinline__ uint32_t stream_round_general(const StreamArgs& a, int64_t base, int lane,
+                                                         float scale, int32_t j) {
+  const float m = a.momentum;
+  const bool nesterov = a.nesterov != 0;
+  const int64_t e0 = base + lane * 4;
+  const int64_t round_end = base + 256 < a.n ? base + 256 : a.n;
+  float u1[4], v1[4];
+  const bool vec = e0 + 4 <= a.n;
+  if (vec) {
+    const vec4 x = *reinterpret_cast<const vec4*>(a.g + e0);
+    const vec4 y = *reinterpret_cast<const vec4*>(a.u + e0);
+    const vec4 z = *reinterpret_cast<const vec4*>(a.v + e0);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) momentum_update(x[c], y[c], z[c], m, scale, nesterov, u1[c], v1[c]);
+  } else {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const bool in = e0 + c < a.n;
+      momentum_update(in ? a.g[e0 + c] : 0.0f, in ? a.u[e0 + c] : 0.0f, in ? a.v[e0 + c] : 0.0f, m,
+                      scale, nesterov, u1[c], v1[c]);
+    }
+  }
+  while (a.offsets[j + 1] <= base) ++j;
+  uint32_t cand = 0;
+  for (; j < a.num_tensors; ++j) {
+    const int64_t lo = a.offsets[j];
+    if (lo >= round_end) break;
+    const int64_t hi = a.offsets[j + 1];
+    const float thr = a.thr[j];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int64_t e = e0 + c;
+      if (e >= lo && e < hi && fabsf(v1[c]) > thr) cand |= 1u << c;
+    }
+  }
+  if (vec) {
+    vec4 uo = {u1[0], u1[1], u1[2], u1[3]};
+    vec4 vo = {v1[0], v1[1], v1[2], v1[3]};
+    *reinterpret_cast<vec4*>(a.u + e0) = uo;
+    *reinterpret_cast<vec4*>(a.v + e0) = vo;
+  } else {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      if (e0 + c < a.n) {
+        a.u[e0 + c] = u1[c];
+        a.v[e0 + c] = v1[c];
+      }
+    }
+  }
+  return cand;
+}
+
 __global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs a) {
+  constexpr int U = kStreamUnroll;
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int64_t tile = (int64_t)blockIdx.x * kStreamWaves + wave;
   const int64_t base = tile * kWaveTile;
   if (base >= a.n) return;
-  const int64_t end = base + kWaveTile < a.n ? base + kWaveTile : a.n;
-  const bool full = base + kWaveTile <= a.n;
+  const uint32_t info = a.tile_info[tile];
   const float scale = a.scale_from_state ? a.state->scale : a.scale_const;
-  const float m = a.momentum;
-  const bool nesterov = a.nesterov != 0;
+  const int32_t j = (int32_t)(info & ~kTileMixed);
 
-  float u1[kStreamUnroll * 4], v1[kStreamUnroll * 4];
-  {
-    float gg[kStreamUnroll * 4], uu[kStreamUnroll * 4], vv[kStreamUnroll * 4];
-#pragma unroll
-    for (int it = 0; it < kStreamUnroll; ++it) {
-      const int64_t e = base + it * 256 + lane * 4;
-      if (full || e + 4 <= a.n) {
-        const float4 x = *reinterpret_cast<const float4*>(a.g + e);
-        const float4 y = *reinterpret_cast<const float4*>(a.u + e);
-        const float4 z = *reinterpret_cast<const float4*>(a.v + e);
-        gg[it * 4 + 0] = x.x; gg[it * 4 + 1] = x.y; gg[it * 4 + 2] = x.z; gg[it * 4 + 3] = x.w;
-        uu[it * 4 + 0] = y.x; uu[it * 4 + 1] = y.y; uu[it * 4 + 2] = y.z; uu[it * 4 + 3] = y.w;
-        vv[it * 4 + 0] = z.x; vv[it * 4 + 1] = z.y; vv[it * 4 + 2] = z.z; vv[it * 4 + 3] = z.w;
-      } else {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          const bool in = e + c < a.n;
-          gg[it * 4 + c] = in ? a.g[e + c] : 0.0f;
-          uu[it * 4 + c] = in ? a.u[e + c] : 0.0f;
-          vv[it * 4 + c] = in ? a.v[e + c] : 0.0f;
-        }
-      }
+  if (info & kTileMixed) {
+    uint32_t cand = 0;
+#pragma unroll 1
+    for (int r = 0; r < U; ++r) {
+      const int64_t rb = base + r * 256;
+      if (rb < a.n) cand |= stream_round_general(a, rb, lane, scale, j) << (r * 4);
     }
-#pragma unroll
-    for (int q = 0; q < kStreamUnroll * 4; ++q)
-      momentum_update(gg[q], uu[q], vv[q], m, scale, nesterov, u1[q], v1[q]);
+    a.mask[tile * 64 + lane] = (uint16_t)cand;
+    return;
   }
 
-  // Tensors touched by this tile (usually one).
-  int32_t j = a.tile_first[base >> kTileShift];
-  while (a.offsets[j + 1] <= base) ++j;
-  uint32_t sent = 0;  // bit q: element q of this lane was written to the payload
-  bool overflow = false;
-  for (; j < a.num_tensors; ++j) {
-    const int64_t lo = a.offsets[j];
-    if (lo >= end) break;
-    const int64_t hi = a.offsets[j + 1];
-    const float thr = a.thr[j];
-    uint32_t cand = 0;
+  // ---- fast path: the whole tile belongs to tensor j and lies inside the buffers ----
+  const float m = a.momentum;
+  const bool nesterov = a.nesterov != 0;
+  const vec4* __restrict__ g4 = reinterpret_cast<const vec4*>(a.g + base) + lane;
+  vec4* __restrict__ u4 = reinterpret_cast<vec4*>(a.u + base) + lane;
+  vec4* __restrict__ v4 = reinterpret_cast<vec4*>(a.v + base) + lane;
+  vec4 x[U], y[U], z[U];
 #pragma unroll
-    for (int q = 0; q < kStreamUnroll * 4; ++q) {
-      const int64_t e = base + (q >> 2) * 256 + lane * 4 + (q & 3);
-      const bool in = e >= lo && e < hi;
-      if (in && fabsf(v1[q]) > thr) cand |= 1u << q;
-    }
-    if (__ballot(cand != 0) == 0ull) continue;
-    const int c = __popc(cand);
-    int incl = c;
-    for (int d = 1; d < 64; d <<= 1) {
-      const int t = __shfl_up(incl, d);
-      if (lane >= d) incl += t;
-    }
-    const int total = __shfl(incl, 63);
-    int slot0 = 0;
-    if (lane == 0) slot0 = atomicAdd(&a.out_counts[j], total);
-    slot0 = __shfl(slot0, 0);
-    const int64_t region = a.out_offsets[j];
-    const int64_t cap = a.out_offsets[j + 1] - region;
-    int64_t slot = (int64_t)slot0 + (incl - c);
+  for (int r = 0; r < U; ++r) {
+    x[r] = __builtin_nontemporal_load(g4 + r * 64);
+    y[r] = __builtin_nontemporal_load(u4 + r * 64);
+    z[r] = __builtin_nontemporal_load(v4 + r * 64);
+  }
+  const float thr = a.thr[j];
+  uint32_t cand = 0;
 #pragma unroll
-    for (int q = 0; q < kStreamUnroll * 4; ++q) {
-      if (cand & (1u << q)) {
-        if (slot < cap) {
-          const int64_t e = base + (q >> 2) * 256 + lane * 4 + (q & 3);
-          a.out_idx[region + slot] = (int32_t)e;
-          a.out_val[region + slot] = v1[q];
-          sent |= 1u << q;
-        } else {
-          overflow = true;
+  for (int r = 0; r < U; ++r) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      float u1, v1;
+      momentum_update(x[r][c], y[r][c], z[r][c], m, scale, nesterov, u1, v1);
+      y[r][c] = u1;
+      z[r][c] = v1;
+      if (fabsf(v1) > thr) cand |= 1u << (r * 4 + c);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < U; ++r) {
+    __builtin_nontemporal_store(y[r], u4 + r * 64);
+    __builtin_nontemporal_store(z[r], v4 + r * 64);
+  }
+  a.mask[tile * 64 + lane] = (uint16_t)cand;
+}
+
+// ---------------------------------------------------------------------------
+// Emit pass: sparse extract + residual + momentum factor masking
+// (paper: Algorithm 3, the three lines after Mask; Section 3.3)
+// ---------------------------------------------------------------------------
+// grid = (chunks, tensors).  A workgroup owns up to kEmitTiles consecutive tiles
+// of one tensor, counts the mask bits that fall inside the tensor, reserves that
+// many slots of the tensor's payload region with ONE atomic, then for every set
+// bit moves v' into the payload and clears v and u.  An element that finds the
+// region full is left untouched (it stays in u, v) and the overflow flag is set.
+__global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
+  constexpr int kWaves = kEmitThreads / 64;
+  constexpr int kPerWave = kEmitTiles / kWaves;
+  constexpr int kBits = kStreamUnroll * 4;
+  __shared__ int wave_tot[kWaves];
+  __shared__ int block_base;
+
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int j = blockIdx.y;
+  const int64_t lo = a.offsets[j];
+  const int64_t hi = a.offsets[j + 1];
+  const int64_t t0 = lo / kWaveTile;
+  const int64_t t1 = (hi - 1) / kWaveTile;
+  const int64_t first = t0 + (int64_t)blockIdx.x * kEmitTiles;
+  if (first > t1) return;
+
+  uint32_t word[kPerWave];
+  int cnt = 0;
+#pragma unroll
+  for (int i = 0; i < kPerWave; ++i) {
+    const int64_t t = first + wave + i * kWaves;
+    uint32_t w = 0;
+    if (t <= t1) {
+      w = a.mask[t * 64 + lane];
+      if (t * kWaveTile < lo || (t + 1) * kWaveTile > hi) {  // tile shared with a neighbour tensor
+        uint32_t keep = 0;
+        for (int q = 0; q < kBits; ++q) {
+          const int64_t e = tile_element(t, lane, q);
+          if (e >= lo && e < hi) keep |= 1u << q;
         }
-        ++slot;
+        w &= keep;
       }
+    }
+    word[i] = w;
+    cnt += __popc(w);
+  }
+  int incl = cnt;
+  for (int d = 1; d < 64; d <<= 1) {
+    const int t = __shfl_up(incl, d);
+    if (lane >= d) incl += t;
+  }
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  int before = 0, total = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    const int t = wave_tot[w];
+    if (w < wave) before += t;
+    total += t;
+  }
+  if (total == 0) return;
+  if (threadIdx.x == 0) block_base = atomicAdd(&a.out_counts[j], total);
+  __syncthreads();
+  const int64_t region = a.out_offsets[j];
+  const int64_t cap = a.out_offsets[j + 1] - region;
+  int64_t slot = (int64_t)block_base + before + (incl - cnt);
+  bool overflow = false;
+#pragma unroll
+  for (int i = 0; i < kPerWave; ++i) {
+    uint32_t w = word[i];
+    const int64_t t = first + wave + i * kWaves;
+    while (w) {
+      const int q = __ffs(w) - 1;
+      w &= w - 1;
+      if (slot < cap) {
+        const int64_t e = tile_element(t, lane, q);
+        a.out_idx[region + slot] = (int32_t)e;
+        a.out_val[region + slot] = a.v[e];
+        a.v[e] = 0.0f;
+        if (a.factor_masking) a.u[e] = 0.0f;
+      } else {
+        overflow = true;
+      }
+      ++slot;
     }
   }
   if (overflow) atomicOr(&a.state->flags, (uint32_t)DGC_DIAG_OVERFLOW);
-
-  // Momentum factor masking: the same mask clears v and u (paper: Section 3.3).
-#pragma unroll
-  for (int q = 0; q < kStreamUnroll * 4; ++q) {
-    if (sent & (1u << q)) {
-      v1[q] = 0.0f;
-      if (a.factor_masking) u1[q] = 0.0f;
-    }
-  }
-#pragma unroll
-  for (int it = 0; it < kStreamUnroll; ++it) {
-    const int64_t e = base + it * 256 + lane * 4;
-    if (full || e + 4 <= a.n) {
-      *reinterpret_cast<float4*>(a.u + e) =
-          make_float4(u1[it * 4 + 0], u1[it * 4 + 1], u1[it * 4 + 2], u1[it * 4 + 3]);
-      *reinterpret_cast<float4*>(a.v + e) =
-          make_float4(v1[it * 4 + 0], v1[it * 4 + 1], v1[it * 4 + 2], v1[it * 4 + 3]);
-    } else {
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        if (e + c < a.n) {
-          a.u[e + c] = u1[it * 4 + c];
-          a.v[e + c] = v1[it * 4 + c];
-        }
-      }
-    }
-  }
 }
 
 // ---------------------------------------------------------------------------
@@ -419,28 +522,26 @@ __global__ __launch_bounds__(256) void scatter_pairs_kernel(float* dense, int64_
     scatter_one(dense, n, idx[q], mode == kScatterClear ? 0.0f : val[q], mode, diag_flags);
 }
 
-// Payloads in the per-tensor region layout written by the streaming pass: a
-// thread per slot, the tensor found by bisection over the region starts.
+// Payloads in the per-tensor region layout written by the emit pass.
+// grid = (chunks, tensors, payloads): a workgroup takes kScatterChunk slots of one
+// tensor's region of one payload and leaves at once when the region holds fewer.
 __global__ __launch_bounds__(256) void scatter_regions_kernel(float* dense, int64_t n,
                                                               RegionPayloads p, int32_t first,
                                                               const int64_t* __restrict__ out_offsets,
-                                                              int32_t num_tensors, int64_t total_slots,
                                                               ScatterMode mode, uint32_t* diag_flags) {
-  const int w = first + blockIdx.y;
-  const int32_t* __restrict__ idx = p.idx[w];
-  const float* __restrict__ val = p.val[w];
-  const int32_t* __restrict__ counts = p.counts[w];
-  const int64_t stride = (int64_t)gridDim.x * 256;
-  for (int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x; s < total_slots; s += stride) {
-    int32_t lo = 0, hi = num_tensors;  // last j with out_offsets[j] <= s
-    while (hi - lo > 1) {
-      const int32_t mid = (lo + hi) >> 1;
-      if (out_offsets[mid] <= s) lo = mid; else hi = mid;
-    }
-    const int64_t local = s - out_offsets[lo];
-    if (local < (int64_t)counts[lo])
-      scatter_one(dense, n, idx[s], mode == kScatterClear ? 0.0f : val[s], mode, diag_flags);
-  }
+  const int w = first + blockIdx.z;
+  const int j = blockIdx.y;
+  const int64_t region = out_offsets[j];
+  const int64_t cap = out_offsets[j + 1] - region;
+  int64_t count = p.counts[w][j];
+  if (count > cap) count = cap;
+  const int64_t begin = (int64_t)blockIdx.x * kScatterChunk;
+  if (begin >= count) return;
+  const int64_t end = begin + kScatterChunk < count ? begin + kScatterChunk : count;
+  const int32_t* __restrict__ idx = p.idx[w] + region;
+  const float* __restrict__ val = mode == kScatterClear ? nullptr : p.val[w] + region;
+  for (int64_t s = begin + threadIdx.x; s < end; s += 256)
+    scatter_one(dense, n, idx[s], mode == kScatterClear ? 0.0f : val[s], mode, diag_flags);
 }
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -472,6 +573,14 @@ hipError_t launch_stream(const StreamArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
+hipError_t launch_emit(const EmitArgs& a, int32_t num_tensors, int64_t max_tiles_per_tensor,
+                       hipStream_t stream) {
+  const int64_t chunks = ceil_div(max_tiles_per_tensor, kEmitTiles);
+  hipLaunchKernelGGL(emit_kernel, dim3((unsigned)chunks, (unsigned)num_tensors), dim3(kEmitThreads), 0,
+                     stream, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_scatter_pairs(float* dense, int64_t n, const PairPayloads& p, int32_t first,
                                 int32_t num, int64_t max_count, ScatterMode mode,
                                 uint32_t* diag_flags, hipStream_t stream) {
@@ -485,14 +594,13 @@ hipError_t launch_scatter_pairs(float* dense, int64_t n, const PairPayloads& p, 
 
 hipError_t launch_scatter_regions(float* dense, int64_t n, const RegionPayloads& p, int32_t first,
                                   int32_t num, const int64_t* out_offsets_dev, int32_t num_tensors,
-                                  int64_t total_slots, ScatterMode mode, uint32_t* diag_flags,
+                                  int64_t max_capacity, ScatterMode mode, uint32_t* diag_flags,
                                   hipStream_t stream) {
-  if (num <= 0 || total_slots <= 0) return hipSuccess;
-  int64_t chunks = ceil_div(total_slots, 256 * 2);
-  if (chunks > 8192) chunks = 8192;
-  hipLaunchKernelGGL(scatter_regions_kernel, dim3((unsigned)chunks, (unsigned)num), dim3(256), 0,
-                     stream, dense, n, p, first, out_offsets_dev, num_tensors, total_slots, mode,
-                     diag_flags);
+  if (num <= 0 || max_capacity <= 0) return hipSuccess;
+  const int64_t chunks = ceil_div(max_capacity, kScatterChunk);
+  if (chunks > 65535 || num_tensors > 65535) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(scatter_regions_kernel, dim3((unsigned)chunks, (unsigned)num_tensors, (unsigned)num),
+                     dim3(256), 0, stream, dense, n, p, first, out_offsets_dev, mode, diag_flags);
   return hipGetLastError();
 }
 
