@@ -23,7 +23,7 @@ struct dgc_handle {
   std::vector<int64_t> k;            // T
   std::vector<int64_t> draws;        // T
   std::vector<uint32_t> tile_info;   // ceil(n / kWaveTile)
-  int64_t max_tiles_per_tensor = 0;  // grid width of the emit pass
+  std::vector<EmitBlock> emit_blocks;  // work list of the emit pass
   WorkspaceLayout lay{};
   // what the bound workspace currently holds
   void* ws = nullptr;
@@ -118,6 +118,7 @@ void build_layout(dgc_handle* h) {
   l.plans = off;        off = align_up(off + sizeof(TensorPlan) * T);
   l.thr = off;          off = align_up(off + sizeof(float) * T);
   l.tile_info = off;    off = align_up(off + sizeof(uint32_t) * tiles);
+  l.emit_blocks = off;  off = align_up(off + sizeof(EmitBlock) * h->emit_blocks.size());
   l.mask = off;         off = align_up(off + sizeof(uint16_t) * 64 * tiles);
   l.total = off;
 }
@@ -161,6 +162,10 @@ dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_
     if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.tile_info), h->tile_info.data(),
                                sizeof(uint32_t) * h->tile_info.size(), hipMemcpyHostToDevice, stream),
                 "upload tile table"))
+      return DGC_ERR_HIP;
+    if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.emit_blocks), h->emit_blocks.data(),
+                               sizeof(EmitBlock) * h->emit_blocks.size(), hipMemcpyHostToDevice, stream),
+                "upload emit work list"))
       return DGC_ERR_HIP;
     h->ws_static_valid = true;
   }
@@ -262,8 +267,9 @@ dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tenso
       h->tile_info[(size_t)t] = (uint32_t)j | (whole ? 0u : kTileMixed);
     }
     for (int32_t t = 0; t < num_tensors; ++t) {
-      const int64_t nt = (h->offsets[t + 1] - 1) / kWaveTile - h->offsets[t] / kWaveTile + 1;
-      if (nt > h->max_tiles_per_tensor) h->max_tiles_per_tensor = nt;
+      const int64_t t0 = h->offsets[t] / kWaveTile;
+      const int64_t t1 = (h->offsets[t + 1] - 1) / kWaveTile;
+      for (int64_t f = t0; f <= t1; f += kEmitTiles) h->emit_blocks.push_back(EmitBlock{t, (int32_t)f});
     }
     h->ws_out_offsets.resize(num_tensors + 1);
   } catch (...) {
@@ -419,6 +425,7 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   if (ev && !hip_ok(hipEventRecord(ev[3], stream), "record event")) return DGC_ERR_HIP;
 
   EmitArgs ea{};
+  ea.blocks = at<EmitBlock>(workspace, h->lay.emit_blocks);
   ea.u = u;
   ea.v = v;
   ea.mask = ta.mask;
@@ -429,7 +436,7 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   ea.out_counts = out_counts;
   ea.state = state;
   ea.factor_masking = (c.flags & DGC_FLAG_NO_FACTOR_MASKING) ? 0 : 1;
-  if (!hip_ok(launch_emit(ea, h->num_tensors, h->max_tiles_per_tensor, stream), "launch emit kernel"))
+  if (!hip_ok(launch_emit(ea, (int32_t)h->emit_blocks.size(), stream), "launch emit kernel"))
     return DGC_ERR_HIP;
   if (ev && !hip_ok(hipEventRecord(ev[4], stream), "record event")) return DGC_ERR_HIP;
   return DGC_OK;

@@ -33,12 +33,13 @@ constexpr int kEmitTiles = 32;
 static_assert(kEmitTiles % (kEmitThreads / 64) == 0, "tiles are dealt round-robin to wavefronts");
 
 // Receive side: slots of one tensor region handled by one workgroup.
-constexpr int kScatterChunk = 2048;
+constexpr int kScatterChunk = 4096;
 
 // Threshold selection: one workgroup per tensor.
 constexpr int kSelectThreads = 1024;
 constexpr int kSelectKeyCap = 32768;  // candidate keys kept in LDS (128 KiB of the 160 KiB)
 constexpr int kSelectBins = 2048;     // 11-bit digits
+constexpr int kSelectInFlight = 8;    // candidates each thread gathers before using any
 
 // Clipping norm: a fixed number of partial sums keeps the result reproducible.
 constexpr int kNormThreads = 256;
@@ -66,7 +67,7 @@ struct TensorPlan {
 };
 
 struct WorkspaceLayout {
-  size_t state, partials, offsets, out_offsets, plans, thr, tile_info, mask, total;
+  size_t state, partials, offsets, out_offsets, plans, thr, tile_info, emit_blocks, mask, total;
 };
 
 struct SelectArgs {
@@ -103,7 +104,13 @@ struct StreamArgs {
   int32_t nesterov;
 };
 
+struct EmitBlock {
+  int32_t tensor;
+  int32_t first_tile;  // first wave tile of the workgroup's run inside that tensor
+};
+
 struct EmitArgs {
+  const EmitBlock* blocks;     // device, one entry per workgroup
   float* u;
   float* v;
   const uint16_t* mask;
@@ -135,8 +142,7 @@ hipError_t launch_norm(const float* g, int64_t n, DeviceState* state, double* pa
                        double thr_local, float scale_override, hipStream_t stream);
 hipError_t launch_select(const SelectArgs& a, int32_t num_tensors, hipStream_t stream);
 hipError_t launch_stream(const StreamArgs& a, hipStream_t stream);
-hipError_t launch_emit(const EmitArgs& a, int32_t num_tensors, int64_t max_tiles_per_tensor,
-                       hipStream_t stream);
+hipError_t launch_emit(const EmitArgs& a, int32_t num_blocks, hipStream_t stream);
 hipError_t launch_scatter_pairs(float* dense, int64_t n, const PairPayloads& p, int32_t first,
                                 int32_t num, int64_t max_count, ScatterMode mode,
                                 uint32_t* diag_flags, hipStream_t stream);

@@ -137,13 +137,6 @@ struct Candidates {
     const uint32_t blk = __umulhi(r, nblocks);
     return ((int64_t)blk << block_shift) + (p & ((1 << block_shift) - 1));
   }
-  // Bit pattern of |v'| at candidate p: order-isomorphic to the magnitude.
-  __device__ __forceinline__ uint32_t key_at(int32_t p) const {
-    const int64_t e = offset + position(p);
-    float u1, v1;
-    momentum_update(g[e], u[e], v[e], m, scale, nesterov, u1, v1);
-    return __float_as_uint(v1) & 0x7FFFFFFFu;
-  }
 };
 
 // One workgroup per tensor.  Three histogram passes (11 + 11 + 9 bits, most
@@ -208,21 +201,31 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
     for (int i = tid; i < kSelectBins; i += kSelectThreads) hist[i] = 0;
     __syncthreads();
     if (pass == 0 || !cached) {
-      // four candidates per thread in flight: the gathers are latency-bound
-      for (int32_t p0 = tid; p0 < count; p0 += 4 * kSelectThreads) {
-        uint32_t k[4];
+      // kSelectInFlight candidates per thread are gathered before any is used: the
+      // gathers are random 64-byte reads, so latency, not bandwidth, sets the pace.
+      for (int32_t p0 = tid; p0 < count; p0 += kSelectInFlight * kSelectThreads) {
+        float gg[kSelectInFlight], uu[kSelectInFlight], vv[kSelectInFlight];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < kSelectInFlight; ++q) {
           const int32_t p = p0 + q * kSelectThreads;
-          k[q] = p < count ? c.key_at(p) : 0u;
+          gg[q] = uu[q] = vv[q] = 0.0f;
+          if (p < count) {
+            const int64_t e = c.offset + c.position(p);
+            gg[q] = c.g[e];
+            uu[q] = c.u[e];
+            vv[q] = c.v[e];
+          }
         }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < kSelectInFlight; ++q) {
           const int32_t p = p0 + q * kSelectThreads;
           if (p < count) {
-            if (cached) keys[p] = k[q];
-            if (pass == 0 || (k[q] >> (shift + bits)) == prefix)
-              atomicAdd(&hist[(k[q] >> shift) & digit_mask], 1u);
+            float u1, v1;
+            momentum_update(gg[q], uu[q], vv[q], c.m, c.scale, c.nesterov, u1, v1);
+            const uint32_t k = __float_as_uint(v1) & 0x7FFFFFFFu;
+            if (cached) keys[p] = k;
+            if (pass == 0 || (k >> (shift + bits)) == prefix)
+              atomicAdd(&hist[(k >> shift) & digit_mask], 1u);
           }
         }
       }
@@ -406,8 +409,9 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs a) {
 // Emit pass: sparse extract + residual + momentum factor masking
 // (paper: Algorithm 3, the three lines after Mask; Section 3.3)
 // ---------------------------------------------------------------------------
-// grid = (chunks, tensors).  A workgroup owns up to kEmitTiles consecutive tiles
-// of one tensor, counts the mask bits that fall inside the tensor, reserves that
+// One workgroup per entry of a host-built list of (tensor, first tile): it owns up
+// to kEmitTiles consecutive tiles of that tensor, counts the mask bits that fall
+// inside the tensor reserves that
 // many slots of the tensor's payload region with ONE atomic, then for every set
 // bit moves v' into the payload and clears v and u.  An element that finds the
 // region full is left untouched (it stays in u, v) and the overflow flag is set.
@@ -420,13 +424,12 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
 
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  const int j = blockIdx.y;
+  const EmitBlock blk = a.blocks[blockIdx.x];
+  const int j = blk.tensor;
   const int64_t lo = a.offsets[j];
   const int64_t hi = a.offsets[j + 1];
-  const int64_t t0 = lo / kWaveTile;
   const int64_t t1 = (hi - 1) / kWaveTile;
-  const int64_t first = t0 + (int64_t)blockIdx.x * kEmitTiles;
-  if (first > t1) return;
+  const int64_t first = blk.first_tile;
 
   uint32_t word[kPerWave];
   int cnt = 0;
@@ -540,8 +543,19 @@ __global__ __launch_bounds__(256) void scatter_regions_kernel(float* dense, int6
   const int64_t end = begin + kScatterChunk < count ? begin + kScatterChunk : count;
   const int32_t* __restrict__ idx = p.idx[w] + region;
   const float* __restrict__ val = mode == kScatterClear ? nullptr : p.val[w] + region;
-  for (int64_t s = begin + threadIdx.x; s < end; s += 256)
-    scatter_one(dense, n, idx[s], mode == kScatterClear ? 0.0f : val[s], mode, diag_flags);
+  for (int64_t s0 = begin + threadIdx.x; s0 < end; s0 += 4 * 256) {
+    int32_t i[4];
+    float x[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int64_t s = s0 + q * 256;
+      i[q] = s < end ? idx[s] : 0;
+      x[q] = (s < end && mode != kScatterClear) ? val[s] : 0.0f;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (s0 + q * 256 < end) scatter_one(dense, n, i[q], x[q], mode, diag_flags);
+  }
 }
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -573,11 +587,8 @@ hipError_t launch_stream(const StreamArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-hipError_t launch_emit(const EmitArgs& a, int32_t num_tensors, int64_t max_tiles_per_tensor,
-                       hipStream_t stream) {
-  const int64_t chunks = ceil_div(max_tiles_per_tensor, kEmitTiles);
-  hipLaunchKernelGGL(emit_kernel, dim3((unsigned)chunks, (unsigned)num_tensors), dim3(kEmitThreads), 0,
-                     stream, a);
+hipError_t launch_emit(const EmitArgs& a, int32_t num_blocks, hipStream_t stream) {
+  hipLaunchKernelGGL(emit_kernel, dim3((unsigned)num_blocks), dim3(kEmitThreads), 0, stream, a);
   return hipGetLastError();
 }
 
