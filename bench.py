@@ -47,6 +47,7 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sample-block", type=int, default=None, help="override dgc_config.sample_block")
     ap.add_argument("--profile-only", action="store_true",
                     help="skip the CPU baseline and the event-instrumented pass (for rocprofv3 runs)")
     return ap.parse_args()
@@ -111,6 +112,8 @@ def main():
     seed = 2025
     scales = S.tensor_scales(gs, seed)
     kw = dict(momentum=0.9, density=0.001, seed=1, num_workers=N_WORKERS)
+    if args.sample_block:
+        kw["sample_block"] = args.sample_block
 
     dgc = B.Dgc(B.make_config(**kw), gs.offsets)
     layout = dgc.dgc_recommended_payload_layout(0.001)
@@ -220,7 +223,7 @@ def main():
             "ms_per_step_with_events": round(profiled_ms, 5),
         }
 
-    counts = int(fresh[0][2].sum().item())
+    counts = max(1, int(fresh[0][2].sum().item()))
     out = {
         "metric": "dense gradient elements/s for compress+decompress",
         "value": n / (ms_per_step * 1e-3),

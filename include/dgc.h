@@ -71,7 +71,7 @@ typedef struct dgc_config {
   double sample_ratio;   /* wanted sample size as a fraction of n_j (0.01)           */
   int32_t sample_min;    /* lower clamp of the sample size (4096)                    */
   int32_t sample_max;    /* upper clamp of the sample size (32768)                   */
-  int32_t sample_block;  /* consecutive elements per draw, power of two <= 64 (16)   */
+  int32_t sample_block;  /* consecutive elements per draw, power of two <= 64 (32)   */
   float scale_override;  /* test hook: NaN = unused, else replaces the clip scale    */
   uint64_t seed;         /* seed of the counter-based sample positions               */
 } dgc_config;
@@ -85,7 +85,7 @@ typedef struct dgc_diagnostics {
 typedef struct dgc_handle dgc_handle;
 
 /* Fill *cfg with m = 0.9, no clipping, N = 1, d = 0.001, sampling 1 % clamped to
- * [4096, 32768] in blocks of 16, seed 0. */
+ * [4096, 32768] in blocks of 32, seed 0. */
 dgc_status dgc_config_default(dgc_config* cfg);
 
 /* Text for a status code (static storage). */

@@ -68,7 +68,7 @@ class OracleConfig:
     sample_ratio: float = 0.01       # Section 5: 0.1 % .. 1 %
     sample_min: int = 4096
     sample_max: int = 32768
-    sample_block: int = 16           # consecutive elements per draw
+    sample_block: int = 32           # consecutive elements per draw (one 128-byte line)
     seed: int = 0
     nesterov: bool = False           # Algorithm 4 instead of Algorithm 3
     factor_masking: bool = True      # Section 3.3; False = ablation / Eq. 3 limit

@@ -16,7 +16,8 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libdgc.so")
+# DGC_LIBRARY selects another build of the library (e.g. one compiled with different tile constants).
+LIB_PATH = os.environ.get("DGC_LIBRARY") or os.path.join(HERE, "libdgc.so")
 
 DGC_OK = 0
 DGC_ERR_INVALID_ARG = -1

@@ -119,6 +119,7 @@ void build_layout(dgc_handle* h) {
   l.thr = off;          off = align_up(off + sizeof(float) * T);
   l.tile_info = off;    off = align_up(off + sizeof(uint32_t) * tiles);
   l.emit_blocks = off;  off = align_up(off + sizeof(EmitBlock) * h->emit_blocks.size());
+  l.counters = off;     off = align_up(off + sizeof(uint32_t) * kCounterStride * T);
   l.mask = off;         off = align_up(off + sizeof(uint16_t) * 64 * tiles);
   l.total = off;
 }
@@ -154,6 +155,10 @@ dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_
   if (!h->ws_static_valid) {
     if (!hip_ok(hipMemsetAsync(at<char>(ws, h->lay.state), 0, sizeof(DeviceState), stream),
                 "clear workspace state"))
+      return DGC_ERR_HIP;
+    if (!hip_ok(hipMemsetAsync(at<char>(ws, h->lay.counters), 0, sizeof(uint32_t) * kCounterStride * T,
+                               stream),
+                "clear emit counters"))
       return DGC_ERR_HIP;
     if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.offsets), h->offsets.data(),
                                sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, stream),
@@ -222,7 +227,7 @@ dgc_status dgc_config_default(dgc_config* cfg) {
   cfg->sample_ratio = 0.01;
   cfg->sample_min = 4096;
   cfg->sample_max = 32768;
-  cfg->sample_block = 16;
+  cfg->sample_block = 32;
   cfg->scale_override = std::nanf("");
   cfg->seed = 0;
   return DGC_OK;
@@ -269,7 +274,8 @@ dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tenso
     for (int32_t t = 0; t < num_tensors; ++t) {
       const int64_t t0 = h->offsets[t] / kWaveTile;
       const int64_t t1 = (h->offsets[t + 1] - 1) / kWaveTile;
-      for (int64_t f = t0; f <= t1; f += kEmitTiles) h->emit_blocks.push_back(EmitBlock{t, (int32_t)f});
+      const int32_t nb = (int32_t)((t1 - t0) / kEmitTiles + 1);
+      for (int64_t f = t0; f <= t1; f += kEmitTiles) h->emit_blocks.push_back(EmitBlock{t, (int32_t)f, nb, 0});
     }
     h->ws_out_offsets.resize(num_tensors + 1);
   } catch (...) {
@@ -391,7 +397,6 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   sa.state = state;
   sa.thr = at<float>(workspace, h->lay.thr);
   sa.out_thr = out_thr;
-  sa.out_counts = out_counts;
   sa.momentum = c.momentum;
   sa.scale_const = scale_const;
   sa.scale_from_state = clip ? 1 : 0;
@@ -426,6 +431,7 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
 
   EmitArgs ea{};
   ea.blocks = at<EmitBlock>(workspace, h->lay.emit_blocks);
+  ea.counters = at<uint32_t>(workspace, h->lay.counters);
   ea.u = u;
   ea.v = v;
   ea.mask = ta.mask;

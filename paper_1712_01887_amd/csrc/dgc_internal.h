@@ -29,15 +29,21 @@ constexpr uint32_t kTileMixed = 0x80000000u;
 
 // Emit pass: a workgroup takes kEmitTiles consecutive wave tiles of one tensor.
 constexpr int kEmitThreads = 256;
-constexpr int kEmitTiles = 32;
+constexpr int kEmitElements = 32768;                  // elements per workgroup
+constexpr int kEmitTiles = kEmitElements / kWaveTile;
 static_assert(kEmitTiles % (kEmitThreads / 64) == 0, "tiles are dealt round-robin to wavefronts");
+constexpr int kEmitList = 4096;                       // elements listed in LDS at a time
+// Per-tensor counters of the emit pass live one per 128-byte line so that atomics
+// on different tensors do not serialise on a shared line.
+constexpr int kCounterStride = 32;  // uint32 words
 
 // Receive side: slots of one tensor region handled by one workgroup.
 constexpr int kScatterChunk = 4096;
 
 // Threshold selection: one workgroup per tensor.
 constexpr int kSelectThreads = 1024;
-constexpr int kSelectKeyCap = 32768;  // candidate keys kept in LDS (128 KiB of the 160 KiB)
+constexpr int kSelectRegKeys = 32;    // candidate keys a thread keeps in registers (32 * 1024 in all)
+constexpr int kSelectDirect = 256;    // a bin with at most this many members is ranked directly
 constexpr int kSelectBins = 2048;     // 11-bit digits
 constexpr int kSelectInFlight = 8;    // candidates each thread gathers before using any
 
@@ -67,7 +73,7 @@ struct TensorPlan {
 };
 
 struct WorkspaceLayout {
-  size_t state, partials, offsets, out_offsets, plans, thr, tile_info, emit_blocks, mask, total;
+  size_t state, partials, offsets, out_offsets, plans, thr, tile_info, emit_blocks, counters, mask, total;
 };
 
 struct SelectArgs {
@@ -78,7 +84,6 @@ struct SelectArgs {
   DeviceState* state;
   float* thr;
   float* out_thr;       // may be null
-  int32_t* out_counts;  // zeroed here for the streaming pass
   float momentum;
   float scale_const;
   int32_t scale_from_state;  // 1: the norm kernel ran and left the scale in `state`
@@ -106,11 +111,14 @@ struct StreamArgs {
 
 struct EmitBlock {
   int32_t tensor;
-  int32_t first_tile;  // first wave tile of the workgroup's run inside that tensor
+  int32_t first_tile;     // first wave tile of the workgroup's run inside that tensor
+  int32_t tensor_blocks;  // workgroups that share this tensor
+  int32_t pad;
 };
 
 struct EmitArgs {
   const EmitBlock* blocks;     // device, one entry per workgroup
+  uint32_t* counters;          // device, kCounterStride words per tensor, zero between calls
   float* u;
   float* v;
   const uint16_t* mask;

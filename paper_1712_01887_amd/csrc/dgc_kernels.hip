@@ -139,23 +139,78 @@ struct Candidates {
   }
 };
 
-// One workgroup per tensor.  Three histogram passes (11 + 11 + 9 bits, most
-// significant first) over the candidate keys find the key of a given
-// descending rank exactly.  Keys are computed once and kept in LDS when they
-// fit; otherwise every pass recomputes them from g, u, v.
-__global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
-  __shared__ uint32_t keys[kSelectKeyCap];
-  __shared__ uint32_t hist[kSelectBins];
-  __shared__ uint32_t wave_tot[kSelectThreads / 64];
-  __shared__ uint32_t sel_bin, sel_above;
+// One workgroup per tensor finds the candidate key of a given descending rank
+// exactly.  Keys are the bit patterns of |v'| (order-isomorphic to the
+// magnitudes).  Up to three histogram passes over 11 + 11 + 9 key bits, most
+// significant first, narrow the key down; as soon as the bin that holds the
+// rank has few enough members they are gathered and ranked directly, which at
+// the paper's densities happens after the first pass.
+//
+// Up to kSelectRegKeys * kSelectThreads candidates live in registers (each
+// thread gathers its own once and keeps them); a larger candidate set (exact
+// selection on a big tensor) is re-evaluated from g, u, v in every pass.
+struct SelectShared {
+  uint32_t hist[kSelectBins];
+  uint32_t wave_tot[kSelectThreads / 64];
+  uint32_t surv[kSelectDirect];
+  uint32_t sel_bin, sel_above, sel_count, surv_n, result;
+};
 
-  const int tid = threadIdx.x;
+// After a histogram pass: the bin that holds descending rank `rank`, how many
+// candidates lie above it, and how many it holds.  Every thread returns the same.
+__device__ __forceinline__ void find_bin(SelectShared& sh, int tid, uint32_t rank, uint32_t& bin,
+                                         uint32_t& above_out, uint32_t& members) {
   const int lane = tid & 63;
   const int wave = tid >> 6;
+  const uint32_t h0 = sh.hist[2 * tid];
+  const uint32_t h1 = sh.hist[2 * tid + 1];
+  const uint32_t local = h0 + h1;
+  uint32_t incl = local;  // suffix sum: this thread's pair of bins and everything above
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t t = __shfl_down(incl, d);
+    if (lane + d < 64) incl += t;
+  }
+  if (lane == 0) sh.wave_tot[wave] = incl;
+  __syncthreads();
+  uint32_t above = incl - local;
+  for (int w = wave + 1; w < kSelectThreads / 64; ++w) above += sh.wave_tot[w];
+  if (above <= rank && rank < above + h1) {
+    sh.sel_bin = 2 * tid + 1;
+    sh.sel_above = above;
+    sh.sel_count = h1;
+  } else if (above + h1 <= rank && rank < above + local) {
+    sh.sel_bin = 2 * tid;
+    sh.sel_above = above + h1;
+    sh.sel_count = h0;
+  }
+  __syncthreads();
+  bin = sh.sel_bin;
+  above_out = sh.sel_above;
+  members = sh.sel_count;
+}
+
+// The `m` <= kSelectDirect keys in sh.surv: the one of descending rank `rank`.
+__device__ __forceinline__ uint32_t rank_directly(SelectShared& sh, int tid, uint32_t m, uint32_t rank) {
+  if (tid < (int)m) {
+    const uint32_t x = sh.surv[tid];
+    uint32_t greater = 0, equal = 0;
+    for (uint32_t i = 0; i < m; ++i) {
+      const uint32_t y = sh.surv[i];
+      greater += y > x;
+      equal += y == x;
+    }
+    if (greater <= rank && rank < greater + equal) sh.result = x;  // ties write the same value
+  }
+  __syncthreads();
+  return sh.result;
+}
+
+__global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
+  __shared__ SelectShared sh;
+  const int tid = threadIdx.x;
   const int j = blockIdx.x;
   const TensorPlan plan = a.plans[j];
 
-  if (tid == 0) a.out_counts[j] = 0;
   if (tid == 0 && j == 0 && !a.scale_from_state) {  // no norm kernel ran: start a clean record
     a.state->norm = __longlong_as_double(0x7FF8000000000000ll);
     a.state->scale = a.scale_const;
@@ -189,20 +244,99 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   }
 
   const int32_t count = plan.count;
-  const bool cached = count <= kSelectKeyCap;
   uint32_t prefix = 0;
   uint32_t rank = (uint32_t)plan.rank;
+  uint32_t thr_bits = 0;
 
-#pragma unroll 1
-  for (int pass = 0; pass < 3; ++pass) {
-    const int shift = pass == 0 ? 20 : (pass == 1 ? 9 : 0);
-    const int bits = pass == 2 ? 9 : 11;
-    const uint32_t digit_mask = (1u << bits) - 1u;
-    for (int i = tid; i < kSelectBins; i += kSelectThreads) hist[i] = 0;
+  if (count <= kSelectRegKeys * kSelectThreads) {
+    // ---- candidates in registers ------------------------------------------------
+    constexpr uint32_t kNoKey = 0xFFFFFFFFu;  // real keys have the sign bit clear
+    uint32_t key[kSelectRegKeys];
+#pragma unroll
+    for (int i = 0; i < kSelectRegKeys; ++i) key[i] = kNoKey;
+    for (int i = tid; i < kSelectBins; i += kSelectThreads) sh.hist[i] = 0;
     __syncthreads();
-    if (pass == 0 || !cached) {
-      // kSelectInFlight candidates per thread are gathered before any is used: the
-      // gathers are random 64-byte reads, so latency, not bandwidth, sets the pace.
+    // Gather: kSelectInFlight candidates per thread are loaded before any is used; the
+    // gathers are random cache-line reads, so latency, not bandwidth, sets the pace.
+#pragma unroll
+    for (int r = 0; r < kSelectRegKeys / kSelectInFlight; ++r) {
+      if (r * kSelectInFlight * kSelectThreads < count) {  // uniform
+        float gg[kSelectInFlight], uu[kSelectInFlight], vv[kSelectInFlight];
+#pragma unroll
+        for (int q = 0; q < kSelectInFlight; ++q) {
+          const int32_t p = tid + (r * kSelectInFlight + q) * kSelectThreads;
+          gg[q] = uu[q] = vv[q] = 0.0f;
+          if (p < count) {
+            const int64_t e = c.offset + c.position(p);
+            gg[q] = c.g[e];
+            uu[q] = c.u[e];
+            vv[q] = c.v[e];
+          }
+        }
+#pragma unroll
+        for (int q = 0; q < kSelectInFlight; ++q) {
+          const int32_t p = tid + (r * kSelectInFlight + q) * kSelectThreads;
+          if (p < count) {
+            float u1, v1;
+            momentum_update(gg[q], uu[q], vv[q], c.m, c.scale, c.nesterov, u1, v1);
+            const uint32_t k = __float_as_uint(v1) & 0x7FFFFFFFu;
+            key[r * kSelectInFlight + q] = k;
+            atomicAdd(&sh.hist[k >> 20], 1u);
+          }
+        }
+      }
+    }
+    __syncthreads();
+    int consumed = 0;  // key bits fixed so far (below the sign bit)
+#pragma unroll 1
+    for (int pass = 0; pass < 3; ++pass) {
+      const int bits = pass == 2 ? 9 : 11;
+      const int shift = 31 - consumed - bits;
+      if (pass > 0) {
+        for (int i = tid; i < kSelectBins; i += kSelectThreads) sh.hist[i] = 0;
+        __syncthreads();
+        const uint32_t digit_mask = (1u << bits) - 1u;
+#pragma unroll
+        for (int i = 0; i < kSelectRegKeys; ++i) {
+          const uint32_t k = key[i];
+          if (k != kNoKey && (k >> (shift + bits)) == prefix)
+            atomicAdd(&sh.hist[(k >> shift) & digit_mask], 1u);
+        }
+        __syncthreads();
+      }
+      uint32_t bin, above, members;
+      find_bin(sh, tid, rank, bin, above, members);
+      prefix = (prefix << bits) | bin;
+      rank -= above;
+      consumed += bits;
+      if (consumed == 31) {
+        thr_bits = prefix;
+        break;
+      }
+      if (members <= (uint32_t)kSelectDirect) {
+        if (tid == 0) sh.surv_n = 0;
+        __syncthreads();
+        const int low = 31 - consumed;  // key bits not yet fixed
+#pragma unroll
+        for (int i = 0; i < kSelectRegKeys; ++i) {
+          const uint32_t k = key[i];
+          if (k != kNoKey && (k >> low) == prefix) sh.surv[atomicAdd(&sh.surv_n, 1u)] = k;
+        }
+        __syncthreads();
+        thr_bits = rank_directly(sh, tid, members, rank);
+        break;
+      }
+    }
+  } else {
+    // ---- candidates re-evaluated in every pass -----------------------------------
+    int consumed = 0;
+#pragma unroll 1
+    for (int pass = 0; pass < 3; ++pass) {
+      const int bits = pass == 2 ? 9 : 11;
+      const int shift = 31 - consumed - bits;
+      const uint32_t digit_mask = (1u << bits) - 1u;
+      for (int i = tid; i < kSelectBins; i += kSelectThreads) sh.hist[i] = 0;
+      __syncthreads();
       for (int32_t p0 = tid; p0 < count; p0 += kSelectInFlight * kSelectThreads) {
         float gg[kSelectInFlight], uu[kSelectInFlight], vv[kSelectInFlight];
 #pragma unroll
@@ -223,46 +357,22 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
             float u1, v1;
             momentum_update(gg[q], uu[q], vv[q], c.m, c.scale, c.nesterov, u1, v1);
             const uint32_t k = __float_as_uint(v1) & 0x7FFFFFFFu;
-            if (cached) keys[p] = k;
             if (pass == 0 || (k >> (shift + bits)) == prefix)
-              atomicAdd(&hist[(k >> shift) & digit_mask], 1u);
+              atomicAdd(&sh.hist[(k >> shift) & digit_mask], 1u);
           }
         }
       }
-    } else {
-      for (int32_t p = tid; p < count; p += kSelectThreads) {
-        const uint32_t k = keys[p];
-        if ((k >> (shift + bits)) == prefix) atomicAdd(&hist[(k >> shift) & digit_mask], 1u);
-      }
+      __syncthreads();
+      uint32_t bin, above, members;
+      find_bin(sh, tid, rank, bin, above, members);
+      prefix = (prefix << bits) | bin;
+      rank -= above;
+      consumed += bits;
     }
-    __syncthreads();
-    // Suffix sums over the bins, two bins per thread, highest bins first in rank order.
-    const uint32_t h0 = hist[2 * tid];
-    const uint32_t h1 = hist[2 * tid + 1];
-    const uint32_t local = h0 + h1;
-    uint32_t incl = local;
-    for (int d = 1; d < 64; d <<= 1) {
-      const uint32_t t = __shfl_down(incl, d);
-      if (lane + d < 64) incl += t;
-    }
-    if (lane == 0) wave_tot[wave] = incl;
-    __syncthreads();
-    uint32_t above = incl - local;  // candidates in bins above this thread's pair
-    for (int w = wave + 1; w < kSelectThreads / 64; ++w) above += wave_tot[w];
-    if (above <= rank && rank < above + h1) {
-      sel_bin = 2 * tid + 1;
-      sel_above = above;
-    } else if (above + h1 <= rank && rank < above + local) {
-      sel_bin = 2 * tid;
-      sel_above = above + h1;
-    }
-    __syncthreads();
-    prefix = (prefix << bits) | sel_bin;
-    rank -= sel_above;
-    __syncthreads();
+    thr_bits = prefix;
   }
   if (tid == 0) {
-    const float thr = __uint_as_float(prefix);
+    const float thr = __uint_as_float(thr_bits);
     a.thr[j] = thr;
     if (a.out_thr) a.out_thr[j] = thr;
   }
@@ -421,6 +531,7 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
   constexpr int kBits = kStreamUnroll * 4;
   __shared__ int wave_tot[kWaves];
   __shared__ int block_base;
+  __shared__ int32_t list[kEmitList];
 
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -430,6 +541,12 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
   const int64_t hi = a.offsets[j + 1];
   const int64_t t1 = (hi - 1) / kWaveTile;
   const int64_t first = blk.first_tile;
+  const uint16_t* __restrict__ mask = a.mask;
+  float* __restrict__ u = a.u;
+  float* __restrict__ v = a.v;
+  int32_t* __restrict__ out_idx = a.out_idx;
+  float* __restrict__ out_val = a.out_val;
+  uint32_t* ctr = a.counters + (size_t)j * kCounterStride;  // [0] passes so far, [1] workgroups done
 
   uint32_t word[kPerWave];
   int cnt = 0;
@@ -438,7 +555,7 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
     const int64_t t = first + wave + i * kWaves;
     uint32_t w = 0;
     if (t <= t1) {
-      w = a.mask[t * 64 + lane];
+      w = mask[t * 64 + lane];
       if (t * kWaveTile < lo || (t + 1) * kWaveTile > hi) {  // tile shared with a neighbour tensor
         uint32_t keep = 0;
         for (int q = 0; q < kBits; ++q) {
@@ -465,31 +582,72 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
     if (w < wave) before += t;
     total += t;
   }
+  if (threadIdx.x == 0) {
+    int base = 0;
+    if (total > 0) base = (int)atomicAdd(&ctr[0], (uint32_t)total);
+    block_base = base;
+    // The workgroup that arrives last for this tensor publishes the count and leaves
+    // the counters at zero for the next call.  Only atomics carry information between
+    // workgroups here, so no fence is needed; the empty asm makes the arrival ticket
+    // wait for the reservation above to have returned.
+    uint32_t one = 1u;
+    asm volatile("" : "+v"(one) : "v"(base) : "memory");
+    const uint32_t done = atomicAdd(&ctr[1], one);
+    if (done == (uint32_t)blk.tensor_blocks - 1u) {
+      a.out_counts[j] = (int32_t)atomicExch(&ctr[0], 0u);
+      atomicExch(&ctr[1], 0u);
+    }
+  }
   if (total == 0) return;
-  if (threadIdx.x == 0) block_base = atomicAdd(&a.out_counts[j], total);
   __syncthreads();
   const int64_t region = a.out_offsets[j];
   const int64_t cap = a.out_offsets[j + 1] - region;
-  int64_t slot = (int64_t)block_base + before + (incl - cnt);
+  const int64_t base_slot = block_base;
+  const int my_first = before + (incl - cnt);  // position of this lane's first element in the workgroup
   bool overflow = false;
+  // The elements to move are first listed in LDS in their slot order, kEmitList at a
+  // time, then dealt out one per thread: every thread has the same amount of work and
+  // the reads of v are independent of each other.
+  for (int win = 0; win < total; win += kEmitList) {
+    int pos = my_first;
 #pragma unroll
-  for (int i = 0; i < kPerWave; ++i) {
-    uint32_t w = word[i];
-    const int64_t t = first + wave + i * kWaves;
-    while (w) {
-      const int q = __ffs(w) - 1;
-      w &= w - 1;
-      if (slot < cap) {
-        const int64_t e = tile_element(t, lane, q);
-        a.out_idx[region + slot] = (int32_t)e;
-        a.out_val[region + slot] = a.v[e];
-        a.v[e] = 0.0f;
-        if (a.factor_masking) a.u[e] = 0.0f;
-      } else {
-        overflow = true;
+    for (int i = 0; i < kPerWave; ++i) {
+      uint32_t w = word[i];
+      const int64_t t = first + wave + i * kWaves;
+      while (w) {
+        const int q = __ffs(w) - 1;
+        w &= w - 1;
+        if (pos >= win && pos < win + kEmitList) list[pos - win] = (int32_t)tile_element(t, lane, q);
+        ++pos;
       }
-      ++slot;
     }
+    __syncthreads();
+    const int in_win = total - win < kEmitList ? total - win : kEmitList;
+    for (int p0 = threadIdx.x; p0 < in_win; p0 += 4 * kEmitThreads) {
+      int32_t e[4];
+      float x[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int p = p0 + k * kEmitThreads;
+        e[k] = p < in_win ? list[p] : -1;
+        if (e[k] >= 0 && base_slot + win + p >= cap) {  // region full: leave the element where it is
+          e[k] = -1;
+          overflow = true;
+        }
+        x[k] = e[k] >= 0 ? v[e[k]] : 0.0f;
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (e[k] >= 0) {
+          const int64_t slot = base_slot + win + p0 + k * kEmitThreads;
+          out_idx[region + slot] = e[k];
+          out_val[region + slot] = x[k];
+          v[e[k]] = 0.0f;
+          if (a.factor_masking) u[e[k]] = 0.0f;
+        }
+      }
+    }
+    __syncthreads();
   }
   if (overflow) atomicOr(&a.state->flags, (uint32_t)DGC_DIAG_OVERFLOW);
 }

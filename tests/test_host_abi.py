@@ -37,7 +37,7 @@ def test_config_default_and_struct_layout(dgc_lib):
     assert C.sizeof(B.DgcConfig) == 56
     assert abs(cfg.momentum - 0.9) < 1e-7 and cfg.clip_threshold == 0.0 and cfg.num_workers == 1
     assert cfg.density == 0.001 and cfg.sample_ratio == 0.01
-    assert (cfg.sample_min, cfg.sample_max, cfg.sample_block) == (4096, 32768, 16)
+    assert (cfg.sample_min, cfg.sample_max, cfg.sample_block) == (4096, 32768, 32)
     assert math.isnan(cfg.scale_override) and cfg.seed == 0
 
 
@@ -114,7 +114,7 @@ def test_resnet50_k_sum_and_toy_plan(dgc_lib):
         assert lay[j + 1] - lay[j] == min(n, max(4 * k, k + 256))
     d.close()
     t = B.Dgc(B.dgc_config_default(), [0, 1 << 20])
-    assert t.dgc_query_plan(0) == (1049, 10496, 11, 656)
+    assert t.dgc_query_plan(0) == (1049, 10496, 11, 328)
     t.close()
 
 

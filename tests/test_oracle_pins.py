@@ -352,8 +352,8 @@ def test_sampled_threshold_estimates_population_quantile():
     n = 1 << 20
     c = O.OracleConfig(momentum=0.0, density=0.001, seed=9)
     plan = O.sample_plan(n, c)
-    # the toy configuration's plan: 1 % of 2**20 in blocks of 16, rank ceil(0.001 * 10496)
-    assert (plan.exact, plan.blocks, plan.count, plan.rank, plan.k) == (False, 656, 10496, 11, 1049)
+    # the toy configuration's plan: 1 % of 2**20 in blocks of 32, rank ceil(0.001 * 10496)
+    assert (plan.exact, plan.blocks, plan.count, plan.rank, plan.k) == (False, 328, 10496, 11, 1049)
     counts = []
     for it in range(12):
         g = (1e-3 * rng.standard_t(3, n)).astype(f32)
@@ -371,9 +371,9 @@ def test_sample_plan_rules():
     p = O.sample_plan(4096, c)
     assert p.exact and p.count == 4096 and p.rank == 5
     p = O.sample_plan(4097, c)
-    assert (not p.exact) and p.blocks == 256 and p.count == 4096 and p.rank == 5 and p.nblocks == 256
+    assert (not p.exact) and p.blocks == 128 and p.count == 4096 and p.rank == 5 and p.nblocks == 128
     p = O.sample_plan(2359296, c)              # ResNet-50's largest tensor: 1 % = 23593
-    assert p.blocks == 1475 and p.count == 23600 and p.rank == 24 and p.k == 2360
+    assert p.blocks == 738 and p.count == 23616 and p.rank == 24 and p.k == 2360
     p = O.sample_plan(15000000, c)             # capped at sample_max
     assert p.count == 32768 and p.rank == 33
     p = O.sample_plan(4723200, c, density=0.25)
@@ -388,9 +388,10 @@ def test_p11_sample_positions_properties():
     n = 100003
     plan = O.sample_plan(n, c)
     pos = O.sample_positions(c.seed, 7, 3, plan, c.sample_block)
-    assert pos.size == plan.count and pos.min() >= 0 and pos.max() < (n // 16) * 16
-    blocks = pos.reshape(-1, 16)
-    assert np.all(blocks[:, 0] % 16 == 0)
+    B = c.sample_block
+    assert pos.size == plan.count and pos.min() >= 0 and pos.max() < (n // B) * B
+    blocks = pos.reshape(-1, B)
+    assert np.all(blocks[:, 0] % B == 0)
     assert np.all(np.diff(blocks, axis=1) == 1)
     assert np.array_equal(pos, O.sample_positions(c.seed, 7, 3, plan, c.sample_block))
     for other in [(c.seed + 1, 7, 3), (c.seed, 8, 3), (c.seed, 7, 4), (c.seed + (1 << 32), 7, 3),
