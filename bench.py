@@ -1,16 +1,21 @@
 #!/usr/bin/env python3
 """Benchmark of the DGC hot path on one MI355X.
 
-A step is one pass of the whole path for one worker of an N = 16 job on the
-ResNet-50-shaped gradient set (25,557,032 fp32 elements in 161 tensors, density
-0.1 %, momentum 0.9, no clipping): dgc_compress of the worker's gradient
-(sampled thresholds, fused update + mask + compaction + factor masking), then
-dgc_decompress_accumulate_regions of 16 payloads (the fresh one and 15 from
+A step is one pass of the whole path for one worker of an N-worker job on a
+paper-shaped gradient set: dgc_compress of the worker's gradient (clipping norm
+when the configuration clips, sampled thresholds, streaming update + mask,
+emit = extraction + residual + factor masking), then
+dgc_decompress_accumulate_regions of N payloads (the fresh one and N - 1 from
 other seeded, correlated streams) into the dense aggregate, then
 dgc_dense_clear_regions to return the aggregate to zero.  Four workers' states
-(g, u, v: 1.2 GB together) rotate so that no step finds its operands in the
-256 MB last-level cache.  Inputs are generated on the host once, seeded, and are
-resident in HBM before the timed region.
+(g, u, v) rotate so that no step finds its operands in the 256 MB last-level
+cache.  Inputs are generated on the host once, seeded, and are resident in HBM
+before the timed region.
+
+The default workload is the one the headline metric is quoted on: the
+ResNet-50-shaped set (25,557,032 fp32 elements in 161 tensors, density 0.1 %,
+momentum 0.9, no clipping, N = 16).  --workload lstm | speech time the two
+larger sets for the record.
 
 Prints one JSON line: whole-job throughput in dense gradient elements per
 second, the roofline of the dominant kernel (the streaming pass, 20 bytes per
@@ -29,16 +34,28 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0           # MI355X published peak
-BYTES_PER_ELEMENT = 20           # read g, u, v; write u, v (fp32)
-N_WORKERS = 16
+BYTES_PER_ELEMENT = 20           # streaming pass: read g, u, v; write u, v (fp32)
 ROTATE = 4
 
-# HBM traffic of one streaming-kernel launch on this workload from rocprofv3 --pmc
+WORKLOADS = {
+    # name: (set constructor, config, N payloads accumulated, description)
+    "resnet50": ("resnet50_set", dict(momentum=0.9, density=0.001, seed=1, num_workers=16), 16,
+                 "ResNet-50-shaped gradient set, 161 fp32 tensors, 25,557,032 elements, density 0.001, "
+                 "m=0.9, no clipping"),
+    "lstm": ("lstm_lm_set", dict(momentum=0.9, density=0.001, seed=1, num_workers=4, clip_threshold=0.25), 4,
+             "2-layer LSTM-1500 language-model-shaped set, 11 fp32 tensors, 66,034,000 elements, density 0.001, "
+             "m=0.9, clipping 0.25 with N=4"),
+    "speech": ("speech_set", dict(momentum=0.9, density=0.001, seed=1, num_workers=8), 8,
+               "speech-model-shaped set (7 bidirectional GRU-1200 layers), 62 fp32 tensors, 122,153,069 "
+               "elements, density 0.001 (steady state of the warm-up schedule), m=0.9, no clipping"),
+}
+
+# HBM traffic of one streaming-kernel launch on the default workload from rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs, each scaled by what the same counter reads for a
 # device copy of n floats): 307.5 MB read + 207.7 MB written.  The counters cannot be
 # read from inside this process; profiles/stream_kernel_resnet50_hbm_traffic.txt holds
 # the run this number comes from.
-MEASURED_TRAFFIC_BYTES = 515155917
+MEASURED_TRAFFIC_BYTES = {"resnet50": 515155917}
 
 
 def parse_args():
@@ -46,6 +63,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", choices=sorted(WORKLOADS), default="resnet50")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sample-block", type=int, default=None, help="override dgc_config.sample_block")
     ap.add_argument("--profile-only", action="store_true",
@@ -53,16 +71,23 @@ def parse_args():
     return ap.parse_args()
 
 
-def cpu_baseline(gs, scales, shared_seed):
+def make_gradient(S, name, gs, seed, worker, shared, scales):
+    g = S.correlated_gradient(gs, seed, worker, 0, shared, scales=scales)
+    if name == "lstm":      # the embedding gradient touches 700 seeded rows only
+        S.zero_inactive_embedding_rows(g, seed, worker, 0)
+    return g
+
+
+def cpu_baseline(name, gs, cfg_kw, n_workers, scales, seed):
     """The oracle, as it stands, on a bounded sample of the same workload."""
     import numpy as np
     from oracle import dgc_oracle as O
     from paper_1712_01887_amd import synthetic as S
 
-    cfg = O.OracleConfig(momentum=0.9, density=0.001, seed=1, num_workers=N_WORKERS)
+    cfg = O.OracleConfig(**cfg_kw)
     u = np.zeros(gs.numel, np.float32)
     v = np.zeros(gs.numel, np.float32)
-    grads = [S.gradient(gs, shared_seed, 0, it, scales) for it in range(4)]
+    grads = [S.gradient(gs, seed, 0, it, scales) for it in range(4)]
     O.compress(grads[0], u, v, gs.offsets, cfg, 0)                     # untimed: first touch of the buffers
     t_comp = 0.0
     iters = 0
@@ -77,7 +102,7 @@ def cpu_baseline(gs, scales, shared_seed):
     reps = 5
     t0 = time.perf_counter()
     for _ in range(reps):
-        O.decompress_accumulate(dense, [payload] * N_WORKERS)
+        O.decompress_accumulate(dense, [payload] * n_workers)
         dense[payload[0]] = 0.0                                        # sparse clear, as the GPU step does
     t_acc = (time.perf_counter() - t0) / reps
     per_step = t_comp / iters + t_acc
@@ -86,8 +111,8 @@ def cpu_baseline(gs, scales, shared_seed):
         "unit": "elements/s",
         "cores": 1,
         "kind": "oracle",
-        "sample": f"{iters} compress iterations of the full ResNet-50-shaped set "
-                  f"({t_comp / iters * 1e3:.0f} ms each) + accumulate/clear of {N_WORKERS} payloads "
+        "sample": f"{iters} compress iterations of the full {name} set "
+                  f"({t_comp / iters * 1e3:.0f} ms each) + accumulate/clear of {n_workers} payloads "
                   f"({t_acc * 1e3:.1f} ms), numpy, single thread",
     }
 
@@ -99,7 +124,6 @@ def main():
               "single MI355X; use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
     from paper_1712_01887_amd import binding as B
     from paper_1712_01887_amd import synthetic as S
@@ -107,31 +131,33 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
     dev = "cuda"
-    gs = S.resnet50_set()
+    set_name, cfg_kw, n_workers, description = WORKLOADS[args.workload]
+    cfg_kw = dict(cfg_kw)
+    gs = getattr(S, set_name)()
     n = gs.numel
     seed = 2025
     scales = S.tensor_scales(gs, seed)
-    kw = dict(momentum=0.9, density=0.001, seed=1, num_workers=N_WORKERS)
     if args.sample_block:
-        kw["sample_block"] = args.sample_block
+        cfg_kw["sample_block"] = args.sample_block
+    clip = cfg_kw.get("clip_threshold", 0.0) > 0.0
 
-    dgc = B.Dgc(B.make_config(**kw), gs.offsets)
-    layout = dgc.dgc_recommended_payload_layout(0.001)
+    dgc = B.Dgc(B.make_config(**cfg_kw), gs.offsets)
+    layout = dgc.dgc_recommended_payload_layout(cfg_kw["density"])
     dgc.set_layout(layout)
 
     # ---- inputs, resident in HBM ----------------------------------------------
     shared = S.gradient(gs, seed, 999, 0, scales)
-    g_pool = [torch.from_numpy(S.correlated_gradient(gs, seed, r, 0, shared, scales=scales)).to(dev)
+    g_pool = [torch.from_numpy(make_gradient(S, args.workload, gs, seed, r, shared, scales)).to(dev)
               for r in range(ROTATE)]
     u = [torch.zeros(n, device=dev) for _ in range(ROTATE)]
     v = [torch.zeros(n, device=dev) for _ in range(ROTATE)]
     fresh = [dgc.alloc_payload(dev) for _ in range(ROTATE)]
-    # 15 payloads of other workers: one compress each of a correlated stream
+    # N - 1 payloads of other workers: one compress each of a correlated stream
     others = []
     tu = torch.zeros(n, device=dev)
     tv = torch.zeros(n, device=dev)
-    for w in range(N_WORKERS - 1):
-        gw = torch.from_numpy(S.correlated_gradient(gs, seed, 100 + w, 0, shared, scales=scales)).to(dev)
+    for w in range(n_workers - 1):
+        gw = torch.from_numpy(make_gradient(S, args.workload, gs, seed, 100 + w, shared, scales)).to(dev)
         tu.zero_()
         tv.zero_()
         pl = dgc.alloc_payload(dev)
@@ -208,7 +234,7 @@ def main():
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
             "algorithmic_bytes": BYTES_PER_ELEMENT * n,
             "avg_kernel_us": round(stream_avg_ms * 1e3, 2),
         }
@@ -216,14 +242,19 @@ def main():
         acc = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
         breakdown = {
             "compress_us": round(comp * 1e3, 2),
+            "norm_kernel_us": round(norm_ms / calls * 1e3, 2) if clip else None,
             "select_kernel_us": round(select_ms / calls * 1e3, 2),
             "stream_kernel_us": round(stream_avg_ms * 1e3, 2),
             "emit_kernel_us": round(emit_ms / calls * 1e3, 2),
             "accumulate_and_clear_us": round(acc * 1e3, 2),
             "ms_per_step_with_events": round(profiled_ms, 5),
         }
+        if clip:
+            nb = 4 * n / (norm_ms / calls * 1e-3) / 1e9
+            breakdown["norm_kernel_GBps"] = round(nb, 1)
 
     counts = max(1, int(fresh[0][2].sum().item()))
+    step_bytes = (BYTES_PER_ELEMENT + (4 if clip else 0)) * n
     out = {
         "metric": "dense gradient elements/s for compress+decompress",
         "value": n / (ms_per_step * 1e-3),
@@ -238,15 +269,15 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": "ResNet-50-shaped gradient set, 161 fp32 tensors, 25,557,032 elements, density 0.001, "
-                        "m=0.9, no clipping; step = compress one worker + accumulate 16 payloads + sparse clear",
+            "workload": description + f"; step = compress one worker + accumulate {n_workers} payloads + "
+                                      "sparse clear",
             "elements": n,
             "tensors": len(gs.sizes),
-            "workers_accumulated": N_WORKERS,
+            "workers_accumulated": n_workers,
             "rotating_states": ROTATE,
             "pairs_per_payload": counts,
         },
-        "algorithmic_GBps_whole_step": round(BYTES_PER_ELEMENT * n / (ms_per_step * 1e-3) / 1e9, 1),
+        "algorithmic_GBps_whole_step": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "compression_ratio": {"ours_8B_pairs": round(4.0 * n / (8 * counts), 1),
                               "ours_6B_entries": round(4.0 * n / (6 * counts), 1),
                               "paper_resnet50": 277, "paper_range": "270-600"},
@@ -254,7 +285,7 @@ def main():
         "roofline": roofline,
     }
     if not (args.no_cpu_baseline or args.profile_only):
-        out["cpu_baseline"] = cpu_baseline(gs, scales, seed)
+        out["cpu_baseline"] = cpu_baseline(args.workload, gs, cfg_kw, n_workers, scales, seed)
     print(json.dumps(out))
 
 

@@ -49,7 +49,7 @@ constexpr int kSelectInFlight = 8;    // candidates each thread gathers before u
 
 // Clipping norm: a fixed number of partial sums keeps the result reproducible.
 constexpr int kNormThreads = 256;
-constexpr int kNormMaxBlocks = 2048;
+constexpr int kNormMaxBlocks = 512;
 
 constexpr int kMaxPayloads = 64;
 

@@ -40,7 +40,7 @@ __device__ __forceinline__ void momentum_update(float g, float u, float v, float
 // Clipping norm (paper: Section 3.2 "Local Gradient Clipping"; Appendix C eq. 12)
 // ---------------------------------------------------------------------------
 // Every workgroup accumulates squares in binary64 over a grid-stride range and
-// stores one partial; the workgroup that finishes last adds the partials in
+// publishes one partial; the workgroup that finishes last adds the partials in
 // index order, so the result does not depend on scheduling.
 __global__ __launch_bounds__(kNormThreads) void norm_kernel(const float* __restrict__ g, int64_t n,
                                                             DeviceState* state, double* partials,
@@ -54,7 +54,32 @@ __global__ __launch_bounds__(kNormThreads) void norm_kernel(const float* __restr
   const float4* __restrict__ g4 = reinterpret_cast<const float4*>(g);
   double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
   const int64_t stride = (int64_t)gridDim.x * kNormThreads;
-  for (int64_t i = (int64_t)blockIdx.x * kNormThreads + tid; i < nvec; i += stride) {
+  int64_t i = (int64_t)blockIdx.x * kNormThreads + tid;
+  // four independent 16-byte loads in flight per thread; ordinary (cached) loads, because
+  // the streaming pass reads g again right after this kernel
+  for (; i + 3 * stride < nvec; i += 4 * stride) {
+    const float4 x0 = g4[i];
+    const float4 x1 = g4[i + stride];
+    const float4 x2 = g4[i + 2 * stride];
+    const float4 x3 = g4[i + 3 * stride];
+    a0 += (double)x0.x * (double)x0.x;
+    a1 += (double)x0.y * (double)x0.y;
+    a2 += (double)x0.z * (double)x0.z;
+    a3 += (double)x0.w * (double)x0.w;
+    a0 += (double)x1.x * (double)x1.x;
+    a1 += (double)x1.y * (double)x1.y;
+    a2 += (double)x1.z * (double)x1.z;
+    a3 += (double)x1.w * (double)x1.w;
+    a0 += (double)x2.x * (double)x2.x;
+    a1 += (double)x2.y * (double)x2.y;
+    a2 += (double)x2.z * (double)x2.z;
+    a3 += (double)x2.w * (double)x2.w;
+    a0 += (double)x3.x * (double)x3.x;
+    a1 += (double)x3.y * (double)x3.y;
+    a2 += (double)x3.z * (double)x3.z;
+    a3 += (double)x3.w * (double)x3.w;
+  }
+  for (; i < nvec; i += stride) {
     const float4 x = g4[i];
     a0 += (double)x.x * (double)x.x;
     a1 += (double)x.y * (double)x.y;
@@ -72,14 +97,19 @@ __global__ __launch_bounds__(kNormThreads) void norm_kernel(const float* __restr
   if (tid == 0) {
     double s = 0.0;
     for (int w = 0; w < kNormThreads / 64; ++w) s += red[w];
-    partials[blockIdx.x] = s;
-    __threadfence();
-    const uint32_t ticket = atomicAdd(&state->norm_ticket, 1u);
+    // The partial is published with a returning device-scope atomic and the arrival
+    // ticket is taken only after it has returned, so the workgroup that draws the last
+    // ticket finds every partial in memory.  Nothing but atomics carries data between
+    // workgroups, which spares a device-wide fence (a full L2 write-back on this part).
+    const unsigned long long old = atomicExch(reinterpret_cast<unsigned long long*>(partials + blockIdx.x),
+                                              (unsigned long long)__double_as_longlong(s));
+    uint32_t one = 1u;
+    asm volatile("" : "+v"(one) : "v"((uint32_t)old) : "memory");
+    const uint32_t ticket = atomicAdd(&state->norm_ticket, one);
     is_last = (ticket == gridDim.x - 1);
   }
   __syncthreads();
   if (!is_last) return;
-  __threadfence();
   double s = 0.0;
   for (int i = tid; i < (int)gridDim.x; i += kNormThreads)
     s += __hip_atomic_load(&partials[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -462,12 +492,28 @@ __device__ __forceinline__ uint32_t stream_round_general(const StreamArgs& a, in
 __global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs a) {
   constexpr int U = kStreamUnroll;
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: table reads go scalar
   const int64_t tile = (int64_t)blockIdx.x * kStreamWaves + wave;
   const int64_t base = tile * kWaveTile;
   if (base >= a.n) return;
   const uint32_t info = a.tile_info[tile];
   const float scale = a.scale_from_state ? a.state->scale : a.scale_const;
+  // The loads of a full tile are issued before the tile's table entry is looked at, so
+  // that the table lookup costs no time on the fast path; a tile that turns out to need
+  // the general path drops them (nothing has been stored yet) and starts over.
+  const bool full = base + kWaveTile <= a.n;
+  const vec4* __restrict__ g4 = reinterpret_cast<const vec4*>(a.g + base) + lane;
+  vec4* __restrict__ u4 = reinterpret_cast<vec4*>(a.u + base) + lane;
+  vec4* __restrict__ v4 = reinterpret_cast<vec4*>(a.v + base) + lane;
+  vec4 x[U], y[U], z[U];
+  if (full) {
+#pragma unroll
+    for (int r = 0; r < U; ++r) {
+      x[r] = __builtin_nontemporal_load(g4 + r * 64);
+      y[r] = __builtin_nontemporal_load(u4 + r * 64);
+      z[r] = __builtin_nontemporal_load(v4 + r * 64);
+    }
+  }
   const int32_t j = (int32_t)(info & ~kTileMixed);
 
   if (info & kTileMixed) {
@@ -484,16 +530,6 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs a) {
   // ---- fast path: the whole tile belongs to tensor j and lies inside the buffers ----
   const float m = a.momentum;
   const bool nesterov = a.nesterov != 0;
-  const vec4* __restrict__ g4 = reinterpret_cast<const vec4*>(a.g + base) + lane;
-  vec4* __restrict__ u4 = reinterpret_cast<vec4*>(a.u + base) + lane;
-  vec4* __restrict__ v4 = reinterpret_cast<vec4*>(a.v + base) + lane;
-  vec4 x[U], y[U], z[U];
-#pragma unroll
-  for (int r = 0; r < U; ++r) {
-    x[r] = __builtin_nontemporal_load(g4 + r * 64);
-    y[r] = __builtin_nontemporal_load(u4 + r * 64);
-    z[r] = __builtin_nontemporal_load(v4 + r * 64);
-  }
   const float thr = a.thr[j];
   uint32_t cand = 0;
 #pragma unroll

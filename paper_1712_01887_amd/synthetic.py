@@ -199,17 +199,28 @@ def toy_gradient(n: int, base_seed: int, worker: int, iteration: int) -> np.ndar
     return out
 
 
-def lstm_gradient(gs: GradientSet, base_seed: int, worker: int, iteration: int,
-                  scales: Optional[np.ndarray] = None) -> np.ndarray:
-    """As `gradient`, but the embedding gradient is zero outside 700 seeded rows."""
-    g = gradient(gs, base_seed, worker, iteration, scales)
+def embedding_active_rows(base_seed: int, worker: int, iteration: int) -> np.ndarray:
+    """Boolean mask over the 10000 embedding rows: the 700 seeded rows a step touches."""
     rng = _chunk_rng(base_seed, worker, iteration, 2, 0)
     rows = rng.choice(LSTM_EMBED_ROWS, size=LSTM_ACTIVE_ROWS, replace=False)
     keep = np.zeros(LSTM_EMBED_ROWS, dtype=bool)
     keep[rows] = True
+    return keep
+
+
+def zero_inactive_embedding_rows(g: np.ndarray, base_seed: int, worker: int, iteration: int) -> np.ndarray:
+    """In place: the embedding gradient (first tensor of the LSTM set) is zero outside the active rows."""
+    keep = embedding_active_rows(base_seed, worker, iteration)
     emb = g[: LSTM_EMBED_ROWS * LSTM_EMBED_DIM].reshape(LSTM_EMBED_ROWS, LSTM_EMBED_DIM)
     emb[~keep] = 0.0
     return g
+
+
+def lstm_gradient(gs: GradientSet, base_seed: int, worker: int, iteration: int,
+                  scales: Optional[np.ndarray] = None) -> np.ndarray:
+    """As `gradient`, but the embedding gradient is zero outside 700 seeded rows."""
+    g = gradient(gs, base_seed, worker, iteration, scales)
+    return zero_inactive_embedding_rows(g, base_seed, worker, iteration)
 
 
 def correlated_gradient(gs: GradientSet, base_seed: int, worker: int, iteration: int,
