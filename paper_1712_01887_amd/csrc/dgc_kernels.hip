@@ -582,7 +582,8 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
   float* __restrict__ v = a.v;
   int32_t* __restrict__ out_idx = a.out_idx;
   float* __restrict__ out_val = a.out_val;
-  uint32_t* ctr = a.counters + (size_t)j * kCounterStride;  // [0] passes so far, [1] workgroups done
+  unsigned long long* ctr =
+      reinterpret_cast<unsigned long long*>(a.counters + (size_t)j * kCounterStride);
 
   uint32_t word[kPerWave];
   int cnt = 0;
@@ -619,19 +620,15 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
     total += t;
   }
   if (threadIdx.x == 0) {
-    int base = 0;
-    if (total > 0) base = (int)atomicAdd(&ctr[0], (uint32_t)total);
-    block_base = base;
-    // The workgroup that arrives last for this tensor publishes the count and leaves
-    // the counters at zero for the next call.  Only atomics carry information between
-    // workgroups here, so no fence is needed; the empty asm makes the arrival ticket
-    // wait for the reservation above to have returned.
-    uint32_t one = 1u;
-    asm volatile("" : "+v"(one) : "v"(base) : "memory");
-    const uint32_t done = atomicAdd(&ctr[1], one);
-    if (done == (uint32_t)blk.tensor_blocks - 1u) {
-      a.out_counts[j] = (int32_t)atomicExch(&ctr[0], 0u);
-      atomicExch(&ctr[1], 0u);
+    // One 64-bit atomic both reserves the slots (low word: elements passed so far) and
+    // takes the arrival ticket (high word: workgroups done).  The workgroup that arrives
+    // last for this tensor publishes the count and leaves the counter at zero for the
+    // next call.  Only atomics carry information between workgroups, so no fence is needed.
+    const unsigned long long old = atomicAdd(ctr, (unsigned long long)(uint32_t)total | (1ull << 32));
+    block_base = (int)(uint32_t)old;
+    if ((uint32_t)(old >> 32) == (uint32_t)blk.tensor_blocks - 1u) {
+      a.out_counts[j] = (int32_t)((uint32_t)old + (uint32_t)total);
+      atomicExch(ctr, 0ull);
     }
   }
   if (total == 0) return;
