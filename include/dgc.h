@@ -132,7 +132,7 @@ dgc_status dgc_workspace_bytes(const dgc_handle* h, size_t* bytes);
 
 /*
  * A payload layout for `density`: out_offsets_host (host, num_tensors + 1) receives
- * the start of each tensor's pair region, capacity_j = min(n_j, max(4 k_j, k_j + 256)).
+ * the start of each tensor's pair region, capacity_j = min(n_j, max(8 k_j, k_j + 256)).
  */
 dgc_status dgc_recommended_payload_layout(const dgc_handle* h, double density,
                                           int64_t* out_offsets_host);

@@ -74,6 +74,7 @@ def test_sixteen_worker_accumulate_resnet50_shape():
         p = Pair(gs.offsets, **kw)
         res = p.step(S.correlated_gradient(gs, 61, w, 0, shared, scales=scales), 0, check_state=False,
                      label=f"acc w{w}")
+        assert not res.overflow                          # else which pairs were kept is order-dependent
         p.u = p.v = None                                 # keep only the payload on the device
         p.ou = p.ov = None
         payloads.append(O.flatten_payload(res))
@@ -92,11 +93,21 @@ def test_sixteen_worker_accumulate_resnet50_shape():
     cnt = [p.out_counts for p in pairs]
     acc.dgc_decompress_accumulate_regions(dense, idx, val, cnt)
     got = dense.cpu().numpy()
-    # any order of the additions stays within 1e-6 of the sum of magnitudes at each index
+    # Summing N binary32 terms in any order stays within (N-1) * 2**-24 * sum|x| of the exact sum
+    # (15 * 2**-24 = 8.9e-7 < 1e-6 for N = 16).  The oracle's worker-ordered sum obeys the same
+    # bound, so the two may differ by up to twice that.
     mags = np.zeros(gs.numel, np.float32)
     O.decompress_accumulate(mags, [(i, np.abs(x)) for i, x in payloads])
-    assert np.all(np.abs(got.astype(np.float64) - expect) <= 1e-6 * mags)
-    assert not got[mags == 0].any()
+    exact = np.zeros(gs.numel, np.float64)
+    for i, x in payloads:
+        np.add.at(exact, i.astype(np.int64), x.astype(np.float64))
+    touched = mags > 0
+    err_exact = np.abs(got.astype(np.float64) - exact)[touched] / mags[touched]
+    err_oracle = np.abs(got.astype(np.float64) - expect)[touched] / mags[touched]
+    say(f"[accumulate] max error / sum|x|: vs exact {err_exact.max():.3e}, vs oracle {err_oracle.max():.3e}")
+    assert err_exact.max() <= 1e-6
+    assert err_oracle.max() <= 2e-6
+    assert not got[~touched].any()
     det = B.Dgc(B.make_config(flags=B.DGC_FLAG_DETERMINISTIC_ACCUMULATE, **kw), gs.offsets)
     det.set_layout(pairs[0].layout)
     dense.zero_()

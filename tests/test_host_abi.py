@@ -111,7 +111,7 @@ def test_resnet50_k_sum_and_toy_plan(dgc_lib):
     assert lay[0] == 0 and len(lay) == 162
     for j, n in enumerate(gs.sizes):
         k = O.topk_count(0.001, n)
-        assert lay[j + 1] - lay[j] == min(n, max(4 * k, k + 256))
+        assert lay[j + 1] - lay[j] == min(n, max(8 * k, k + 256))
     d.close()
     t = B.Dgc(B.dgc_config_default(), [0, 1 << 20])
     assert t.dgc_query_plan(0) == (1049, 10496, 11, 328)
