@@ -66,6 +66,8 @@ def parse_args():
     ap.add_argument("--workload", choices=sorted(WORKLOADS), default="resnet50")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sample-block", type=int, default=None, help="override dgc_config.sample_block")
+    ap.add_argument("--refine-alpha", type=float, default=None,
+                    help="switch the Section 5 re-threshold on (dgc_config.refine_alpha); off by default")
     ap.add_argument("--profile-only", action="store_true",
                     help="skip the CPU baseline and the event-instrumented pass (for rocprofv3 runs)")
     return ap.parse_args()
@@ -139,6 +141,9 @@ def main():
     scales = S.tensor_scales(gs, seed)
     if args.sample_block:
         cfg_kw["sample_block"] = args.sample_block
+    if args.refine_alpha:
+        cfg_kw["refine_alpha"] = args.refine_alpha
+        description += f", re-threshold when more than {args.refine_alpha:g} k pass"
     clip = cfg_kw.get("clip_threshold", 0.0) > 0.0
 
     dgc = B.Dgc(B.make_config(**cfg_kw), gs.offsets)

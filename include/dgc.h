@@ -74,6 +74,10 @@ typedef struct dgc_config {
   int32_t sample_block;  /* consecutive elements per draw, power of two <= 64 (32)   */
   float scale_override;  /* test hook: NaN = unused, else replaces the clip scale    */
   uint64_t seed;         /* seed of the counter-based sample positions               */
+  float refine_alpha;    /* Section 5 re-threshold: when more than alpha * k_j elements of a
+                            tensor pass the sampled threshold, the threshold is recomputed
+                            exactly from those that passed; 0 = off, otherwise >= 1 (2)  */
+  uint32_t reserved;     /* zero                                                     */
 } dgc_config;
 
 typedef struct dgc_diagnostics {
@@ -85,7 +89,7 @@ typedef struct dgc_diagnostics {
 typedef struct dgc_handle dgc_handle;
 
 /* Fill *cfg with m = 0.9, no clipping, N = 1, d = 0.001, sampling 1 % clamped to
- * [4096, 32768] in blocks of 32, seed 0. */
+ * [4096, 32768] in blocks of 32, seed 0, no re-threshold. */
 dgc_status dgc_config_default(dgc_config* cfg);
 
 /* Text for a status code (static storage). */
@@ -143,6 +147,8 @@ dgc_status dgc_recommended_payload_layout(const dgc_handle* h, double density,
  *   u'     = m u + scale g ;  v' = v + u'                            (equation 7)
  *   thr_j  = magnitude of descending rank r_j among the sampled |v'| of tensor j,
  *            or of the whole tensor when it is small or EXACT_SELECT (Section 5)
+ *   if refine_alpha > 0 and more than refine_alpha * k_j elements pass: thr_j =
+ *            magnitude of descending rank k_j among those that passed    (Section 5)
  *   keep   = |v'| > thr_j  (strict)                                  (Algorithm 3)
  *   emit (global flat index, v') for kept elements; v <- keep ? 0 : v';
  *   u <- keep ? 0 : u'                                               (Section 3.3)

@@ -58,6 +58,8 @@ class DgcConfig(C.Structure):
         ("sample_block", C.c_int32),
         ("scale_override", C.c_float),
         ("seed", C.c_uint64),
+        ("refine_alpha", C.c_float),
+        ("reserved", C.c_uint32),
     ]
 
 

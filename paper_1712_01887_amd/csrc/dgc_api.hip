@@ -81,6 +81,11 @@ void build_plan(dgc_handle* h) {
     p.n = n;
     const int64_t k = topk_count(c.density, n);
     h->k[j] = k;
+    p.k = (int32_t)k;
+    {
+      const double lim = std::floor((double)c.refine_alpha * (double)k);
+      p.refine_limit = lim >= 2147483647.0 ? 2147483647 : (int32_t)lim;
+    }
     int64_t want = (int64_t)std::ceil(c.sample_ratio * (double)n);
     if (want > c.sample_max) want = c.sample_max;
     if (want < c.sample_min) want = c.sample_min;
@@ -120,6 +125,7 @@ void build_layout(dgc_handle* h) {
   l.tile_info = off;    off = align_up(off + sizeof(uint32_t) * tiles);
   l.emit_blocks = off;  off = align_up(off + sizeof(EmitBlock) * h->emit_blocks.size());
   l.counters = off;     off = align_up(off + sizeof(uint32_t) * kCounterStride * T);
+  l.refine_counters = off; off = align_up(off + sizeof(uint32_t) * kCounterStride * T);
   l.mask = off;         off = align_up(off + sizeof(uint16_t) * 64 * tiles);
   l.total = off;
 }
@@ -156,7 +162,7 @@ dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_
     if (!hip_ok(hipMemsetAsync(at<char>(ws, h->lay.state), 0, sizeof(DeviceState), stream),
                 "clear workspace state"))
       return DGC_ERR_HIP;
-    if (!hip_ok(hipMemsetAsync(at<char>(ws, h->lay.counters), 0, sizeof(uint32_t) * kCounterStride * T,
+    if (!hip_ok(hipMemsetAsync(at<char>(ws, h->lay.counters), 0, 2 * align_up(sizeof(uint32_t) * kCounterStride * T),
                                stream),
                 "clear emit counters"))
       return DGC_ERR_HIP;
@@ -230,6 +236,8 @@ dgc_status dgc_config_default(dgc_config* cfg) {
   cfg->sample_block = 32;
   cfg->scale_override = std::nanf("");
   cfg->seed = 0;
+  cfg->refine_alpha = 0.0f;
+  cfg->reserved = 0;
   return DGC_OK;
 }
 
@@ -245,6 +253,7 @@ dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tenso
   if (B < 1 || B > 64 || (B & (B - 1)) != 0) return DGC_ERR_INVALID_ARG;
   if (cfg->sample_min < B || cfg->sample_max < cfg->sample_min) return DGC_ERR_INVALID_ARG;
   if (cfg->clip_threshold != cfg->clip_threshold) return DGC_ERR_INVALID_ARG;
+  if (!(cfg->refine_alpha == 0.0f || cfg->refine_alpha >= 1.0f)) return DGC_ERR_INVALID_ARG;
   if (offsets_host[0] != 0) return DGC_ERR_INVALID_ARG;
   for (int32_t j = 0; j < num_tensors; ++j)
     if (offsets_host[j + 1] <= offsets_host[j]) return DGC_ERR_INVALID_ARG;
@@ -430,6 +439,22 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   ta.nesterov = sa.nesterov;
   if (!hip_ok(launch_stream(ta, stream), "launch stream kernel")) return DGC_ERR_HIP;
   if (ev && !hip_ok(hipEventRecord(ev[3], stream), "record event")) return DGC_ERR_HIP;
+
+  // paper: Section 5 -- "if the number of gradients exceeding the threshold is far more than
+  // expected, a precise threshold is calculated from the already-selected gradients"
+  if (c.refine_alpha > 0.0f) {
+    RefineArgs ra{};
+    ra.blocks = at<EmitBlock>(workspace, h->lay.emit_blocks);
+    ra.counters = at<uint32_t>(workspace, h->lay.refine_counters);
+    ra.plans = sa.plans;
+    ra.v = v;
+    ra.mask = ta.mask;
+    ra.offsets = ta.offsets;
+    ra.thr = sa.thr;
+    ra.out_thr = out_thr;
+    if (!hip_ok(launch_refine(ra, (int32_t)h->emit_blocks.size(), stream), "launch refine kernel"))
+      return DGC_ERR_HIP;
+  }
 
   EmitArgs ea{};
   ea.blocks = at<EmitBlock>(workspace, h->lay.emit_blocks);

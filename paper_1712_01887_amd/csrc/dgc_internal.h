@@ -33,6 +33,7 @@ constexpr int kEmitElements = 32768;                  // elements per workgroup
 constexpr int kEmitTiles = kEmitElements / kWaveTile;
 static_assert(kEmitTiles % (kEmitThreads / 64) == 0, "tiles are dealt round-robin to wavefronts");
 constexpr int kEmitList = 4096;                       // elements listed in LDS at a time
+constexpr int kRefineThreads = kEmitThreads;          // the re-threshold pass shares the emit work list
 // Per-tensor counters of the emit pass live one per 128-byte line so that atomics
 // on different tensors do not serialise on a shared line.
 constexpr int kCounterStride = 32;  // uint32 words
@@ -70,10 +71,12 @@ struct TensorPlan {
   int32_t rank;     // 0-based descending rank that becomes the threshold
   uint32_t nblocks; // aligned sample blocks in the tensor (sampled mode)
   int32_t exact;    // 1: candidates are elements 0..n-1
+  int32_t k;             // clamp(ceil(d n), 1, n)
+  int32_t refine_limit;  // floor(refine_alpha * k): more passes than this trigger the re-threshold
 };
 
 struct WorkspaceLayout {
-  size_t state, partials, offsets, out_offsets, plans, thr, tile_info, emit_blocks, counters, mask, total;
+  size_t state, partials, offsets, out_offsets, plans, thr, tile_info, emit_blocks, counters, refine_counters, mask, total;
 };
 
 struct SelectArgs {
@@ -116,6 +119,17 @@ struct EmitBlock {
   int32_t pad;
 };
 
+struct RefineArgs {
+  const EmitBlock* blocks;     // the emit work list
+  uint32_t* counters;          // device, kCounterStride words per tensor, zero between calls
+  const TensorPlan* plans;
+  const float* v;              // pre-mask v' as left by the streaming pass
+  uint16_t* mask;
+  const int64_t* offsets;
+  float* thr;
+  float* out_thr;              // may be null
+};
+
 struct EmitArgs {
   const EmitBlock* blocks;     // device, one entry per workgroup
   uint32_t* counters;          // device, kCounterStride words per tensor, zero between calls
@@ -150,6 +164,7 @@ hipError_t launch_norm(const float* g, int64_t n, DeviceState* state, double* pa
                        double thr_local, float scale_override, hipStream_t stream);
 hipError_t launch_select(const SelectArgs& a, int32_t num_tensors, hipStream_t stream);
 hipError_t launch_stream(const StreamArgs& a, hipStream_t stream);
+hipError_t launch_refine(const RefineArgs& a, int32_t num_blocks, hipStream_t stream);
 hipError_t launch_emit(const EmitArgs& a, int32_t num_blocks, hipStream_t stream);
 hipError_t launch_scatter_pairs(float* dense, int64_t n, const PairPayloads& p, int32_t first,
                                 int32_t num, int64_t max_count, ScatterMode mode,

@@ -183,40 +183,49 @@ struct SelectShared {
   uint32_t hist[kSelectBins];
   uint32_t wave_tot[kSelectThreads / 64];
   uint32_t surv[kSelectDirect];
-  uint32_t sel_bin, sel_above, sel_count, surv_n, result;
+  uint32_t sel[3];
+  uint32_t surv_n, result;
 };
 
 // After a histogram pass: the bin that holds descending rank `rank`, how many
 // candidates lie above it, and how many it holds.  Every thread returns the same.
-__device__ __forceinline__ void find_bin(SelectShared& sh, int tid, uint32_t rank, uint32_t& bin,
-                                         uint32_t& above_out, uint32_t& members) {
+// `sel` is three words of LDS, `wave_tot` one word per wavefront.
+template <int THREADS>
+__device__ __forceinline__ void find_bin(const uint32_t* hist, uint32_t* wave_tot, uint32_t* sel, int tid,
+                                         uint32_t rank, uint32_t& bin, uint32_t& above_out,
+                                         uint32_t& members) {
+  constexpr int PER = kSelectBins / THREADS;  // consecutive bins owned by a thread
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const uint32_t h0 = sh.hist[2 * tid];
-  const uint32_t h1 = sh.hist[2 * tid + 1];
-  const uint32_t local = h0 + h1;
-  uint32_t incl = local;  // suffix sum: this thread's pair of bins and everything above
+  uint32_t h[PER];
+  uint32_t local = 0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    h[i] = hist[PER * tid + i];
+    local += h[i];
+  }
+  uint32_t incl = local;  // suffix sum: this thread's bins and everything above
   for (int d = 1; d < 64; d <<= 1) {
     const uint32_t t = __shfl_down(incl, d);
     if (lane + d < 64) incl += t;
   }
-  if (lane == 0) sh.wave_tot[wave] = incl;
+  if (lane == 0) wave_tot[wave] = incl;
   __syncthreads();
-  uint32_t above = incl - local;
-  for (int w = wave + 1; w < kSelectThreads / 64; ++w) above += sh.wave_tot[w];
-  if (above <= rank && rank < above + h1) {
-    sh.sel_bin = 2 * tid + 1;
-    sh.sel_above = above;
-    sh.sel_count = h1;
-  } else if (above + h1 <= rank && rank < above + local) {
-    sh.sel_bin = 2 * tid;
-    sh.sel_above = above + h1;
-    sh.sel_count = h0;
+  uint32_t run = incl - local;  // candidates above this thread's bins
+  for (int w = wave + 1; w < THREADS / 64; ++w) run += wave_tot[w];
+#pragma unroll
+  for (int i = PER - 1; i >= 0; --i) {
+    if (run <= rank && rank < run + h[i]) {
+      sel[0] = PER * tid + i;
+      sel[1] = run;
+      sel[2] = h[i];
+    }
+    run += h[i];
   }
   __syncthreads();
-  bin = sh.sel_bin;
-  above_out = sh.sel_above;
-  members = sh.sel_count;
+  bin = sel[0];
+  above_out = sel[1];
+  members = sel[2];
 }
 
 // The `m` <= kSelectDirect keys in sh.surv: the one of descending rank `rank`.
@@ -335,7 +344,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
         __syncthreads();
       }
       uint32_t bin, above, members;
-      find_bin(sh, tid, rank, bin, above, members);
+      find_bin<kSelectThreads>(sh.hist, sh.wave_tot, sh.sel, tid, rank, bin, above, members);
       prefix = (prefix << bits) | bin;
       rank -= above;
       consumed += bits;
@@ -394,7 +403,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       }
       __syncthreads();
       uint32_t bin, above, members;
-      find_bin(sh, tid, rank, bin, above, members);
+      find_bin<kSelectThreads>(sh.hist, sh.wave_tot, sh.sel, tid, rank, bin, above, members);
       prefix = (prefix << bits) | bin;
       rank -= above;
       consumed += bits;
@@ -549,6 +558,146 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs a) {
     __builtin_nontemporal_store(z[r], v4 + r * 64);
   }
   a.mask[tile * 64 + lane] = (uint16_t)cand;
+}
+
+// ---------------------------------------------------------------------------
+// Re-threshold on over-selection
+// (paper: Section 5 -- when far more elements pass than expected, a precise
+//  threshold is computed from those already selected)
+// ---------------------------------------------------------------------------
+// Runs between the streaming and the emit pass over the emit work list.  Every
+// workgroup counts the mask bits of its part of a tensor and adds them to the
+// tensor's counter with one 64-bit atomic that is also the arrival ticket.  The
+// workgroup that arrives last knows the tensor's total; only if that exceeds
+// refine_limit does it go on, alone: three histogram passes over |v'| of the
+// selected elements find the magnitude of descending rank k exactly, and a
+// last walk clears the mask bits of elements that do not exceed it.  What the
+// emit pass then extracts is the exact top k of the tensor.
+struct RefineShared {
+  uint32_t hist[kSelectBins];
+  uint32_t wave_tot[kRefineThreads / 64];
+  uint32_t sel[3];
+  int red[kRefineThreads / 64];
+  int go;
+};
+
+// This thread's filtered mask word `wi` (0-based within the tensor's tiles) of tensor [lo, hi).
+__device__ __forceinline__ uint32_t tensor_mask_word(const uint16_t* mask, int64_t t0, int64_t wi, int64_t lo,
+                                                     int64_t hi, int64_t& tile, int& lane) {
+  constexpr int kBits = kStreamUnroll * 4;
+  tile = t0 + (wi >> 6);
+  lane = (int)(wi & 63);
+  uint32_t w = mask[tile * 64 + lane];
+  if (w && (tile * kWaveTile < lo || (tile + 1) * kWaveTile > hi)) {
+    uint32_t keep = 0;
+    for (int q = 0; q < kBits; ++q) {
+      const int64_t e = tile_element(tile, lane, q);
+      if (e >= lo && e < hi) keep |= 1u << q;
+    }
+    w &= keep;
+  }
+  return w;
+}
+
+__global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
+  constexpr int kWaves = kRefineThreads / 64;
+  constexpr int kPerWave = kEmitTiles / kWaves;
+  __shared__ RefineShared sh;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const EmitBlock blk = a.blocks[blockIdx.x];
+  const int j = blk.tensor;
+  const int64_t lo = a.offsets[j];
+  const int64_t hi = a.offsets[j + 1];
+  const int64_t t0 = lo / kWaveTile;
+  const int64_t t1 = (hi - 1) / kWaveTile;
+  const int64_t first = blk.first_tile;
+
+  int cnt = 0;
+#pragma unroll
+  for (int i = 0; i < kPerWave; ++i) {
+    const int64_t t = first + wave + i * kWaves;
+    if (t <= t1) {
+      int64_t tile;
+      int l;
+      cnt += __popc(tensor_mask_word(a.mask, t0, (t - t0) * 64 + lane, lo, hi, tile, l));
+    }
+  }
+  for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_down(cnt, d);
+  if (lane == 0) sh.red[wave] = cnt;
+  __syncthreads();
+  if (tid == 0) {
+    int total = 0;
+    for (int w = 0; w < kWaves; ++w) total += sh.red[w];
+    unsigned long long* ctr = reinterpret_cast<unsigned long long*>(a.counters + (size_t)j * kCounterStride);
+    const unsigned long long old = atomicAdd(ctr, (unsigned long long)(uint32_t)total | (1ull << 32));
+    int go = 0;
+    if ((uint32_t)(old >> 32) == (uint32_t)blk.tensor_blocks - 1u) {  // last arriver: the tensor's total is known
+      atomicExch(ctr, 0ull);
+      const uint32_t passed = (uint32_t)old + (uint32_t)total;
+      go = passed > (uint32_t)a.plans[j].refine_limit;
+    }
+    sh.go = go;
+  }
+  __syncthreads();
+  if (!sh.go) return;
+
+  // ---- exact threshold among the selected elements of tensor j (rare) ---------------
+  const int64_t words = (t1 - t0 + 1) * 64;
+  uint32_t prefix = 0;
+  uint32_t rank = (uint32_t)a.plans[j].k;
+  int consumed = 0;
+#pragma unroll 1
+  for (int pass = 0; pass < 3; ++pass) {
+    const int bits = pass == 2 ? 9 : 11;
+    const int shift = 31 - consumed - bits;
+    const uint32_t digit_mask = (1u << bits) - 1u;
+    for (int i = tid; i < kSelectBins; i += kRefineThreads) sh.hist[i] = 0;
+    __syncthreads();
+    for (int64_t wi = tid; wi < words; wi += kRefineThreads) {
+      int64_t tile;
+      int l;
+      uint32_t w = tensor_mask_word(a.mask, t0, wi, lo, hi, tile, l);
+      while (w) {
+        const int q = __ffs(w) - 1;
+        w &= w - 1;
+        const uint32_t key = __float_as_uint(a.v[tile_element(tile, l, q)]) & 0x7FFFFFFFu;
+        if (pass == 0 || (key >> (shift + bits)) == prefix) atomicAdd(&sh.hist[(key >> shift) & digit_mask], 1u);
+      }
+    }
+    __syncthreads();
+    uint32_t bin, above, members;
+    find_bin<kRefineThreads>(sh.hist, sh.wave_tot, sh.sel, tid, rank, bin, above, members);
+    prefix = (prefix << bits) | bin;
+    rank -= above;
+    consumed += bits;
+  }
+  // Clear the bits of selected elements that do not exceed the new threshold.  A word of a
+  // tile shared with a neighbour tensor also holds that tensor's bits, and its re-threshold
+  // may run at the same time, so the update is an atomic AND on the enclosing 32-bit word.
+  uint32_t* mask32 = reinterpret_cast<uint32_t*>(a.mask);
+  for (int64_t wi = tid; wi < words; wi += kRefineThreads) {
+    int64_t tile;
+    int l;
+    uint32_t w = tensor_mask_word(a.mask, t0, wi, lo, hi, tile, l);
+    uint32_t drop = 0;
+    while (w) {
+      const int q = __ffs(w) - 1;
+      w &= w - 1;
+      const uint32_t key = __float_as_uint(a.v[tile_element(tile, l, q)]) & 0x7FFFFFFFu;
+      if (!(key > prefix)) drop |= 1u << q;
+    }
+    if (drop) {
+      const int64_t h = tile * 64 + l;  // index of the 16-bit word
+      atomicAnd(&mask32[h >> 1], ~(drop << (16 * (int)(h & 1))));
+    }
+  }
+  if (tid == 0) {
+    const float thr = __uint_as_float(prefix);
+    a.thr[j] = thr;
+    if (a.out_thr) a.out_thr[j] = thr;
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -775,6 +924,11 @@ hipError_t launch_stream(const StreamArgs& a, hipStream_t stream) {
   const int64_t tiles = ceil_div(a.n, kWaveTile);
   const int64_t blocks = ceil_div(tiles, kStreamWaves);
   hipLaunchKernelGGL(stream_kernel, dim3((unsigned)blocks), dim3(kStreamThreads), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_refine(const RefineArgs& a, int32_t num_blocks, hipStream_t stream) {
+  hipLaunchKernelGGL(refine_kernel, dim3((unsigned)num_blocks), dim3(kRefineThreads), 0, stream, a);
   return hipGetLastError();
 }
 

@@ -34,6 +34,19 @@ def test_resnet50_set_three_iterations():
     p.close()
 
 
+def test_resnet50_set_with_rethreshold():
+    gs = S.resnet50_set()
+    scales = S.tensor_scales(gs, 32)
+    p = Pair(gs.offsets, momentum=0.9, density=0.001, seed=32, refine_alpha=2.0)
+    for it in range(2):
+        res = p.step(S.gradient(gs, 32, 0, it, scales), it, label=f"resnet50 refine it{it}")
+        say(f"[resnet50 refine] iteration {it}: {sum(res.refined)} tensors re-thresholded, pairs={int(res.counts.sum())}")
+        assert not res.overflow
+        for j, n in enumerate(gs.sizes):
+            assert int(res.counts[j]) <= 2 * O.topk_count(0.001, n)
+    p.close()
+
+
 def test_lstm_set_with_clipping_two_iterations():
     gs = S.lstm_lm_set()
     scales = S.tensor_scales(gs, 41)

@@ -158,6 +158,43 @@ def test_warmup_schedule_changes_plan_between_iterations():
     p.close()
 
 
+@pytest.mark.parametrize("alpha", [1.0, 2.0])
+def test_rethreshold_on_over_selection(alpha):
+    # tiny samples make the estimated threshold wander: over-selection triggers the exact
+    # re-threshold on some tensors (then exactly k are sent) and not on others
+    gs = S.ragged_set(12, tensors=14, max_numel=120000)
+    p = Pair(gs.offsets, momentum=0.9, density=0.01, seed=21, sample_min=64, sample_max=64, sample_block=4,
+             refine_alpha=alpha)
+    refined = 0
+    for it in range(4):
+        res = p.step(S.gradient(gs, 26, 0, it), it, label=f"refine alpha={alpha} it{it}")
+        assert not res.overflow
+        for j, n in enumerate(gs.sizes):
+            k = O.topk_count(0.01, n)
+            if res.refined[j]:
+                refined += 1
+                assert int(res.counts[j]) <= k           # exactly k unless magnitudes tie at the cut
+            else:
+                assert int(res.counts[j]) <= alpha * k
+    assert refined >= 3
+    p.close()
+
+
+def test_rethreshold_with_shared_tiles_and_nesterov():
+    # many small tensors inside one wave tile: their re-thresholds update the same mask words
+    sizes = [300, 17, 700, 5, 1000, 2000, 64, 3000, 10, 900]
+    offsets = np.concatenate([[0], np.cumsum(sizes)])
+    p = Pair(offsets, layout_density=1.0, momentum=0.9, density=0.05, seed=4, sample_min=16, sample_max=16,
+             sample_block=1, refine_alpha=1.0, flags=B.DGC_FLAG_NESTEROV)
+    rng = np.random.default_rng(99)
+    hits = 0
+    for it in range(5):
+        res = p.step(rng.standard_t(3, offsets[-1]).astype(np.float32), it, label=f"refine shared it{it}")
+        hits += sum(res.refined)
+    assert hits >= 5
+    p.close()
+
+
 def test_resume_with_a_new_handle_gives_identical_results():
     import torch
     gs = S.ragged_set(10, tensors=8)

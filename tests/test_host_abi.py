@@ -34,11 +34,11 @@ def test_library_exports_every_declared_symbol(dgc_lib):
 
 def test_config_default_and_struct_layout(dgc_lib):
     cfg = B.dgc_config_default()
-    assert C.sizeof(B.DgcConfig) == 56
+    assert C.sizeof(B.DgcConfig) == 64
     assert abs(cfg.momentum - 0.9) < 1e-7 and cfg.clip_threshold == 0.0 and cfg.num_workers == 1
     assert cfg.density == 0.001 and cfg.sample_ratio == 0.01
     assert (cfg.sample_min, cfg.sample_max, cfg.sample_block) == (4096, 32768, 32)
-    assert math.isnan(cfg.scale_override) and cfg.seed == 0
+    assert math.isnan(cfg.scale_override) and cfg.seed == 0 and cfg.refine_alpha == 0.0
 
 
 def test_create_rejects_bad_arguments(dgc_lib):
@@ -55,7 +55,7 @@ def test_create_rejects_bad_arguments(dgc_lib):
     assert create(B.dgc_config_default(), [0, 1 << 31])[0] == B.DGC_ERR_CAPACITY
     for field, value in [("density", 0.0), ("density", 1.5), ("density", float("nan")), ("num_workers", 0),
                          ("momentum", -0.1), ("sample_block", 3), ("sample_block", 128),
-                         ("sample_min", 8), ("sample_ratio", 0.0)]:
+                         ("sample_min", 8), ("sample_ratio", 0.0), ("refine_alpha", 0.5), ("refine_alpha", -1.0)]:
         cfg = B.dgc_config_default()
         setattr(cfg, field, value)
         assert create(cfg, [0, 100])[0] == B.DGC_ERR_INVALID_ARG, field
