@@ -450,6 +450,9 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
     ra.v = v;
     ra.mask = ta.mask;
     ra.offsets = ta.offsets;
+    ra.out_offsets = at<int64_t>(workspace, h->lay.out_offsets);
+    ra.out_idx = out_idx;
+    ra.out_val = out_val;
     ra.thr = sa.thr;
     ra.out_thr = out_thr;
     if (!hip_ok(launch_refine(ra, (int32_t)h->emit_blocks.size(), stream), "launch refine kernel"))

@@ -33,7 +33,7 @@ constexpr int kEmitElements = 32768;                  // elements per workgroup
 constexpr int kEmitTiles = kEmitElements / kWaveTile;
 static_assert(kEmitTiles % (kEmitThreads / 64) == 0, "tiles are dealt round-robin to wavefronts");
 constexpr int kEmitList = 4096;                       // elements listed in LDS at a time
-constexpr int kRefineThreads = kEmitThreads;          // the re-threshold pass shares the emit work list
+constexpr int kRefineThreads = 1024;                  // the re-threshold pass shares the emit work list
 // Per-tensor counters of the emit pass live one per 128-byte line so that atomics
 // on different tensors do not serialise on a shared line.
 constexpr int kCounterStride = 32;  // uint32 words
@@ -126,6 +126,9 @@ struct RefineArgs {
   const float* v;              // pre-mask v' as left by the streaming pass
   uint16_t* mask;
   const int64_t* offsets;
+  const int64_t* out_offsets;  // payload regions: free until the emit pass, used as scratch
+  int32_t* out_idx;
+  float* out_val;
   float* thr;
   float* out_thr;              // may be null
 };

@@ -579,6 +579,8 @@ struct RefineShared {
   uint32_t sel[3];
   int red[kRefineThreads / 64];
   int go;
+  uint32_t passed;
+  uint32_t listed;
 };
 
 // This thread's filtered mask word `wi` (0-based within the tensor's tiles) of tensor [lo, hi).
@@ -637,6 +639,7 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
       atomicExch(ctr, 0ull);
       const uint32_t passed = (uint32_t)old + (uint32_t)total;
       go = passed > (uint32_t)a.plans[j].refine_limit;
+      sh.passed = passed;
     }
     sh.go = go;
   }
@@ -645,52 +648,152 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
 
   // ---- exact threshold among the selected elements of tensor j (rare) ---------------
   const int64_t words = (t1 - t0 + 1) * 64;
+  const int64_t region = a.out_offsets[j];
+  const int64_t cap = a.out_offsets[j + 1] - region;
+  const int64_t passed = sh.passed;
   uint32_t prefix = 0;
   uint32_t rank = (uint32_t)a.plans[j].k;
   int consumed = 0;
-#pragma unroll 1
-  for (int pass = 0; pass < 3; ++pass) {
-    const int bits = pass == 2 ? 9 : 11;
-    const int shift = 31 - consumed - bits;
-    const uint32_t digit_mask = (1u << bits) - 1u;
-    for (int i = tid; i < kSelectBins; i += kRefineThreads) sh.hist[i] = 0;
+  uint32_t* mask32 = reinterpret_cast<uint32_t*>(a.mask);
+
+  if (passed <= cap) {
+    // The tensor's payload region is free until the emit pass: list the selected elements
+    // there, then their keys, so that everything after one walk over the mask is coalesced.
+    int32_t* list = a.out_idx + region;
+    uint32_t* keys = reinterpret_cast<uint32_t*>(a.out_val + region);
+    if (tid == 0) sh.listed = 0;
     __syncthreads();
+    // eight mask words (16 bytes) per load, four loads in flight per thread
+    const uint4* mask128 = reinterpret_cast<const uint4*>(a.mask + t0 * 64);
+    const int64_t chunks = words >> 3;
+    for (int64_t c0 = tid; c0 < chunks; c0 += 4 * kRefineThreads) {
+      uint4 m[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int64_t c = c0 + k * kRefineThreads;
+        m[k] = c < chunks ? mask128[c] : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int64_t c = c0 + k * kRefineThreads;
+        if ((m[k].x | m[k].y | m[k].z | m[k].w) == 0) continue;
+        const uint32_t pair[4] = {m[k].x, m[k].y, m[k].z, m[k].w};
+#pragma unroll
+        for (int h = 0; h < 8; ++h) {
+          uint32_t w = (pair[h >> 1] >> (16 * (h & 1))) & 0xFFFFu;
+          if (!w) continue;
+          const int64_t wi = c * 8 + h;
+          const int64_t tile = t0 + (wi >> 6);
+          const int l = (int)(wi & 63);
+          if (tile * kWaveTile < lo || (tile + 1) * kWaveTile > hi) {  // tile shared with a neighbour
+            uint32_t keep = 0;
+            for (int q = 0; q < kStreamUnroll * 4; ++q) {
+              const int64_t e = tile_element(tile, l, q);
+              if (e >= lo && e < hi) keep |= 1u << q;
+            }
+            w &= keep;
+            if (!w) continue;
+          }
+          int pos = (int)atomicAdd(&sh.listed, (uint32_t)__popc(w));
+          while (w) {
+            const int q = __ffs(w) - 1;
+            w &= w - 1;
+            list[pos++] = (int32_t)tile_element(tile, l, q);
+          }
+        }
+      }
+    }
+    __syncthreads();
+    const int count = (int)passed;
+    for (int p0 = tid; p0 < count; p0 += 4 * kRefineThreads) {
+      float x[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int p = p0 + q * kRefineThreads;
+        x[q] = p < count ? a.v[list[p]] : 0.0f;
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int p = p0 + q * kRefineThreads;
+        if (p < count) keys[p] = __float_as_uint(x[q]) & 0x7FFFFFFFu;
+      }
+    }
+    __syncthreads();
+#pragma unroll 1
+    for (int pass = 0; pass < 3; ++pass) {
+      const int bits = pass == 2 ? 9 : 11;
+      const int shift = 31 - consumed - bits;
+      const uint32_t digit_mask = (1u << bits) - 1u;
+      for (int i = tid; i < kSelectBins; i += kRefineThreads) sh.hist[i] = 0;
+      __syncthreads();
+      for (int p = tid; p < count; p += kRefineThreads) {
+        const uint32_t key = keys[p];
+        if (pass == 0 || (key >> (shift + bits)) == prefix) atomicAdd(&sh.hist[(key >> shift) & digit_mask], 1u);
+      }
+      __syncthreads();
+      uint32_t bin, above, members;
+      find_bin<kRefineThreads>(sh.hist, sh.wave_tot, sh.sel, tid, rank, bin, above, members);
+      prefix = (prefix << bits) | bin;
+      rank -= above;
+      consumed += bits;
+    }
+    // Clear the mask bit of every selected element that does not exceed the new threshold.
+    // A 16-bit mask word of a tile shared with a neighbour tensor also holds that tensor's
+    // bits, and its re-threshold may run at the same time: atomic AND on the 32-bit word.
+    for (int p = tid; p < count; p += kRefineThreads) {
+      if (!(keys[p] > prefix)) {
+        const int64_t e = list[p];
+        const int64_t tile = e / kWaveTile;
+        const int r = (int)(e % kWaveTile);
+        const int64_t h = tile * 64 + ((r & 255) >> 2);        // the lane's 16-bit word
+        const int q = (r >> 8) * 4 + (r & 3);
+        atomicAnd(&mask32[h >> 1], ~((1u << q) << (16 * (int)(h & 1))));
+      }
+    }
+  } else {
+    // More passed than the payload region holds (the caller's capacity is below the
+    // over-selection): walk the mask in every pass and read v' element by element.
+#pragma unroll 1
+    for (int pass = 0; pass < 3; ++pass) {
+      const int bits = pass == 2 ? 9 : 11;
+      const int shift = 31 - consumed - bits;
+      const uint32_t digit_mask = (1u << bits) - 1u;
+      for (int i = tid; i < kSelectBins; i += kRefineThreads) sh.hist[i] = 0;
+      __syncthreads();
+      for (int64_t wi = tid; wi < words; wi += kRefineThreads) {
+        int64_t tile;
+        int l;
+        uint32_t w = tensor_mask_word(a.mask, t0, wi, lo, hi, tile, l);
+        while (w) {
+          const int q = __ffs(w) - 1;
+          w &= w - 1;
+          const uint32_t key = __float_as_uint(a.v[tile_element(tile, l, q)]) & 0x7FFFFFFFu;
+          if (pass == 0 || (key >> (shift + bits)) == prefix)
+            atomicAdd(&sh.hist[(key >> shift) & digit_mask], 1u);
+        }
+      }
+      __syncthreads();
+      uint32_t bin, above, members;
+      find_bin<kRefineThreads>(sh.hist, sh.wave_tot, sh.sel, tid, rank, bin, above, members);
+      prefix = (prefix << bits) | bin;
+      rank -= above;
+      consumed += bits;
+    }
     for (int64_t wi = tid; wi < words; wi += kRefineThreads) {
       int64_t tile;
       int l;
       uint32_t w = tensor_mask_word(a.mask, t0, wi, lo, hi, tile, l);
+      uint32_t drop = 0;
       while (w) {
         const int q = __ffs(w) - 1;
         w &= w - 1;
         const uint32_t key = __float_as_uint(a.v[tile_element(tile, l, q)]) & 0x7FFFFFFFu;
-        if (pass == 0 || (key >> (shift + bits)) == prefix) atomicAdd(&sh.hist[(key >> shift) & digit_mask], 1u);
+        if (!(key > prefix)) drop |= 1u << q;
       }
-    }
-    __syncthreads();
-    uint32_t bin, above, members;
-    find_bin<kRefineThreads>(sh.hist, sh.wave_tot, sh.sel, tid, rank, bin, above, members);
-    prefix = (prefix << bits) | bin;
-    rank -= above;
-    consumed += bits;
-  }
-  // Clear the bits of selected elements that do not exceed the new threshold.  A word of a
-  // tile shared with a neighbour tensor also holds that tensor's bits, and its re-threshold
-  // may run at the same time, so the update is an atomic AND on the enclosing 32-bit word.
-  uint32_t* mask32 = reinterpret_cast<uint32_t*>(a.mask);
-  for (int64_t wi = tid; wi < words; wi += kRefineThreads) {
-    int64_t tile;
-    int l;
-    uint32_t w = tensor_mask_word(a.mask, t0, wi, lo, hi, tile, l);
-    uint32_t drop = 0;
-    while (w) {
-      const int q = __ffs(w) - 1;
-      w &= w - 1;
-      const uint32_t key = __float_as_uint(a.v[tile_element(tile, l, q)]) & 0x7FFFFFFFu;
-      if (!(key > prefix)) drop |= 1u << q;
-    }
-    if (drop) {
-      const int64_t h = tile * 64 + l;  // index of the 16-bit word
-      atomicAnd(&mask32[h >> 1], ~(drop << (16 * (int)(h & 1))));
+      if (drop) {
+        const int64_t h = tile * 64 + l;  // index of the 16-bit word
+        atomicAnd(&mask32[h >> 1], ~(drop << (16 * (int)(h & 1))));
+      }
     }
   }
   if (tid == 0) {
