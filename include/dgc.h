@@ -226,6 +226,26 @@ dgc_status dgc_dense_clear_regions(dgc_handle* h, float* dense, int32_t num_payl
                                    size_t workspace_bytes, void* stream);
 
 /*
+ * Receive side fused with the optimizer step (the last line of Algorithm 3 with plain SGD,
+ * theta <- theta - lr * G_t, G_t being the sum of the N sparse gradients): for every pair
+ *       theta[idx] -= lr * val
+ * so that no dense aggregate is formed and none has to be cleared.  Arguments as for
+ * dgc_decompress_accumulate / dgc_decompress_accumulate_regions, theta (device, n floats) in
+ * place of dense.  Each pair is applied on its own (theta - lr*v1 - lr*v2 rather than
+ * theta - lr*(v1 + v2)); with DGC_FLAG_DETERMINISTIC_ACCUMULATE workers are applied in order.
+ */
+dgc_status dgc_sparse_sgd_apply(dgc_handle* h, float* theta, int64_t n, float learning_rate,
+                                int32_t num_payloads, const int32_t* const* idx_ptrs_host,
+                                const float* const* val_ptrs_host, const int64_t* pair_counts_host,
+                                uint32_t* diag_flags_dev, void* stream);
+dgc_status dgc_sparse_sgd_apply_regions(dgc_handle* h, float* theta, float learning_rate,
+                                        int32_t num_payloads, const int32_t* const* idx_ptrs_host,
+                                        const float* const* val_ptrs_host,
+                                        const int32_t* const* count_ptrs_host,
+                                        const int64_t* out_offsets_host, void* workspace,
+                                        size_t workspace_bytes, void* stream);
+
+/*
  * Kernel timing for measurement harnesses.  After dgc_profile_enable the next
  * `max_calls` dgc_compress calls record HIP events on the caller's stream before
  * the norm kernel, after it, after the select kernel, after the streaming kernel

@@ -306,6 +306,19 @@ def decompress_accumulate(dense: np.ndarray,
         np.add.at(dense, np.asarray(idx, dtype=np.int64), np.asarray(val, dtype=np.float32))
 
 
+def sparse_sgd_apply(theta: np.ndarray, payloads: Sequence[Tuple[np.ndarray, np.ndarray]],
+                     learning_rate: float) -> None:
+    """Last line of Algorithm 3 with plain SGD, applied pair by pair:
+    theta[idx] <- theta[idx] - lr * val, workers in the order given, binary32, the
+    product rounded before the subtraction.  Equal to theta - lr * G_t (G_t the sum
+    of the sparse gradients) up to rounding, and exactly where an index occurs once."""
+    assert theta.dtype == np.float32
+    lr = np.float32(learning_rate)
+    for idx, val in payloads:
+        step = lr * np.asarray(val, dtype=np.float32)
+        np.subtract.at(theta, np.asarray(idx, dtype=np.int64), step)
+
+
 def compression_ratio(n: int, pairs: int, bytes_per_pair: int) -> float:
     """Dense bytes over payload bytes (the tables print this reciprocal of the
     formula of Section 4.1, e.g. 277x)."""

@@ -41,7 +41,7 @@ EXPORTS = [
     "dgc_recommended_payload_layout", "dgc_compress", "dgc_get_diagnostics",
     "dgc_decompress_accumulate", "dgc_decompress_accumulate_regions", "dgc_dense_clear_regions",
     "dgc_version", "dgc_last_error_string", "dgc_profile_enable", "dgc_profile_collect",
-    "dgc_profile_disable",
+    "dgc_profile_disable", "dgc_sparse_sgd_apply", "dgc_sparse_sgd_apply_regions",
 ]
 
 
@@ -124,6 +124,11 @@ def load() -> C.CDLL:
                                                       C.c_size_t, vp]
     lib.dgc_dense_clear_regions.restype = i32
     lib.dgc_dense_clear_regions.argtypes = [vp, vp, i32, P(vp), P(vp), P(i64), vp, C.c_size_t, vp]
+    lib.dgc_sparse_sgd_apply.restype = i32
+    lib.dgc_sparse_sgd_apply.argtypes = [vp, vp, i64, C.c_float, i32, P(vp), P(vp), P(i64), vp, vp]
+    lib.dgc_sparse_sgd_apply_regions.restype = i32
+    lib.dgc_sparse_sgd_apply_regions.argtypes = [vp, vp, C.c_float, i32, P(vp), P(vp), P(vp), P(i64), vp,
+                                                 C.c_size_t, vp]
     lib.dgc_profile_enable.restype = i32
     lib.dgc_profile_enable.argtypes = [vp, i32]
     lib.dgc_profile_collect.restype = i32
@@ -292,6 +297,20 @@ class Dgc:
             self._h, _ptr(dense), len(idx_list), _ptr_array(idx_list), _ptr_array(val_list),
             _ptr_array(count_list), self._layout_c, self._ws_ptr, self._ws_bytes, _stream()),
             "dgc_decompress_accumulate_regions")
+
+    def dgc_sparse_sgd_apply(self, theta, learning_rate: float, idx_list, val_list, counts: Sequence[int],
+                             diag_flags=None) -> None:
+        _check(self.lib.dgc_sparse_sgd_apply(self._h, _ptr(theta), int(theta.numel()), float(learning_rate),
+                                             len(idx_list), _ptr_array(idx_list), _ptr_array(val_list),
+                                             _i64_array(counts), _ptr(diag_flags), _stream()),
+               "dgc_sparse_sgd_apply")
+
+    def dgc_sparse_sgd_apply_regions(self, theta, learning_rate: float, idx_list, val_list, count_list) -> None:
+        self.ensure_workspace(theta.device)
+        _check(self.lib.dgc_sparse_sgd_apply_regions(
+            self._h, _ptr(theta), float(learning_rate), len(idx_list), _ptr_array(idx_list),
+            _ptr_array(val_list), _ptr_array(count_list), self._layout_c, self._ws_ptr, self._ws_bytes,
+            _stream()), "dgc_sparse_sgd_apply_regions")
 
     def dgc_dense_clear_regions(self, dense, idx_list, count_list) -> None:
         self.ensure_workspace(dense.device)

@@ -547,11 +547,14 @@ dgc_status dgc_get_diagnostics(dgc_handle* h, const void* workspace, dgc_diagnos
   return DGC_OK;
 }
 
-dgc_status dgc_decompress_accumulate(dgc_handle* h, float* dense, int64_t n, int32_t num_payloads,
-                                     const int32_t* const* idx_ptrs_host,
-                                     const float* const* val_ptrs_host,
-                                     const int64_t* pair_counts_host, uint32_t* diag_flags_dev,
-                                     void* stream_) {
+namespace {
+enum class ScatterOp { kAccumulate, kClear, kSgd };
+}
+
+static dgc_status scatter_pairs(dgc_handle* h, float* dense, int64_t n, int32_t num_payloads,
+                                const int32_t* const* idx_ptrs_host, const float* const* val_ptrs_host,
+                                const int64_t* pair_counts_host, uint32_t* diag_flags_dev, void* stream_,
+                                ScatterOp op, float scale) {
   if (!h || !dense || !idx_ptrs_host || !val_ptrs_host || !pair_counts_host) return DGC_ERR_INVALID_ARG;
   if (n < 1 || n >= (int64_t)1 << 31) return DGC_ERR_INVALID_ARG;
   if (num_payloads < 1) return DGC_ERR_INVALID_ARG;
@@ -569,18 +572,39 @@ dgc_status dgc_decompress_accumulate(dgc_handle* h, float* dense, int64_t n, int
     if (c > max_count) max_count = c;
   }
   hipStream_t stream = static_cast<hipStream_t>(stream_);
+  const bool sgd = op == ScatterOp::kSgd;
   if (h->cfg.flags & DGC_FLAG_DETERMINISTIC_ACCUMULATE) {
     // one launch per worker, in order: within a payload every index is distinct
     for (int32_t w = 0; w < num_payloads; ++w)
-      if (!hip_ok(launch_scatter_pairs(dense, n, p, w, 1, p.count[w], kScatterPlainAdd, diag_flags_dev,
-                               stream), "launch scatter kernel"))
+      if (!hip_ok(launch_scatter_pairs(dense, n, p, w, 1, p.count[w], sgd ? kScatterPlainSgd : kScatterPlainAdd,
+                                       scale, diag_flags_dev, stream),
+                  "launch scatter kernel"))
         return DGC_ERR_HIP;
   } else {
-    if (!hip_ok(launch_scatter_pairs(dense, n, p, 0, num_payloads, max_count, kScatterAtomicAdd,
-                             diag_flags_dev, stream), "launch scatter kernel"))
+    if (!hip_ok(launch_scatter_pairs(dense, n, p, 0, num_payloads, max_count,
+                                     sgd ? kScatterAtomicSgd : kScatterAtomicAdd, scale, diag_flags_dev, stream),
+                "launch scatter kernel"))
       return DGC_ERR_HIP;
   }
   return DGC_OK;
+}
+
+dgc_status dgc_decompress_accumulate(dgc_handle* h, float* dense, int64_t n, int32_t num_payloads,
+                                     const int32_t* const* idx_ptrs_host,
+                                     const float* const* val_ptrs_host,
+                                     const int64_t* pair_counts_host, uint32_t* diag_flags_dev,
+                                     void* stream) {
+  return scatter_pairs(h, dense, n, num_payloads, idx_ptrs_host, val_ptrs_host, pair_counts_host,
+                       diag_flags_dev, stream, ScatterOp::kAccumulate, 0.0f);
+}
+
+dgc_status dgc_sparse_sgd_apply(dgc_handle* h, float* theta, int64_t n, float learning_rate,
+                                int32_t num_payloads, const int32_t* const* idx_ptrs_host,
+                                const float* const* val_ptrs_host, const int64_t* pair_counts_host,
+                                uint32_t* diag_flags_dev, void* stream) {
+  if (!(learning_rate == learning_rate)) return DGC_ERR_INVALID_ARG;
+  return scatter_pairs(h, theta, n, num_payloads, idx_ptrs_host, val_ptrs_host, pair_counts_host,
+                       diag_flags_dev, stream, ScatterOp::kSgd, -learning_rate);
 }
 
 static dgc_status scatter_regions(dgc_handle* h, float* dense, int32_t num_payloads,
@@ -588,7 +612,9 @@ static dgc_status scatter_regions(dgc_handle* h, float* dense, int32_t num_paylo
                                   const float* const* val_ptrs_host,
                                   const int32_t* const* count_ptrs_host,
                                   const int64_t* out_offsets_host, void* workspace,
-                                  size_t workspace_bytes, void* stream_, bool clear) {
+                                  size_t workspace_bytes, void* stream_, ScatterOp op, float scale) {
+  const bool clear = op == ScatterOp::kClear;
+  const bool sgd = op == ScatterOp::kSgd;
   if (!h || !dense || !idx_ptrs_host || !count_ptrs_host) return DGC_ERR_INVALID_ARG;
   if (!clear && !val_ptrs_host) return DGC_ERR_INVALID_ARG;
   if (num_payloads < 1) return DGC_ERR_INVALID_ARG;
@@ -607,21 +633,24 @@ static dgc_status scatter_regions(dgc_handle* h, float* dense, int32_t num_paylo
   st = sync_workspace(h, workspace, workspace_bytes, out_offsets_host, false, stream);
   if (st != DGC_OK) return st;
   const int64_t* oo = at<int64_t>(workspace, h->lay.out_offsets);
-  int64_t total = 0;  // widest region
+  int64_t widest = 0;  // widest region
   for (int32_t j = 0; j < h->num_tensors; ++j)
-    if (out_offsets_host[j + 1] - out_offsets_host[j] > total) total = out_offsets_host[j + 1] - out_offsets_host[j];
+    if (out_offsets_host[j + 1] - out_offsets_host[j] > widest) widest = out_offsets_host[j + 1] - out_offsets_host[j];
   if (clear) {
-    if (!hip_ok(launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, total,
-                               kScatterClear, nullptr, stream), "launch scatter kernel"))
+    if (!hip_ok(launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, widest,
+                                       kScatterClear, 0.0f, nullptr, stream),
+                "launch scatter kernel"))
       return DGC_ERR_HIP;
   } else if (h->cfg.flags & DGC_FLAG_DETERMINISTIC_ACCUMULATE) {
     for (int32_t w = 0; w < num_payloads; ++w)
-      if (!hip_ok(launch_scatter_regions(dense, h->n, p, w, 1, oo, h->num_tensors, total, kScatterPlainAdd,
-                                 nullptr, stream), "launch scatter kernel"))
+      if (!hip_ok(launch_scatter_regions(dense, h->n, p, w, 1, oo, h->num_tensors, widest,
+                                         sgd ? kScatterPlainSgd : kScatterPlainAdd, scale, nullptr, stream),
+                  "launch scatter kernel"))
         return DGC_ERR_HIP;
   } else {
-    if (!hip_ok(launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, total,
-                               kScatterAtomicAdd, nullptr, stream), "launch scatter kernel"))
+    if (!hip_ok(launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, widest,
+                                       sgd ? kScatterAtomicSgd : kScatterAtomicAdd, scale, nullptr, stream),
+                "launch scatter kernel"))
       return DGC_ERR_HIP;
   }
   return DGC_OK;
@@ -634,7 +663,18 @@ dgc_status dgc_decompress_accumulate_regions(dgc_handle* h, float* dense, int32_
                                              const int64_t* out_offsets_host, void* workspace,
                                              size_t workspace_bytes, void* stream) {
   return scatter_regions(h, dense, num_payloads, idx_ptrs_host, val_ptrs_host, count_ptrs_host,
-                         out_offsets_host, workspace, workspace_bytes, stream, false);
+                         out_offsets_host, workspace, workspace_bytes, stream, ScatterOp::kAccumulate, 0.0f);
+}
+
+dgc_status dgc_sparse_sgd_apply_regions(dgc_handle* h, float* theta, float learning_rate,
+                                        int32_t num_payloads, const int32_t* const* idx_ptrs_host,
+                                        const float* const* val_ptrs_host,
+                                        const int32_t* const* count_ptrs_host,
+                                        const int64_t* out_offsets_host, void* workspace,
+                                        size_t workspace_bytes, void* stream) {
+  if (!(learning_rate == learning_rate)) return DGC_ERR_INVALID_ARG;
+  return scatter_regions(h, theta, num_payloads, idx_ptrs_host, val_ptrs_host, count_ptrs_host,
+                         out_offsets_host, workspace, workspace_bytes, stream, ScatterOp::kSgd, -learning_rate);
 }
 
 dgc_status dgc_dense_clear_regions(dgc_handle* h, float* dense, int32_t num_payloads,
@@ -643,7 +683,7 @@ dgc_status dgc_dense_clear_regions(dgc_handle* h, float* dense, int32_t num_payl
                                    const int64_t* out_offsets_host, void* workspace,
                                    size_t workspace_bytes, void* stream) {
   return scatter_regions(h, dense, num_payloads, idx_ptrs_host, nullptr, count_ptrs_host,
-                         out_offsets_host, workspace, workspace_bytes, stream, true);
+                         out_offsets_host, workspace, workspace_bytes, stream, ScatterOp::kClear, 0.0f);
 }
 
 }  // extern "C"

@@ -160,7 +160,13 @@ struct RegionPayloads {
   const int32_t* counts[kMaxPayloads];
 };
 
-enum ScatterMode : int32_t { kScatterAtomicAdd = 0, kScatterPlainAdd = 1, kScatterClear = 2 };
+enum ScatterMode : int32_t {
+  kScatterAtomicAdd = 0,
+  kScatterPlainAdd = 1,
+  kScatterClear = 2,
+  kScatterAtomicSgd = 3,  // target += scale * value, scale = -learning rate
+  kScatterPlainSgd = 4
+};
 
 // ---- launchers (dgc_kernels.hip) ---------------------------------------------
 hipError_t launch_norm(const float* g, int64_t n, DeviceState* state, double* partials,
@@ -170,12 +176,12 @@ hipError_t launch_stream(const StreamArgs& a, hipStream_t stream);
 hipError_t launch_refine(const RefineArgs& a, int32_t num_blocks, hipStream_t stream);
 hipError_t launch_emit(const EmitArgs& a, int32_t num_blocks, hipStream_t stream);
 hipError_t launch_scatter_pairs(float* dense, int64_t n, const PairPayloads& p, int32_t first,
-                                int32_t num, int64_t max_count, ScatterMode mode,
+                                int32_t num, int64_t max_count, ScatterMode mode, float scale,
                                 uint32_t* diag_flags, hipStream_t stream);
 hipError_t launch_scatter_regions(float* dense, int64_t n, const RegionPayloads& p, int32_t first,
                                   int32_t num, const int64_t* out_offsets_dev, int32_t num_tensors,
-                                  int64_t max_capacity, ScatterMode mode, uint32_t* diag_flags,
-                                  hipStream_t stream);
+                                  int64_t max_capacity, ScatterMode mode, float scale,
+                                  uint32_t* diag_flags, hipStream_t stream);
 
 }  // namespace dgc
 #endif  // DGC_INTERNAL_H_

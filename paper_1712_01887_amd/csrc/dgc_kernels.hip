@@ -940,15 +940,18 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
 // ---------------------------------------------------------------------------
 // Receive side (paper: the sum in Algorithm 3's all-reduce line)
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void scatter_one(float* dense, int64_t n, int32_t i, float x,
+// `scale` multiplies the value first in the two SGD modes (it is -learning rate there:
+// theta - lr*x and theta + (-lr)*x round identically) and is ignored otherwise.
+__device__ __forceinline__ void scatter_one(float* dense, int64_t n, int32_t i, float x, float scale,
                                             ScatterMode mode, uint32_t* diag_flags) {
   if (i < 0 || (int64_t)i >= n) {
     if (diag_flags) atomicOr(diag_flags, (uint32_t)DGC_DIAG_BAD_INDEX);
     return;
   }
-  if (mode == kScatterAtomicAdd) {
+  if (mode == kScatterAtomicSgd || mode == kScatterPlainSgd) x = scale * x;
+  if (mode == kScatterAtomicAdd || mode == kScatterAtomicSgd) {
     unsafeAtomicAdd(dense + i, x);  // hardware float add at the L2 / memory side
-  } else if (mode == kScatterPlainAdd) {
+  } else if (mode == kScatterPlainAdd || mode == kScatterPlainSgd) {
     dense[i] = dense[i] + x;
   } else {
     dense[i] = 0.0f;
@@ -958,14 +961,14 @@ __device__ __forceinline__ void scatter_one(float* dense, int64_t n, int32_t i, 
 // grid = (chunks, payloads)
 __global__ __launch_bounds__(256) void scatter_pairs_kernel(float* dense, int64_t n, PairPayloads p,
                                                             int32_t first, ScatterMode mode,
-                                                            uint32_t* diag_flags) {
+                                                            float scale, uint32_t* diag_flags) {
   const int w = first + blockIdx.y;
   const int64_t count = p.count[w];
   const int32_t* __restrict__ idx = p.idx[w];
   const float* __restrict__ val = p.val[w];
   const int64_t stride = (int64_t)gridDim.x * 256;
   for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < count; q += stride)
-    scatter_one(dense, n, idx[q], mode == kScatterClear ? 0.0f : val[q], mode, diag_flags);
+    scatter_one(dense, n, idx[q], mode == kScatterClear ? 0.0f : val[q], scale, mode, diag_flags);
 }
 
 // Payloads in the per-tensor region layout written by the emit pass.
@@ -974,7 +977,8 @@ __global__ __launch_bounds__(256) void scatter_pairs_kernel(float* dense, int64_
 __global__ __launch_bounds__(256) void scatter_regions_kernel(float* dense, int64_t n,
                                                               RegionPayloads p, int32_t first,
                                                               const int64_t* __restrict__ out_offsets,
-                                                              ScatterMode mode, uint32_t* diag_flags) {
+                                                              ScatterMode mode, float scale,
+                                                              uint32_t* diag_flags) {
   const int w = first + blockIdx.z;
   const int j = blockIdx.y;
   const int64_t region = out_offsets[j];
@@ -997,7 +1001,7 @@ __global__ __launch_bounds__(256) void scatter_regions_kernel(float* dense, int6
     }
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-      if (s0 + q * 256 < end) scatter_one(dense, n, i[q], x[q], mode, diag_flags);
+      if (s0 + q * 256 < end) scatter_one(dense, n, i[q], x[q], scale, mode, diag_flags);
   }
 }
 
@@ -1041,25 +1045,25 @@ hipError_t launch_emit(const EmitArgs& a, int32_t num_blocks, hipStream_t stream
 }
 
 hipError_t launch_scatter_pairs(float* dense, int64_t n, const PairPayloads& p, int32_t first,
-                                int32_t num, int64_t max_count, ScatterMode mode,
+                                int32_t num, int64_t max_count, ScatterMode mode, float scale,
                                 uint32_t* diag_flags, hipStream_t stream) {
   if (num <= 0 || max_count <= 0) return hipSuccess;
   int64_t chunks = ceil_div(max_count, 256 * 4);
   if (chunks > 4096) chunks = 4096;
   hipLaunchKernelGGL(scatter_pairs_kernel, dim3((unsigned)chunks, (unsigned)num), dim3(256), 0, stream,
-                     dense, n, p, first, mode, diag_flags);
+                     dense, n, p, first, mode, scale, diag_flags);
   return hipGetLastError();
 }
 
 hipError_t launch_scatter_regions(float* dense, int64_t n, const RegionPayloads& p, int32_t first,
                                   int32_t num, const int64_t* out_offsets_dev, int32_t num_tensors,
-                                  int64_t max_capacity, ScatterMode mode, uint32_t* diag_flags,
-                                  hipStream_t stream) {
+                                  int64_t max_capacity, ScatterMode mode, float scale,
+                                  uint32_t* diag_flags, hipStream_t stream) {
   if (num <= 0 || max_capacity <= 0) return hipSuccess;
   const int64_t chunks = ceil_div(max_capacity, kScatterChunk);
   if (chunks > 65535 || num_tensors > 65535) return hipErrorInvalidValue;
   hipLaunchKernelGGL(scatter_regions_kernel, dim3((unsigned)chunks, (unsigned)num_tensors, (unsigned)num),
-                     dim3(256), 0, stream, dense, n, p, first, out_offsets_dev, mode, diag_flags);
+                     dim3(256), 0, stream, dense, n, p, first, out_offsets_dev, mode, scale, diag_flags);
   return hipGetLastError();
 }
 

@@ -214,6 +214,55 @@ def test_resume_with_a_new_handle_gives_identical_results():
         x.close()
 
 
+def test_sparse_sgd_apply_matches_oracle():
+    import torch
+    gs = S.ragged_set(14, tensors=9, max_numel=90000)
+    N, lr = 4, 0.1
+    kw = dict(layout_density=0.05, momentum=0.9, density=0.01, seed=8, sample_min=256, sample_max=2048)
+    pairs = [Pair(gs.offsets, **kw) for _ in range(N)]
+    shared = S.gradient(gs, 27, 99, 0)
+    payloads = []
+    for w, p in enumerate(pairs):
+        res = p.step(S.correlated_gradient(gs, 27, w, 0, shared), 0, label=f"sgd w{w}")
+        payloads.append(O.flatten_payload(res))
+    rng = np.random.default_rng(3)
+    theta0 = rng.standard_normal(gs.numel).astype(np.float32)
+    cfg_kw = {k: v for k, v in kw.items() if k != "layout_density"}
+    idx = [p.out_idx for p in pairs]
+    val = [p.out_val for p in pairs]
+    cnt = [p.out_counts for p in pairs]
+    expect = theta0.copy()
+    O.sparse_sgd_apply(expect, payloads, lr)
+    # workers applied in order: bit-exact
+    det = B.Dgc(B.make_config(flags=B.DGC_FLAG_DETERMINISTIC_ACCUMULATE, **cfg_kw), gs.offsets)
+    det.set_layout(pairs[0].layout)
+    theta = torch.from_numpy(theta0).cuda()
+    det.dgc_sparse_sgd_apply_regions(theta, lr, idx, val, cnt)
+    assert np.array_equal(theta.cpu().numpy().view(np.uint32), expect.view(np.uint32))
+    # atomics in any order: within the reordering bound of N + 1 terms
+    acc = B.Dgc(B.make_config(**cfg_kw), gs.offsets)
+    acc.set_layout(pairs[0].layout)
+    theta = torch.from_numpy(theta0).cuda()
+    acc.dgc_sparse_sgd_apply_regions(theta, lr, idx, val, cnt)
+    mags = np.abs(theta0).astype(np.float64)
+    for i, x in payloads:
+        np.add.at(mags, i.astype(np.int64), lr * np.abs(x.astype(np.float64)))
+    assert np.all(np.abs(theta.cpu().numpy().astype(np.float64) - expect) <= 1e-6 * mags)
+    # contiguous pair lists with host counts (one tensor's region each is contiguous only
+    # for a single-tensor set, so use the first pair's first region)
+    one = Pair([0, 5000], layout_density=0.1, momentum=0.0, density=0.02, seed=2, sample_min=4096, sample_max=4096)
+    g = rng.standard_normal(5000).astype(np.float32)
+    r1 = one.step(g, 0, label="sgd single")
+    t0 = rng.standard_normal(5000).astype(np.float32)
+    e1 = t0.copy()
+    O.sparse_sgd_apply(e1, [O.flatten_payload(r1)], 0.25)
+    t = torch.from_numpy(t0).cuda()
+    one.dgc.dgc_sparse_sgd_apply(t, 0.25, [one.out_idx], [one.out_val], [int(one.out_counts.item())])
+    assert np.array_equal(t.cpu().numpy().view(np.uint32), e1.view(np.uint32))
+    for p in pairs + [one]:
+        p.close()
+
+
 def test_bad_payload_index_is_skipped_and_flagged():
     import torch
     d = B.Dgc(B.dgc_config_default(), [0, 1000])

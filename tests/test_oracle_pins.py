@@ -476,6 +476,34 @@ def test_p10_density_one_all_workers_equals_sum_of_v():
     assert np.array_equal(out, total)
 
 
+def test_sparse_sgd_apply_is_dense_sgd_on_the_aggregate():
+    # theta - lr * G_t with G_t = sum of the workers' sparse gradients (Algorithm 3, last two lines)
+    rng = np.random.default_rng(83)
+    n, N, lr = 4000, 4, 0.05
+    theta0 = rng.standard_normal(n).astype(f32)
+    payloads = []
+    G = np.zeros(n, np.float64)
+    for w in range(N):
+        idx = np.sort(rng.choice(n, size=500, replace=False)).astype(np.int32)
+        val = rng.standard_normal(500).astype(f32)
+        payloads.append((idx, val))
+        G[idx] += val
+    theta = theta0.copy()
+    O.sparse_sgd_apply(theta, payloads, lr)
+    np.testing.assert_allclose(theta, theta0 - lr * G, rtol=0, atol=4e-7 * (np.abs(theta0) + lr * 4 * 4).max())
+    untouched = G == 0
+    assert np.array_equal(theta[untouched], theta0[untouched])
+    # an index that occurs once is updated with exactly two roundings
+    once = np.zeros(n, int)
+    for idx, _ in payloads:
+        once[idx] += 1
+    single = once == 1
+    dense32 = np.zeros(n, f32)
+    O.decompress_accumulate(dense32, payloads)
+    expect = theta0 - f32(lr) * dense32
+    assert np.array_equal(theta[single], expect[single])
+
+
 # ---------------------------------------------------------------------------
 # Values the paper prints
 # ---------------------------------------------------------------------------
