@@ -319,6 +319,56 @@ def sparse_sgd_apply(theta: np.ndarray, payloads: Sequence[Tuple[np.ndarray, np.
         np.subtract.at(theta, np.asarray(idx, dtype=np.int64), step)
 
 
+# --------------------------------------------------------------------------
+# Wire format (Section 3.1: "encode() packs the 32-bit nonzero gradient values
+# and 16-bit run lengths of zeros"; Table 3 footnote)
+# --------------------------------------------------------------------------
+RUN_MAX = 65535
+"""Largest zero-run a 16-bit field holds."""
+
+
+def encode(indices: np.ndarray, values: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Entries (run, value) of the flattened sparse gradient, in index order.
+
+    `run` zeros precede `value`.  The paper does not say what happens when more
+    than 65535 zeros separate two values; the reading used here: an entry
+    (65535, 0.0) stands for 65535 zeros followed by one explicit zero element,
+    i.e. it advances 65536 positions, and as many of them as needed precede the
+    real entry.  Trailing zeros are not encoded (the length is known)."""
+    order = np.argsort(indices, kind="stable")
+    idx = np.asarray(indices, dtype=np.int64)[order]
+    val = np.asarray(values, dtype=np.float32)[order]
+    runs: List[int] = []
+    vals: List[np.float32] = []
+    pos = 0                                  # next position not yet described
+    for i, x in zip(idx.tolist(), val.tolist()):
+        gap = i - pos
+        assert gap >= 0, "indices must be distinct"
+        while gap > RUN_MAX:
+            runs.append(RUN_MAX)
+            vals.append(np.float32(0.0))
+            gap -= RUN_MAX + 1
+        runs.append(gap)
+        vals.append(np.float32(x))
+        pos = i + 1
+    return np.asarray(runs, dtype=np.uint16), np.asarray(vals, dtype=np.float32)
+
+
+def decode_accumulate(dense: np.ndarray, runs: np.ndarray, vals: np.ndarray) -> None:
+    """dense[position] += value for every entry, binary32, entries in order."""
+    assert dense.dtype == np.float32
+    pos = 0
+    for r, x in zip(runs.tolist(), vals.tolist()):
+        pos += r
+        dense[pos] = dense[pos] + np.float32(x)
+        pos += 1
+
+
+def encoded_bytes(entries: int) -> int:
+    """Six bytes per entry: a 32-bit value and a 16-bit run length."""
+    return 6 * int(entries)
+
+
 def compression_ratio(n: int, pairs: int, bytes_per_pair: int) -> float:
     """Dense bytes over payload bytes (the tables print this reciprocal of the
     formula of Section 4.1, e.g. 277x)."""

@@ -505,6 +505,62 @@ def test_sparse_sgd_apply_is_dense_sgd_on_the_aggregate():
 
 
 # ---------------------------------------------------------------------------
+# Wire format: 32-bit values + 16-bit zero-run lengths (Section 3.1)
+# ---------------------------------------------------------------------------
+def brute_decode(n, runs, vals):
+    out = [0.0] * n
+    pos = 0
+    for r, x in zip(runs, vals):
+        for _ in range(int(r)):
+            pos += 1                       # a zero
+        out[pos] = float(x)
+        pos += 1
+    return out
+
+
+def test_encode_hand_example():
+    # dense vector 0 0 5 0 0 0 -2 7 0 -> runs 2, 3, 0 and values 5, -2, 7 (trailing zero not sent)
+    runs, vals = O.encode(np.array([7, 2, 6]), np.array([7.0, 5.0, -2.0], f32))
+    assert runs.tolist() == [2, 3, 0] and vals.tolist() == [5.0, -2.0, 7.0]
+    assert runs.dtype == np.uint16 and vals.dtype == f32
+    assert O.encoded_bytes(len(runs)) == 18
+    assert brute_decode(9, runs, vals) == [0, 0, 5, 0, 0, 0, -2, 7, 0]
+
+
+def test_encode_long_runs_use_filler_entries():
+    # first value after exactly 65535 zeros fits one entry; after 65536 it needs a filler
+    r, v = O.encode(np.array([65535]), np.array([1.0], f32))
+    assert r.tolist() == [65535] and v.tolist() == [1.0]
+    r, v = O.encode(np.array([65536]), np.array([1.0], f32))
+    assert r.tolist() == [65535, 0] and v.tolist() == [0.0, 1.0]
+    r, v = O.encode(np.array([3, 3 + 1 + 200000]), np.array([1.0, 2.0], f32))
+    assert r.tolist() == [3, 65535, 65535, 65535, 200000 - 3 * 65536] and v.tolist() == [1.0, 0.0, 0.0, 0.0, 2.0]
+    dense = np.zeros(200010, f32)
+    O.decode_accumulate(dense, r, v)
+    assert dense[3] == 1.0 and dense[200004] == 2.0 and np.count_nonzero(dense) == 2
+
+
+def test_encode_decode_round_trip_random():
+    rng = np.random.default_rng(91)
+    for trial in range(30):
+        n = int(rng.integers(1, 400000))
+        k = int(rng.integers(0, min(n, 300) + 1))
+        idx = rng.choice(n, size=k, replace=False)
+        val = rng.standard_normal(k).astype(f32)
+        runs, vals = O.encode(idx, val)
+        expect = np.zeros(n, f32)
+        expect[idx] = val
+        if n <= 5000:
+            assert brute_decode(n, runs, vals) == expect.tolist()
+        got = np.ones(n, f32)
+        O.decode_accumulate(got, runs, vals)
+        assert np.array_equal(got, expect + f32(1.0))            # accumulates, does not overwrite
+        fillers = int(np.count_nonzero((runs == 65535) & (vals == 0)))
+        assert len(runs) <= k + n // 65536 and len(runs) >= k
+        assert len(runs) - k <= fillers
+
+
+# ---------------------------------------------------------------------------
 # Values the paper prints
 # ---------------------------------------------------------------------------
 def _golden_rows(name):
