@@ -68,6 +68,8 @@ def parse_args():
     ap.add_argument("--sample-block", type=int, default=None, help="override dgc_config.sample_block")
     ap.add_argument("--refine-alpha", type=float, default=None,
                     help="switch the Section 5 re-threshold on (dgc_config.refine_alpha); off by default")
+    ap.add_argument("--sorted", action="store_true",
+                    help="emit every tensor's pairs in ascending index order (DGC_FLAG_SORTED_OUTPUT)")
     ap.add_argument("--profile-only", action="store_true",
                     help="skip the CPU baseline and the event-instrumented pass (for rocprofv3 runs)")
     return ap.parse_args()
@@ -86,7 +88,7 @@ def cpu_baseline(name, gs, cfg_kw, n_workers, scales, seed):
     from oracle import dgc_oracle as O
     from paper_1712_01887_amd import synthetic as S
 
-    cfg = O.OracleConfig(**cfg_kw)
+    cfg = O.OracleConfig(**{k: v for k, v in cfg_kw.items() if k != "flags"})   # its payload is always ascending
     u = np.zeros(gs.numel, np.float32)
     v = np.zeros(gs.numel, np.float32)
     grads = [S.gradient(gs, seed, 0, it, scales) for it in range(4)]
@@ -144,6 +146,9 @@ def main():
     if args.refine_alpha:
         cfg_kw["refine_alpha"] = args.refine_alpha
         description += f", re-threshold when more than {args.refine_alpha:g} k pass"
+    if args.sorted:
+        cfg_kw["flags"] = cfg_kw.get("flags", 0) | B.DGC_FLAG_SORTED_OUTPUT
+        description += ", sorted payload"
     clip = cfg_kw.get("clip_threshold", 0.0) > 0.0
 
     dgc = B.Dgc(B.make_config(**cfg_kw), gs.offsets)

@@ -47,7 +47,10 @@ enum {
   DGC_FLAG_NESTEROV = 1u << 0,          /* Algorithm 4: U <- m(U+G); V <- V+U+G          */
   DGC_FLAG_NO_FACTOR_MASKING = 1u << 1, /* leave U untouched (Section 3.3 switched off)   */
   DGC_FLAG_EXACT_SELECT = 1u << 2,      /* threshold from the whole tensor, not a sample  */
-  DGC_FLAG_DETERMINISTIC_ACCUMULATE = 1u << 3 /* receive side adds workers in order       */
+  DGC_FLAG_DETERMINISTIC_ACCUMULATE = 1u << 3, /* receive side adds workers in order      */
+  DGC_FLAG_SORTED_OUTPUT = 1u << 4      /* pairs of a tensor in ascending index order; the
+                                           payload is then identical on every run, and a full
+                                           region keeps the lowest indices                   */
 };
 
 /* dgc_diagnostics.flags */
@@ -161,9 +164,11 @@ dgc_status dgc_recommended_payload_layout(const dgc_handle* h, double density,
  *              region; read during the call (the caller may reuse it afterwards)
  *   out_counts device, int32[num_tensors]: elements of tensor j that passed the
  *              mask.  Pairs [out_offsets[j], out_offsets[j] + min(count_j, capacity_j))
- *              are valid, in unspecified order.  An element that passed but found the
+ *              are valid, in unspecified order (ascending indices with
+ *              DGC_FLAG_SORTED_OUTPUT).  An element that passed but found the
  *              region full is neither emitted nor cleared (it stays in u, v) and
- *              DGC_DIAG_OVERFLOW is raised.
+ *              DGC_DIAG_OVERFLOW is raised; which elements those are depends on the
+ *              order of arrival, with DGC_FLAG_SORTED_OUTPUT they are the highest indices.
  *   out_thr    device, float[num_tensors], or NULL
  *   iteration  t: with the seed and the tensor index it fixes the sample positions
  *   workspace  device, >= dgc_workspace_bytes, 256-byte aligned; it must not be

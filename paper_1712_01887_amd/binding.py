@@ -30,6 +30,7 @@ DGC_FLAG_NESTEROV = 1 << 0
 DGC_FLAG_NO_FACTOR_MASKING = 1 << 1
 DGC_FLAG_EXACT_SELECT = 1 << 2
 DGC_FLAG_DETERMINISTIC_ACCUMULATE = 1 << 3
+DGC_FLAG_SORTED_OUTPUT = 1 << 4
 
 DGC_DIAG_OVERFLOW = 1 << 0
 DGC_DIAG_NONFINITE = 1 << 1
@@ -367,8 +368,9 @@ class PreparedStep:
         self.accumulate_and_clear = accumulate_and_clear
 
 
-def gather_payload(layout: Sequence[int], out_idx, out_val, out_counts):
-    """Host copy of a region-layout payload as per-tensor (indices, values) sorted by index.
+def gather_payload(layout: Sequence[int], out_idx, out_val, out_counts, sort: bool = True):
+    """Host copy of a region-layout payload as per-tensor (indices, values), sorted by index
+    unless `sort` is false (then in the order the library left them).
     Test/report helper: it waits for the device."""
     idx = out_idx.cpu().numpy()
     val = out_val.cpu().numpy()
@@ -378,7 +380,7 @@ def gather_payload(layout: Sequence[int], out_idx, out_val, out_counts):
         lo = layout[j]
         c = min(int(cnt[j]), layout[j + 1] - lo)
         i = idx[lo:lo + c]
-        order = np.argsort(i, kind="stable")
+        order = np.argsort(i, kind="stable") if sort else np.arange(c)
         per_idx.append(i[order].copy())
         per_val.append(val[lo:lo + c][order].copy())
     return per_idx, per_val, cnt

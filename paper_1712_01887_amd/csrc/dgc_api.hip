@@ -126,6 +126,7 @@ void build_layout(dgc_handle* h) {
   l.emit_blocks = off;  off = align_up(off + sizeof(EmitBlock) * h->emit_blocks.size());
   l.counters = off;     off = align_up(off + sizeof(uint32_t) * kCounterStride * T);
   l.refine_counters = off; off = align_up(off + sizeof(uint32_t) * kCounterStride * T);
+  l.block_counts = off; off = align_up(off + sizeof(uint32_t) * h->emit_blocks.size());
   l.mask = off;         off = align_up(off + sizeof(uint16_t) * 64 * tiles);
   l.total = off;
 }
@@ -459,8 +460,22 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
       return DGC_ERR_HIP;
   }
 
+  // Sorted output: a count pass over the final mask tells every emit workgroup where its
+  // part of the tensor's region starts.
+  const bool sorted = (c.flags & DGC_FLAG_SORTED_OUTPUT) != 0;
+  if (sorted) {
+    CountArgs ca{};
+    ca.blocks = at<EmitBlock>(workspace, h->lay.emit_blocks);
+    ca.mask = ta.mask;
+    ca.offsets = ta.offsets;
+    ca.block_counts = at<uint32_t>(workspace, h->lay.block_counts);
+    if (!hip_ok(launch_count(ca, (int32_t)h->emit_blocks.size(), stream), "launch count kernel"))
+      return DGC_ERR_HIP;
+  }
+
   EmitArgs ea{};
   ea.blocks = at<EmitBlock>(workspace, h->lay.emit_blocks);
+  ea.block_counts = at<uint32_t>(workspace, h->lay.block_counts);
   ea.counters = at<uint32_t>(workspace, h->lay.counters);
   ea.u = u;
   ea.v = v;
@@ -472,7 +487,7 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   ea.out_counts = out_counts;
   ea.state = state;
   ea.factor_masking = (c.flags & DGC_FLAG_NO_FACTOR_MASKING) ? 0 : 1;
-  if (!hip_ok(launch_emit(ea, (int32_t)h->emit_blocks.size(), stream), "launch emit kernel"))
+  if (!hip_ok(launch_emit(ea, (int32_t)h->emit_blocks.size(), sorted, stream), "launch emit kernel"))
     return DGC_ERR_HIP;
   if (ev && !hip_ok(hipEventRecord(ev[4], stream), "record event")) return DGC_ERR_HIP;
   return DGC_OK;

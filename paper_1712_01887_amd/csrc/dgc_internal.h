@@ -76,7 +76,8 @@ struct TensorPlan {
 };
 
 struct WorkspaceLayout {
-  size_t state, partials, offsets, out_offsets, plans, thr, tile_info, emit_blocks, counters, refine_counters, mask, total;
+  size_t state, partials, offsets, out_offsets, plans, thr, tile_info, emit_blocks, counters, refine_counters,
+      block_counts, mask, total;
 };
 
 struct SelectArgs {
@@ -146,6 +147,14 @@ struct EmitArgs {
   int32_t* out_counts;         // device, T
   DeviceState* state;
   int32_t factor_masking;
+  const uint32_t* block_counts;  // sorted output: mask bits of every workgroup's run (count pass)
+};
+
+struct CountArgs {
+  const EmitBlock* blocks;
+  const uint16_t* mask;
+  const int64_t* offsets;
+  uint32_t* block_counts;      // device, one word per entry of the emit work list
 };
 
 struct PairPayloads {
@@ -174,7 +183,8 @@ hipError_t launch_norm(const float* g, int64_t n, DeviceState* state, double* pa
 hipError_t launch_select(const SelectArgs& a, int32_t num_tensors, hipStream_t stream);
 hipError_t launch_stream(const StreamArgs& a, hipStream_t stream);
 hipError_t launch_refine(const RefineArgs& a, int32_t num_blocks, hipStream_t stream);
-hipError_t launch_emit(const EmitArgs& a, int32_t num_blocks, hipStream_t stream);
+hipError_t launch_count(const CountArgs& a, int32_t num_blocks, hipStream_t stream);
+hipError_t launch_emit(const EmitArgs& a, int32_t num_blocks, bool sorted, hipStream_t stream);
 hipError_t launch_scatter_pairs(float* dense, int64_t n, const PairPayloads& p, int32_t first,
                                 int32_t num, int64_t max_count, ScatterMode mode, float scale,
                                 uint32_t* diag_flags, hipStream_t stream);

@@ -809,14 +809,103 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
 // ---------------------------------------------------------------------------
 // One workgroup per entry of a host-built list of (tensor, first tile): it owns up
 // to kEmitTiles consecutive tiles of that tensor, counts the mask bits that fall
-// inside the tensor reserves that
-// many slots of the tensor's payload region with ONE atomic, then for every set
-// bit moves v' into the payload and clears v and u.  An element that finds the
-// region full is left untouched (it stays in u, v) and the overflow flag is set.
+// inside the tensor, obtains that many slots of the tensor's payload region, then
+// for every set bit moves v' into the payload and clears v and u.  An element that
+// finds the region full is left untouched (it stays in u, v) and the overflow flag
+// is set.
+//
+// Two ways of handing out the slots:
+//   unordered  ONE atomic per workgroup on the tensor's counter reserves the slots
+//              in order of arrival; pairs land in unspecified order.
+//   sorted     a count pass has left every workgroup's number of bits in
+//              block_counts; a workgroup starts after the sum of its predecessors
+//              within the tensor and places its own elements in index order, so a
+//              region holds ascending indices, the result is the same on every
+//              run, and a full region keeps the lowest indices.
+
+// This lane's mask word of tile t with the bits outside tensor [lo, hi) removed.
+__device__ __forceinline__ uint32_t tensor_tile_word(const uint16_t* __restrict__ mask, int64_t t, int lane,
+                                                     int64_t lo, int64_t hi) {
+  constexpr int kBits = kStreamUnroll * 4;
+  uint32_t w = mask[t * 64 + lane];
+  if (w && (t * kWaveTile < lo || (t + 1) * kWaveTile > hi)) {  // tile shared with a neighbour tensor
+    uint32_t keep = 0;
+    for (int q = 0; q < kBits; ++q) {
+      const int64_t e = tile_element(t, lane, q);
+      if (e >= lo && e < hi) keep |= 1u << q;
+    }
+    w &= keep;
+  }
+  return w;
+}
+
+// Count pass of the sorted output: mask bits of every emit workgroup's run.
+__global__ __launch_bounds__(kEmitThreads) void count_kernel(CountArgs a) {
+  constexpr int kWaves = kEmitThreads / 64;
+  constexpr int kPerWave = kEmitTiles / kWaves;
+  __shared__ int red[kWaves];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const EmitBlock blk = a.blocks[blockIdx.x];
+  const int64_t lo = a.offsets[blk.tensor];
+  const int64_t hi = a.offsets[blk.tensor + 1];
+  const int64_t t1 = (hi - 1) / kWaveTile;
+  int cnt = 0;
+#pragma unroll
+  for (int i = 0; i < kPerWave; ++i) {
+    const int64_t t = (int64_t)blk.first_tile + wave + i * kWaves;
+    if (t <= t1) cnt += __popc(tensor_tile_word(a.mask, t, lane, lo, hi));
+  }
+  for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_down(cnt, d);
+  if (lane == 0) red[wave] = cnt;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int total = 0;
+    for (int w = 0; w < kWaves; ++w) total += red[w];
+    a.block_counts[blockIdx.x] = (uint32_t)total;
+  }
+}
+
+// Moves the `in_win` elements listed in `list` to slots slot0, slot0 + 1, ... of the
+// tensor's region [region, region + cap): reads v', writes the pair, clears v and u.
+// Returns true if some element found the region full.
+__device__ __forceinline__ bool emit_move(const EmitArgs& a, const int32_t* list, int in_win, int64_t slot0,
+                                          int64_t region, int64_t cap) {
+  float* __restrict__ u = a.u;
+  float* __restrict__ v = a.v;
+  int32_t* __restrict__ out_idx = a.out_idx;
+  float* __restrict__ out_val = a.out_val;
+  bool overflow = false;
+  for (int p0 = threadIdx.x; p0 < in_win; p0 += 4 * kEmitThreads) {
+    int32_t e[4];
+    float x[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int p = p0 + k * kEmitThreads;
+      e[k] = p < in_win ? list[p] : -1;
+      if (e[k] >= 0 && slot0 + p >= cap) {  // region full: leave the element where it is
+        e[k] = -1;
+        overflow = true;
+      }
+      x[k] = e[k] >= 0 ? v[e[k]] : 0.0f;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (e[k] >= 0) {
+        const int64_t slot = slot0 + p0 + k * kEmitThreads;
+        out_idx[region + slot] = e[k];
+        out_val[region + slot] = x[k];
+        v[e[k]] = 0.0f;
+        if (a.factor_masking) u[e[k]] = 0.0f;
+      }
+    }
+  }
+  return overflow;
+}
+
 __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
   constexpr int kWaves = kEmitThreads / 64;
   constexpr int kPerWave = kEmitTiles / kWaves;
-  constexpr int kBits = kStreamUnroll * 4;
   __shared__ int wave_tot[kWaves];
   __shared__ int block_base;
   __shared__ int32_t list[kEmitList];
@@ -829,31 +918,13 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
   const int64_t hi = a.offsets[j + 1];
   const int64_t t1 = (hi - 1) / kWaveTile;
   const int64_t first = blk.first_tile;
-  const uint16_t* __restrict__ mask = a.mask;
-  float* __restrict__ u = a.u;
-  float* __restrict__ v = a.v;
-  int32_t* __restrict__ out_idx = a.out_idx;
-  float* __restrict__ out_val = a.out_val;
-  unsigned long long* ctr =
-      reinterpret_cast<unsigned long long*>(a.counters + (size_t)j * kCounterStride);
 
   uint32_t word[kPerWave];
   int cnt = 0;
 #pragma unroll
   for (int i = 0; i < kPerWave; ++i) {
     const int64_t t = first + wave + i * kWaves;
-    uint32_t w = 0;
-    if (t <= t1) {
-      w = mask[t * 64 + lane];
-      if (t * kWaveTile < lo || (t + 1) * kWaveTile > hi) {  // tile shared with a neighbour tensor
-        uint32_t keep = 0;
-        for (int q = 0; q < kBits; ++q) {
-          const int64_t e = tile_element(t, lane, q);
-          if (e >= lo && e < hi) keep |= 1u << q;
-        }
-        w &= keep;
-      }
-    }
+    const uint32_t w = t <= t1 ? tensor_tile_word(a.mask, t, lane, lo, hi) : 0u;
     word[i] = w;
     cnt += __popc(w);
   }
@@ -876,6 +947,7 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
     // takes the arrival ticket (high word: workgroups done).  The workgroup that arrives
     // last for this tensor publishes the count and leaves the counter at zero for the
     // next call.  Only atomics carry information between workgroups, so no fence is needed.
+    unsigned long long* ctr = reinterpret_cast<unsigned long long*>(a.counters + (size_t)j * kCounterStride);
     const unsigned long long old = atomicAdd(ctr, (unsigned long long)(uint32_t)total | (1ull << 32));
     block_base = (int)(uint32_t)old;
     if ((uint32_t)(old >> 32) == (uint32_t)blk.tensor_blocks - 1u) {
@@ -908,30 +980,132 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
     }
     __syncthreads();
     const int in_win = total - win < kEmitList ? total - win : kEmitList;
-    for (int p0 = threadIdx.x; p0 < in_win; p0 += 4 * kEmitThreads) {
-      int32_t e[4];
-      float x[4];
+    overflow |= emit_move(a, list, in_win, base_slot + win, region, cap);
+    __syncthreads();
+  }
+  if (overflow) atomicOr(&a.state->flags, (uint32_t)DGC_DIAG_OVERFLOW);
+}
+
+// Sorted variant.  The workgroup's mask words are parked in LDS; everything that
+// follows walks the tiles one at a time from there, which keeps the register count low
+// (the kernel is latency-bound: what matters is how many workgroups a CU holds).
+__global__ __launch_bounds__(kEmitThreads) void emit_sorted_kernel(EmitArgs a) {
+  constexpr int kWaves = kEmitThreads / 64;
+  constexpr int kPerWave = kEmitTiles / kWaves;
+  constexpr int kRows = kStreamUnroll;  // rounds of 256 elements per tile
+  static_assert(kEmitTiles <= 64, "one wavefront scans the tile totals");
+  __shared__ uint16_t words[kEmitTiles * 64];
+  __shared__ int tile_tot[kEmitTiles];
+  __shared__ int tile_base[kEmitTiles];
+  __shared__ int wave_tot[kWaves];
+  __shared__ int block_base, block_total;
+  __shared__ int32_t list[kEmitList];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const EmitBlock blk = a.blocks[blockIdx.x];
+  const int j = blk.tensor;
+  const int64_t lo = a.offsets[j];
+  const int64_t hi = a.offsets[j + 1];
+  const int64_t t1 = (hi - 1) / kWaveTile;
+  const int64_t first = blk.first_tile;
+
+  // slots taken by the workgroups before this one within the tensor (count pass)
+  const int in_tensor = (int)((first - lo / kWaveTile) / kEmitTiles);
+  const uint32_t* __restrict__ prior = a.block_counts + ((int64_t)blockIdx.x - in_tensor);
+  int before = 0;
+  for (int b = threadIdx.x; b < in_tensor; b += kEmitThreads) before += (int)prior[b];
+
+  static_assert(kPerWave % 2 == 0, "tile totals are reduced two to a register");
+  {
+    uint32_t word[kPerWave];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int p = p0 + k * kEmitThreads;
-        e[k] = p < in_win ? list[p] : -1;
-        if (e[k] >= 0 && base_slot + win + p >= cap) {  // region full: leave the element where it is
-          e[k] = -1;
-          overflow = true;
-        }
-        x[k] = e[k] >= 0 ? v[e[k]] : 0.0f;
-      }
+    for (int i = 0; i < kPerWave; ++i) {
+      const int64_t t = first + wave + i * kWaves;
+      word[i] = t <= t1 ? tensor_tile_word(a.mask, t, lane, lo, hi) : 0u;
+    }
+    // elements per tile: the lanes' bit counts of two tiles share a register (16 bits each,
+    // a tile holds at most 1024) and are summed over the wavefront by a butterfly
+    uint32_t pair[kPerWave / 2];
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        if (e[k] >= 0) {
-          const int64_t slot = base_slot + win + p0 + k * kEmitThreads;
-          out_idx[region + slot] = e[k];
-          out_val[region + slot] = x[k];
-          v[e[k]] = 0.0f;
-          if (a.factor_masking) u[e[k]] = 0.0f;
+    for (int i = 0; i < kPerWave; ++i) {
+      words[(wave + i * kWaves) * 64 + lane] = (uint16_t)word[i];
+      if (i & 1) pair[i / 2] |= (uint32_t)__popc(word[i]) << 16;
+      else pair[i / 2] = (uint32_t)__popc(word[i]);
+    }
+    for (int d = 32; d >= 1; d >>= 1) {
+#pragma unroll
+      for (int i = 0; i < kPerWave / 2; ++i) pair[i] += __shfl_xor(pair[i], d);
+      before += __shfl_xor(before, d);
+    }
+    if (lane == 0) {
+      wave_tot[wave] = before;
+#pragma unroll
+      for (int i = 0; i < kPerWave; ++i)
+        tile_tot[wave + i * kWaves] = (int)((pair[i / 2] >> (16 * (i & 1))) & 0xFFFFu);
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    const int own = lane < kEmitTiles ? tile_tot[lane] : 0;
+    int incl = own;
+    for (int d = 1; d < 64; d <<= 1) {
+      const int t = __shfl_up(incl, d);
+      if (lane >= d) incl += t;
+    }
+    if (lane < kEmitTiles) tile_base[lane] = incl - own;
+    if (lane == 63) {
+      int base = 0;
+      for (int w = 0; w < kWaves; ++w) base += wave_tot[w];
+      block_base = base;
+      block_total = incl;
+      if (in_tensor == blk.tensor_blocks - 1) a.out_counts[j] = base + incl;
+    }
+  }
+  __syncthreads();
+  const int total = block_total;
+  if (total == 0) return;
+  const int64_t region = a.out_offsets[j];
+  const int64_t cap = a.out_offsets[j + 1] - region;
+  const int64_t base_slot = block_base;
+  bool overflow = false;
+  for (int win = 0; win < total; win += kEmitList) {
+    // Index order inside a tile is row (round of 256 elements), lane, component: an
+    // element's position is the tile's base, plus the rows before it, plus the bits of
+    // its row in lower lanes (counted from the votes), plus the lower bits of its nibble.
+#pragma unroll 1
+    for (int i = 0; i < kPerWave; ++i) {
+      const int tl = wave + i * kWaves;
+      if (tile_tot[tl] == 0) continue;
+      const uint32_t w = words[tl * 64 + lane];
+      const int64_t t = first + tl;
+      int row_base = tile_base[tl];
+#pragma unroll
+      for (int r = 0; r < kRows; ++r) {
+        const uint32_t nib = (w >> (4 * r)) & 0xFu;
+        if (__ballot(nib != 0) == 0) continue;  // nothing in this row of the tile
+        int lower = 0, row = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const unsigned long long vote = __ballot((nib >> c) & 1u);
+          lower += (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(vote >> 32),
+                                                  __builtin_amdgcn_mbcnt_lo((uint32_t)vote, 0u));
+          row += __popcll(vote);
         }
+        int pos = row_base + lower;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          if ((nib >> c) & 1u) {
+            if (pos >= win && pos < win + kEmitList) list[pos - win] = (int32_t)tile_element(t, lane, 4 * r + c);
+            ++pos;
+          }
+        }
+        row_base += row;
       }
     }
+    __syncthreads();
+    const int in_win = total - win < kEmitList ? total - win : kEmitList;
+    overflow |= emit_move(a, list, in_win, base_slot + win, region, cap);
     __syncthreads();
   }
   if (overflow) atomicOr(&a.state->flags, (uint32_t)DGC_DIAG_OVERFLOW);
@@ -1039,8 +1213,16 @@ hipError_t launch_refine(const RefineArgs& a, int32_t num_blocks, hipStream_t st
   return hipGetLastError();
 }
 
-hipError_t launch_emit(const EmitArgs& a, int32_t num_blocks, hipStream_t stream) {
-  hipLaunchKernelGGL(emit_kernel, dim3((unsigned)num_blocks), dim3(kEmitThreads), 0, stream, a);
+hipError_t launch_count(const CountArgs& a, int32_t num_blocks, hipStream_t stream) {
+  hipLaunchKernelGGL(count_kernel, dim3((unsigned)num_blocks), dim3(kEmitThreads), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_emit(const EmitArgs& a, int32_t num_blocks, bool sorted, hipStream_t stream) {
+  if (sorted)
+    hipLaunchKernelGGL(emit_sorted_kernel, dim3((unsigned)num_blocks), dim3(kEmitThreads), 0, stream, a);
+  else
+    hipLaunchKernelGGL(emit_kernel, dim3((unsigned)num_blocks), dim3(kEmitThreads), 0, stream, a);
   return hipGetLastError();
 }
 

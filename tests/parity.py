@@ -9,7 +9,9 @@ Comparison bar
     from its saved state with the library's scale, and that run must match
     bit-exactly; the scales themselves must agree to 1e-6 relative.
 Payload order inside a tensor's region is unspecified, so pairs are compared
-after sorting by index.
+after sorting by index; with DGC_FLAG_SORTED_OUTPUT the regions are compared as
+the library left them, and a full region must hold the lowest indices, as in
+the oracle.
 """
 
 from __future__ import annotations
@@ -47,6 +49,7 @@ class Pair:
         self.T = len(self.offsets) - 1
         self.cfg_kw = dict(cfg_kw)
         self.ocfg = oracle_config(**cfg_kw)
+        self.sorted = bool(cfg_kw.get("flags", 0) & B.DGC_FLAG_SORTED_OUTPUT)
         self.dgc = B.Dgc(B.make_config(**cfg_kw), self.offsets)
         if capacities is not None:
             layout = np.concatenate([[0], np.cumsum(capacities)]).tolist()
@@ -81,7 +84,8 @@ class Pair:
         self.dgc.dgc_compress(g_dev, self.u, self.v, self.out_idx, self.out_val, self.out_counts,
                               self.out_thr, iteration)
         diag = self.dgc.dgc_get_diagnostics()
-        per_idx, per_val, counts = B.gather_payload(self.layout, self.out_idx, self.out_val, self.out_counts)
+        per_idx, per_val, counts = B.gather_payload(self.layout, self.out_idx, self.out_val, self.out_counts,
+                                                    sort=not self.sorted)
         thr = self.out_thr.cpu().numpy()
 
         u0, v0 = self.ou.copy(), self.ov.copy()
@@ -106,7 +110,7 @@ class Pair:
         assert np.array_equal(counts.astype(np.int64), res.counts), (label, "counts")
         overflow = bool(diag.flags & B.DGC_DIAG_OVERFLOW)
         assert overflow == res.overflow, (label, "overflow flag")
-        if not res.overflow:
+        if self.sorted or not res.overflow:
             for j in range(self.T):
                 assert np.array_equal(per_idx[j], res.indices[j]), (label, "index set", j)
                 assert np.array_equal(per_val[j].view(np.uint32), res.values[j].view(np.uint32)), \

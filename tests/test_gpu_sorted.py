@@ -1,0 +1,107 @@
+"""GPU parity of the sorted payload (DGC_FLAG_SORTED_OUTPUT): every tensor's region
+must hold the oracle's pairs in the oracle's order (ascending index), without any
+sorting on the test's side, and a full region must keep the lowest indices.
+Run with `-m gpu` on an MI355X."""
+
+import numpy as np
+import pytest
+
+from oracle import dgc_oracle as O
+from paper_1712_01887_amd import binding as B
+from paper_1712_01887_amd import synthetic as S
+from tests.parity import Pair, say
+
+pytestmark = pytest.mark.gpu
+
+SORTED = B.DGC_FLAG_SORTED_OUTPUT
+
+
+@pytest.mark.parametrize("flags", [SORTED, SORTED | B.DGC_FLAG_NESTEROV | B.DGC_FLAG_NO_FACTOR_MASKING,
+                                   SORTED | B.DGC_FLAG_EXACT_SELECT])
+@pytest.mark.parametrize("density", [0.001, 0.05, 1.0])
+def test_sorted_ragged_set(flags, density):
+    gs = S.ragged_set(3)
+    p = Pair(gs.offsets, layout_density=max(density, 0.05), momentum=0.9, density=density, flags=flags,
+             seed=11, sample_min=256, sample_max=2048, sample_block=16)
+    for it in range(3):
+        p.step(S.gradient(gs, 21, 0, it), it, label=f"sorted ragged flags={flags} d={density} it{it}")
+    p.close()
+
+
+def test_sorted_edge_sizes():
+    for sizes in ([1], [1023], [1024], [1025], [4096, 3], [5, 1019, 1, 2047, 7], [32768, 32769, 1, 65536]):
+        offsets = np.concatenate([[0], np.cumsum(sizes)])
+        p = Pair(offsets, layout_density=1.0, momentum=0.9, density=0.3, seed=1, sample_min=64, sample_max=256,
+                 flags=SORTED)
+        rng = np.random.default_rng(sum(sizes))
+        for it in range(2):
+            p.step(rng.standard_normal(offsets[-1]).astype(np.float32), it, label=f"sorted sizes={sizes} it{it}")
+        p.close()
+
+
+def test_sorted_overflow_keeps_lowest_indices_like_the_oracle():
+    gs = S.ragged_set(6, tensors=10)
+    caps = [max(1, O.topk_count(0.05, s) // 2) for s in gs.sizes]
+    p = Pair(gs.offsets, capacities=caps, momentum=0.9, density=0.05, seed=9,
+             flags=SORTED | B.DGC_FLAG_EXACT_SELECT)
+    u0 = (0.1 * S.gradient(gs, 23, 1, 0)).astype(np.float32)
+    v0 = (0.1 * S.gradient(gs, 23, 2, 0)).astype(np.float32)
+    p.set_state(u0, v0)
+    for it in range(3):                                   # what overflowed stays in v and passes again
+        res = p.step(S.gradient(gs, 23, 0, it), it, label=f"sorted overflow it{it}")
+        assert res.overflow
+    p.close()
+
+
+def test_sorted_with_rethreshold():
+    gs = S.ragged_set(12, tensors=14, max_numel=120000)
+    p = Pair(gs.offsets, momentum=0.9, density=0.01, seed=21, sample_min=64, sample_max=64, sample_block=4,
+             refine_alpha=1.0, flags=SORTED)
+    refined = 0
+    for it in range(4):
+        res = p.step(S.gradient(gs, 26, 0, it), it, label=f"sorted refine it{it}")
+        refined += sum(res.refined)
+    assert refined >= 3
+    p.close()
+
+
+def test_sorted_payload_is_identical_on_every_run():
+    import torch
+    gs = S.ragged_set(15, tensors=16, max_numel=300000)
+    kw = dict(layout_density=0.02, momentum=0.9, density=0.01, seed=5, sample_min=256, sample_max=2048,
+              flags=SORTED)
+    g = [S.gradient(gs, 28, 0, it) for it in range(3)]
+    runs = []
+    for rep in range(3):
+        p = Pair(gs.offsets, **kw)
+        p.out_idx.fill_(-7)
+        p.out_val.fill_(float("nan"))
+        for it in range(3):
+            p.dgc.dgc_compress(torch.from_numpy(g[it]).cuda(), p.u, p.v, p.out_idx, p.out_val, p.out_counts,
+                               p.out_thr, it)
+        runs.append((p.out_idx.cpu().numpy().copy(), p.out_val.cpu().numpy().view(np.uint32).copy(),
+                     p.out_counts.cpu().numpy().copy()))
+        p.close()
+    for r in runs[1:]:
+        for a, b in zip(runs[0], r):
+            assert np.array_equal(a, b)
+
+
+def test_sorted_resnet50_set_and_high_density_speech():
+    gs = S.resnet50_set()
+    scales = S.tensor_scales(gs, 31)
+    p = Pair(gs.offsets, momentum=0.9, density=0.001, seed=31, flags=SORTED)
+    for it in range(2):
+        say(f"[sorted resnet50] iteration {it}")
+        p.step(S.gradient(gs, 31, 0, it, scales), it, label=f"sorted resnet50 it{it}")
+    p.close()
+    gs = S.speech_set()
+    scales = S.tensor_scales(gs, 51)
+    p = Pair(gs.offsets, layout_density=0.25, momentum=0.9, density=0.25, seed=51, num_workers=8, flags=SORTED)
+    for it in range(2):                                   # 25 % then 6.25 %: millions of pairs per tensor
+        d = O.warmup_density(O.WARMUP_DENSITIES, it)
+        p.dgc.dgc_set_iteration_density(it)
+        p.ocfg.density = d
+        say(f"[sorted speech] iteration {it} density {d}")
+        p.step(S.gradient(gs, 51, 0, it, scales), it, check_state=(it == 1), label=f"sorted speech it{it}")
+    p.close()
