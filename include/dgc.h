@@ -57,7 +57,8 @@ enum {
 enum {
   DGC_DIAG_OVERFLOW = 1u << 0,   /* some tensor had more passes than payload capacity */
   DGC_DIAG_NONFINITE = 1u << 1,  /* the clipping norm was not finite                  */
-  DGC_DIAG_BAD_INDEX = 1u << 2   /* a payload index fell outside [0, n): skipped      */
+  DGC_DIAG_BAD_INDEX = 1u << 2,  /* a payload index fell outside [0, n): skipped      */
+  DGC_DIAG_UNSORTED = 1u << 3    /* dgc_encode met a region that is not ascending     */
 };
 
 /*
@@ -249,6 +250,49 @@ dgc_status dgc_sparse_sgd_apply_regions(dgc_handle* h, float* theta, float learn
                                         const int32_t* const* count_ptrs_host,
                                         const int64_t* out_offsets_host, void* workspace,
                                         size_t workspace_bytes, void* stream);
+
+/*
+ * Wire format (Section 3.1: encode() packs the 32-bit nonzero values and 16-bit run
+ * lengths of zeros; the sizes of Tables 3 and 4 count six bytes per entry).
+ * Entry e is (runs[e], vals[e]): runs[e] zeros of the flat gradient, then vals[e].  A gap
+ * of more than 65535 zeros is bridged by entries (65535, 0.0f), each covering 65536
+ * positions (the paper does not say how such gaps are written; this keeps the decoder a
+ * plain prefix sum).  Trailing zeros are not encoded.
+ *
+ * dgc_encode turns one payload in region layout into entries.
+ *   idx, val, counts   device, outputs of a dgc_compress call made with
+ *                      DGC_FLAG_SORTED_OUTPUT (every region ascending; a region that
+ *                      is not raises DGC_DIAG_UNSORTED and is encoded as if adjacent)
+ *   runs               device, uint16[entry_capacity]
+ *   vals               device, float[entry_capacity]
+ *   entry_capacity     dgc_encode_max_entries(pairs) always suffices; entries beyond
+ *                      the capacity are dropped and DGC_DIAG_OVERFLOW is raised
+ *   num_entries        device, int32: entries the payload needs
+ *   workspace          device workspace of this handle (scratch for the prefix sums)
+ * Diagnostics are ORed into the workspace's record (dgc_get_diagnostics).
+ */
+dgc_status dgc_encode_max_entries(const dgc_handle* h, int64_t pairs, int64_t* entries);
+dgc_status dgc_encode(dgc_handle* h, const int32_t* idx, const float* val, const int32_t* counts,
+                      const int64_t* out_offsets_host, uint16_t* runs, float* vals,
+                      int64_t entry_capacity, int32_t* num_entries, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
+/*
+ * Receive side for encoded payloads: dense[position] += value for every entry of every
+ * payload, position = (sum of run + 1 over the entries before it) + its own run.
+ *   runs_ptrs_host, vals_ptrs_host   host arrays of num_payloads (1 .. 64) device pointers
+ *   entry_counts_host                host, entries in each payload (the receiver knows
+ *                                    the message sizes)
+ * Entries that land outside [0, n) are skipped and flagged in *diag_flags_dev (may be
+ * NULL).  Ordering and DGC_FLAG_DETERMINISTIC_ACCUMULATE as for dgc_decompress_accumulate.
+ * Errors: INVALID_ARG, ALIGNMENT, CAPACITY (more entries than a set of n elements can
+ * need, or too many payloads), HIP.
+ */
+dgc_status dgc_decode_accumulate(dgc_handle* h, float* dense, int64_t n, int32_t num_payloads,
+                                 const uint16_t* const* runs_ptrs_host,
+                                 const float* const* vals_ptrs_host,
+                                 const int64_t* entry_counts_host, uint32_t* diag_flags_dev,
+                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Kernel timing for measurement harnesses.  After dgc_profile_enable the next

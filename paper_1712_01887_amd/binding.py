@@ -35,6 +35,7 @@ DGC_FLAG_SORTED_OUTPUT = 1 << 4
 DGC_DIAG_OVERFLOW = 1 << 0
 DGC_DIAG_NONFINITE = 1 << 1
 DGC_DIAG_BAD_INDEX = 1 << 2
+DGC_DIAG_UNSORTED = 1 << 3
 
 EXPORTS = [
     "dgc_config_default", "dgc_status_string", "dgc_create", "dgc_destroy", "dgc_set_density",
@@ -43,6 +44,7 @@ EXPORTS = [
     "dgc_decompress_accumulate", "dgc_decompress_accumulate_regions", "dgc_dense_clear_regions",
     "dgc_version", "dgc_last_error_string", "dgc_profile_enable", "dgc_profile_collect",
     "dgc_profile_disable", "dgc_sparse_sgd_apply", "dgc_sparse_sgd_apply_regions",
+    "dgc_encode_max_entries", "dgc_encode", "dgc_decode_accumulate",
 ]
 
 
@@ -130,6 +132,12 @@ def load() -> C.CDLL:
     lib.dgc_sparse_sgd_apply_regions.restype = i32
     lib.dgc_sparse_sgd_apply_regions.argtypes = [vp, vp, C.c_float, i32, P(vp), P(vp), P(vp), P(i64), vp,
                                                  C.c_size_t, vp]
+    lib.dgc_encode_max_entries.restype = i32
+    lib.dgc_encode_max_entries.argtypes = [vp, i64, P(i64)]
+    lib.dgc_encode.restype = i32
+    lib.dgc_encode.argtypes = [vp, vp, vp, vp, P(i64), vp, vp, i64, vp, vp, C.c_size_t, vp]
+    lib.dgc_decode_accumulate.restype = i32
+    lib.dgc_decode_accumulate.argtypes = [vp, vp, i64, i32, P(vp), P(vp), P(i64), vp, vp, C.c_size_t, vp]
     lib.dgc_profile_enable.restype = i32
     lib.dgc_profile_enable.argtypes = [vp, i32]
     lib.dgc_profile_collect.restype = i32
@@ -312,6 +320,26 @@ class Dgc:
             self._h, _ptr(theta), float(learning_rate), len(idx_list), _ptr_array(idx_list),
             _ptr_array(val_list), _ptr_array(count_list), self._layout_c, self._ws_ptr, self._ws_bytes,
             _stream()), "dgc_sparse_sgd_apply_regions")
+
+    # -- wire format ---------------------------------------------------------------
+    def dgc_encode_max_entries(self, pairs: int) -> int:
+        e = C.c_int64()
+        _check(self.lib.dgc_encode_max_entries(self._h, int(pairs), C.byref(e)), "dgc_encode_max_entries")
+        return int(e.value)
+
+    def dgc_encode(self, out_idx, out_val, out_counts, runs, vals, num_entries) -> None:
+        """runs: int16/uint16 tensor, vals: float32 tensor of the same length, num_entries: int32[1]."""
+        self.ensure_workspace(out_idx.device)
+        _check(self.lib.dgc_encode(self._h, _ptr(out_idx), _ptr(out_val), _ptr(out_counts), self._layout_c,
+                                   _ptr(runs), _ptr(vals), int(min(runs.numel(), vals.numel())),
+                                   _ptr(num_entries), self._ws_ptr, self._ws_bytes, _stream()), "dgc_encode")
+
+    def dgc_decode_accumulate(self, dense, runs_list, vals_list, counts: Sequence[int], diag_flags=None) -> None:
+        self.ensure_workspace(dense.device)
+        _check(self.lib.dgc_decode_accumulate(self._h, _ptr(dense), int(dense.numel()), len(runs_list),
+                                              _ptr_array(runs_list), _ptr_array(vals_list), _i64_array(counts),
+                                              _ptr(diag_flags), self._ws_ptr, self._ws_bytes, _stream()),
+               "dgc_decode_accumulate")
 
     def dgc_dense_clear_regions(self, dense, idx_list, count_list) -> None:
         self.ensure_workspace(dense.device)

@@ -31,6 +31,8 @@ struct dgc_handle {
   bool ws_plan_valid = false;
   bool ws_layout_valid = false;
   std::vector<int64_t> ws_out_offsets;
+  std::vector<uint32_t> wire_first_block;  // T + 1: encoder workgroup slots per region of the bound layout
+  size_t wire_slots = 0;                   // words reserved for block sums of the wire-format passes
   // optional kernel timing: five events per dgc_compress call
   // (start, after norm, after select, after stream, after emit)
   std::vector<hipEvent_t> prof_events;
@@ -127,6 +129,16 @@ void build_layout(dgc_handle* h) {
   l.counters = off;     off = align_up(off + sizeof(uint32_t) * kCounterStride * T);
   l.refine_counters = off; off = align_up(off + sizeof(uint32_t) * kCounterStride * T);
   l.block_counts = off; off = align_up(off + sizeof(uint32_t) * h->emit_blocks.size());
+  // wire format: one block sum per kWireChunk pairs of every region (encoder, at most
+  // n / kWireChunk + T) or per kWireChunk entries of every payload (decoder, an entry
+  // stream of a set of n elements has at most n + (n >> 16) entries)
+  {
+    const size_t enc = (size_t)(h->n / kWireChunk) + T + 1;
+    const size_t dec = (size_t)kMaxPayloads * ((size_t)((h->n + (h->n >> 16)) / kWireChunk) + 2);
+    h->wire_slots = enc > dec ? enc : dec;
+  }
+  l.wire_first_block = off; off = align_up(off + sizeof(uint32_t) * (T + 1));
+  l.wire_sums = off;    off = align_up(off + sizeof(uint32_t) * h->wire_slots);
   l.mask = off;         off = align_up(off + sizeof(uint16_t) * 64 * tiles);
   l.total = off;
 }
@@ -196,6 +208,16 @@ dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_
       if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.out_offsets), h->ws_out_offsets.data(),
                                  sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, stream),
                   "upload payload layout"))
+        return DGC_ERR_HIP;
+      uint64_t slots = 0;
+      for (size_t j = 0; j < T; ++j) {
+        h->wire_first_block[j] = (uint32_t)slots;
+        slots += (uint64_t)((out_offsets[j + 1] - out_offsets[j] + kWireChunk - 1) / kWireChunk);
+      }
+      h->wire_first_block[T] = (uint32_t)slots;
+      if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.wire_first_block), h->wire_first_block.data(),
+                                 sizeof(uint32_t) * (T + 1), hipMemcpyHostToDevice, stream),
+                  "upload encoder slots"))
         return DGC_ERR_HIP;
       h->ws_layout_valid = true;
     }
@@ -288,6 +310,7 @@ dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tenso
       for (int64_t f = t0; f <= t1; f += kEmitTiles) h->emit_blocks.push_back(EmitBlock{t, (int32_t)f, nb, 0});
     }
     h->ws_out_offsets.resize(num_tensors + 1);
+    h->wire_first_block.resize(num_tensors + 1);
   } catch (...) {
     delete h;
     return DGC_ERR_CAPACITY;
@@ -699,6 +722,89 @@ dgc_status dgc_dense_clear_regions(dgc_handle* h, float* dense, int32_t num_payl
                                    size_t workspace_bytes, void* stream) {
   return scatter_regions(h, dense, num_payloads, idx_ptrs_host, nullptr, count_ptrs_host,
                          out_offsets_host, workspace, workspace_bytes, stream, ScatterOp::kClear, 0.0f);
+}
+
+dgc_status dgc_encode_max_entries(const dgc_handle* h, int64_t pairs, int64_t* entries) {
+  if (!h || !entries || pairs < 0) return DGC_ERR_INVALID_ARG;
+  // every filler entry accounts for 65536 positions of the set
+  *entries = pairs + (h->n >> 16);
+  return DGC_OK;
+}
+
+dgc_status dgc_encode(dgc_handle* h, const int32_t* idx, const float* val, const int32_t* counts,
+                      const int64_t* out_offsets_host, uint16_t* runs, float* vals, int64_t entry_capacity,
+                      int32_t* num_entries, void* workspace, size_t workspace_bytes, void* stream_) {
+  if (!h || !idx || !val || !counts || !runs || !vals || !num_entries) return DGC_ERR_INVALID_ARG;
+  if (entry_capacity < 0) return DGC_ERR_INVALID_ARG;
+  if (!aligned(idx, 4) || !aligned(val, 4) || !aligned(counts, 4) || !aligned(runs, 2) || !aligned(vals, 4) ||
+      !aligned(num_entries, 4))
+    return DGC_ERR_ALIGNMENT;
+  dgc_status st = check_layout(h, out_offsets_host);
+  if (st != DGC_OK) return st;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  st = sync_workspace(h, workspace, workspace_bytes, out_offsets_host, false, stream);
+  if (st != DGC_OK) return st;
+  int64_t widest = 0;
+  for (int32_t j = 0; j < h->num_tensors; ++j)
+    if (out_offsets_host[j + 1] - out_offsets_host[j] > widest) widest = out_offsets_host[j + 1] - out_offsets_host[j];
+  const uint32_t total_blocks = h->wire_first_block[(size_t)h->num_tensors];
+  if ((size_t)total_blocks > h->wire_slots) return DGC_ERR_CAPACITY;
+  EncodeArgs ea{};
+  ea.idx = idx;
+  ea.val = val;
+  ea.counts = counts;
+  ea.out_offsets = at<int64_t>(workspace, h->lay.out_offsets);
+  ea.first_block = at<uint32_t>(workspace, h->lay.wire_first_block);
+  ea.sums = at<uint32_t>(workspace, h->lay.wire_sums);
+  ea.runs = runs;
+  ea.vals = vals;
+  ea.num_entries = num_entries;
+  ea.state = at<DeviceState>(workspace, h->lay.state);
+  ea.capacity = entry_capacity;
+  ea.num_tensors = h->num_tensors;
+  if (!hip_ok(launch_encode(ea, widest, (int32_t)total_blocks, stream), "launch encode kernels")) return DGC_ERR_HIP;
+  return DGC_OK;
+}
+
+dgc_status dgc_decode_accumulate(dgc_handle* h, float* dense, int64_t n, int32_t num_payloads,
+                                 const uint16_t* const* runs_ptrs_host, const float* const* vals_ptrs_host,
+                                 const int64_t* entry_counts_host, uint32_t* diag_flags_dev, void* workspace,
+                                 size_t workspace_bytes, void* stream_) {
+  if (!h || !dense || !runs_ptrs_host || !vals_ptrs_host || !entry_counts_host) return DGC_ERR_INVALID_ARG;
+  if (n < 1 || n >= (int64_t)1 << 31) return DGC_ERR_INVALID_ARG;
+  if (num_payloads < 1) return DGC_ERR_INVALID_ARG;
+  if (num_payloads > kMaxPayloads) return DGC_ERR_CAPACITY;
+  if (!aligned(dense, 4)) return DGC_ERR_ALIGNMENT;
+  DecodeArgs da{};
+  int64_t slots = 0;
+  for (int32_t w = 0; w < num_payloads; ++w) {
+    const int64_t c = entry_counts_host[w];
+    if (c < 0 || c >= (int64_t)1 << 31) return DGC_ERR_INVALID_ARG;
+    if (c > 0 && (!runs_ptrs_host[w] || !vals_ptrs_host[w])) return DGC_ERR_INVALID_ARG;
+    if (c > 0 && (!aligned(runs_ptrs_host[w], 2) || !aligned(vals_ptrs_host[w], 4))) return DGC_ERR_ALIGNMENT;
+    da.runs[w] = runs_ptrs_host[w];
+    da.vals[w] = vals_ptrs_host[w];
+    da.count[w] = c;
+    da.seg.begin[w] = (int32_t)slots;
+    slots += (c + kWireChunk - 1) / kWireChunk;
+    if (slots > (int64_t)h->wire_slots) return DGC_ERR_CAPACITY;
+  }
+  da.seg.begin[num_payloads] = (int32_t)slots;
+  hipStream_t stream = static_cast<hipStream_t>(stream_);
+  dgc_status st = sync_workspace(h, workspace, workspace_bytes, nullptr, false, stream);
+  if (st != DGC_OK) return st;
+  da.sums = at<uint32_t>(workspace, h->lay.wire_sums);
+  da.dense = dense;
+  da.n = n;
+  da.diag_flags = diag_flags_dev;
+  if (h->cfg.flags & DGC_FLAG_DETERMINISTIC_ACCUMULATE) {
+    // one payload after the other: inside a payload every position is distinct
+    for (int32_t w = 0; w < num_payloads; ++w)
+      if (!hip_ok(launch_decode(da, w, 1, false, stream), "launch decode kernels")) return DGC_ERR_HIP;
+  } else {
+    if (!hip_ok(launch_decode(da, 0, num_payloads, true, stream), "launch decode kernels")) return DGC_ERR_HIP;
+  }
+  return DGC_OK;
 }
 
 }  // extern "C"

@@ -41,6 +41,13 @@ constexpr int kCounterStride = 32;  // uint32 words
 // Receive side: slots of one tensor region handled by one workgroup.
 constexpr int kScatterChunk = 4096;
 
+// Wire format (32-bit values + 16-bit zero-run lengths): pairs or entries handled by one
+// workgroup, kWirePerThread consecutive ones per thread.
+constexpr int kWireThreads = 256;
+constexpr int kWirePerThread = 16;
+constexpr int kWireChunk = kWireThreads * kWirePerThread;
+constexpr int kScanThreads = 1024;
+
 // Threshold selection: one workgroup per tensor.
 constexpr int kSelectThreads = 1024;
 constexpr int kSelectRegKeys = 32;    // candidate keys a thread keeps in registers (32 * 1024 in all)
@@ -77,7 +84,7 @@ struct TensorPlan {
 
 struct WorkspaceLayout {
   size_t state, partials, offsets, out_offsets, plans, thr, tile_info, emit_blocks, counters, refine_counters,
-      block_counts, mask, total;
+      block_counts, wire_first_block, wire_sums, mask, total;
 };
 
 struct SelectArgs {
@@ -169,6 +176,39 @@ struct RegionPayloads {
   const int32_t* counts[kMaxPayloads];
 };
 
+// Encoder: regions in, entries out.
+struct EncodeArgs {
+  const int32_t* idx;            // region layout, ascending inside every region
+  const float* val;
+  const int32_t* counts;         // device, T
+  const int64_t* out_offsets;    // device, T + 1
+  const uint32_t* first_block;   // device, T + 1: first workgroup slot of every tensor
+  uint32_t* sums;                // device, one word per workgroup slot
+  uint16_t* runs;
+  float* vals;
+  int32_t* num_entries;          // device
+  DeviceState* state;
+  int64_t capacity;              // entries that fit in runs / vals
+  int32_t num_tensors;
+};
+
+// Segments of the block-sum array handed to the scan kernel: segment s is
+// [begin[s], begin[s + 1]).
+struct ScanSegments {
+  int32_t begin[kMaxPayloads + 1];
+};
+
+struct DecodeArgs {
+  const uint16_t* runs[kMaxPayloads];
+  const float* vals[kMaxPayloads];
+  int64_t count[kMaxPayloads];   // entries
+  ScanSegments seg;              // workgroup slots of every payload in `sums`
+  uint32_t* sums;
+  float* dense;
+  int64_t n;
+  uint32_t* diag_flags;          // may be null
+};
+
 enum ScatterMode : int32_t {
   kScatterAtomicAdd = 0,
   kScatterPlainAdd = 1,
@@ -192,6 +232,9 @@ hipError_t launch_scatter_regions(float* dense, int64_t n, const RegionPayloads&
                                   int32_t num, const int64_t* out_offsets_dev, int32_t num_tensors,
                                   int64_t max_capacity, ScatterMode mode, float scale,
                                   uint32_t* diag_flags, hipStream_t stream);
+
+hipError_t launch_encode(const EncodeArgs& a, int64_t widest_region, int32_t total_blocks, hipStream_t stream);
+hipError_t launch_decode(const DecodeArgs& a, int32_t first, int32_t num, bool atomic, hipStream_t stream);
 
 }  // namespace dgc
 #endif  // DGC_INTERNAL_H_
