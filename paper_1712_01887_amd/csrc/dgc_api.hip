@@ -671,9 +671,7 @@ static dgc_status scatter_regions(dgc_handle* h, float* dense, int32_t num_paylo
   st = sync_workspace(h, workspace, workspace_bytes, out_offsets_host, false, stream);
   if (st != DGC_OK) return st;
   const int64_t* oo = at<int64_t>(workspace, h->lay.out_offsets);
-  int64_t widest = 0;  // widest region
-  for (int32_t j = 0; j < h->num_tensors; ++j)
-    if (out_offsets_host[j + 1] - out_offsets_host[j] > widest) widest = out_offsets_host[j + 1] - out_offsets_host[j];
+  const int64_t widest = out_offsets_host[h->num_tensors];  // pairs a payload can hold
   if (clear) {
     if (!hip_ok(launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, widest,
                                        kScatterClear, 0.0f, nullptr, stream),

@@ -38,8 +38,12 @@ constexpr int kRefineThreads = 1024;                  // the re-threshold pass s
 // on different tensors do not serialise on a shared line.
 constexpr int kCounterStride = 32;  // uint32 words
 
-// Receive side: slots of one tensor region handled by one workgroup.
-constexpr int kScatterChunk = 4096;
+// Receive side: pairs of one payload handled by one workgroup (kFlatPer per thread) and
+// tensors whose counts a workgroup stages in LDS at a time.
+constexpr int kFlatThreads = 256;
+constexpr int kFlatPer = 4;
+constexpr int kFlatChunk = kFlatThreads * kFlatPer;
+constexpr int kFlatTensors = 1024;
 
 // Wire format (32-bit values + 16-bit zero-run lengths): pairs or entries handled by one
 // workgroup, kWirePerThread consecutive ones per thread.
@@ -230,7 +234,7 @@ hipError_t launch_scatter_pairs(float* dense, int64_t n, const PairPayloads& p, 
                                 uint32_t* diag_flags, hipStream_t stream);
 hipError_t launch_scatter_regions(float* dense, int64_t n, const RegionPayloads& p, int32_t first,
                                   int32_t num, const int64_t* out_offsets_dev, int32_t num_tensors,
-                                  int64_t max_capacity, ScatterMode mode, float scale,
+                                  int64_t total_capacity, ScatterMode mode, float scale,
                                   uint32_t* diag_flags, hipStream_t stream);
 
 hipError_t launch_encode(const EncodeArgs& a, int64_t widest_region, int32_t total_blocks, hipStream_t stream);

@@ -828,7 +828,8 @@ __device__ __forceinline__ uint32_t tensor_tile_word(const uint16_t* __restrict_
                                                      int64_t lo, int64_t hi) {
   constexpr int kBits = kStreamUnroll * 4;
   uint32_t w = mask[t * 64 + lane];
-  if (w && (t * kWaveTile < lo || (t + 1) * kWaveTile > hi)) {  // tile shared with a neighbour tensor
+  // (the test must not depend on w: the loads of several tiles are to be in flight together)
+  if (t * kWaveTile < lo || (t + 1) * kWaveTile > hi) {  // tile shared with a neighbour tensor
     uint32_t keep = 0;
     for (int q = 0; q < kBits; ++q) {
       const int64_t e = tile_element(t, lane, q);
@@ -1146,36 +1147,103 @@ __global__ __launch_bounds__(256) void scatter_pairs_kernel(float* dense, int64_
 }
 
 // Payloads in the per-tensor region layout written by the emit pass.
-// grid = (chunks, tensors, payloads): a workgroup takes kScatterChunk slots of one
-// tensor's region of one payload and leaves at once when the region holds fewer.
-__global__ __launch_bounds__(256) void scatter_regions_kernel(float* dense, int64_t n,
-                                                              RegionPayloads p, int32_t first,
-                                                              const int64_t* __restrict__ out_offsets,
-                                                              ScatterMode mode, float scale,
-                                                              uint32_t* diag_flags) {
-  const int w = first + blockIdx.z;
-  const int j = blockIdx.y;
-  const int64_t region = out_offsets[j];
-  const int64_t cap = out_offsets[j + 1] - region;
-  int64_t count = p.counts[w][j];
-  if (count > cap) count = cap;
-  const int64_t begin = (int64_t)blockIdx.x * kScatterChunk;
-  if (begin >= count) return;
-  const int64_t end = begin + kScatterChunk < count ? begin + kScatterChunk : count;
-  const int32_t* __restrict__ idx = p.idx[w] + region;
-  const float* __restrict__ val = mode == kScatterClear ? nullptr : p.val[w] + region;
-  for (int64_t s0 = begin + threadIdx.x; s0 < end; s0 += 4 * 256) {
-    int32_t i[4];
-    float x[4];
+// grid = (workgroups per payload, payloads).  The pairs of a payload are numbered
+// through all its regions (tensor by tensor, only the filled part of each region), and a
+// workgroup takes chunks of kFlatChunk consecutive numbers, grid-strided until the pairs
+// run out, so that every thread that runs has a pair to move however unevenly the
+// tensors are filled and however little of the capacity is used.  The numbering needs the prefix
+// sum of the per-tensor counts: every workgroup forms it in LDS, kFlatTensors tensors at
+// a time, and a thread finds the tensor of its pair by bisection there.
+__global__ __launch_bounds__(kFlatThreads) void scatter_regions_kernel(float* dense, int64_t n,
+                                                                       RegionPayloads p, int32_t first,
+                                                                       const int64_t* __restrict__ out_offsets,
+                                                                       int32_t num_tensors, ScatterMode mode,
+                                                                       float scale, uint32_t* diag_flags) {
+  constexpr int kPerThread = kFlatTensors / kFlatThreads;  // tensors a thread stages per round
+  __shared__ int64_t s_off[kFlatTensors];
+  __shared__ uint32_t s_pre[kFlatTensors];   // pairs in the staged tensors before each one
+  __shared__ uint32_t wave_sums[kFlatThreads / 64];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int w = first + blockIdx.y;
+  const int32_t* __restrict__ counts = p.counts[w];
+  const int32_t* __restrict__ idx = p.idx[w];
+  const float* __restrict__ val = mode == kScatterClear ? nullptr : p.val[w];
+  int64_t carry = 0;                                    // pairs in the tensors before the staged ones
+  for (int32_t c0 = 0; c0 < num_tensors; c0 += kFlatTensors) {
+    uint32_t cnt[kPerThread];
+    int64_t off[kPerThread];
+    uint32_t mine = 0;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int64_t s = s0 + q * 256;
-      i[q] = s < end ? idx[s] : 0;
-      x[q] = (s < end && mode != kScatterClear) ? val[s] : 0.0f;
+    for (int k = 0; k < kPerThread; ++k) {
+      const int32_t j = c0 + tid * kPerThread + k;
+      cnt[k] = 0;
+      off[k] = 0;
+      if (j < num_tensors) {
+        off[k] = out_offsets[j];
+        const int64_t cap = out_offsets[j + 1] - off[k];
+        int64_t c = counts[j];
+        if (c > cap) c = cap;
+        if (c < 0) c = 0;
+        cnt[k] = (uint32_t)c;
+      }
+      mine += cnt[k];
     }
+    uint32_t incl = mine;
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t t = __shfl_up(incl, d);
+      if (lane >= d) incl += t;
+    }
+    if (lane == 63) wave_sums[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0, staged = 0;
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-      if (s0 + q * 256 < end) scatter_one(dense, n, i[q], x[q], scale, mode, diag_flags);
+    for (int v = 0; v < kFlatThreads / 64; ++v) {
+      const uint32_t t = wave_sums[v];
+      if (v < wave) before += t;
+      staged += t;
+    }
+    uint32_t run = before + incl - mine;
+#pragma unroll
+    for (int k = 0; k < kPerThread; ++k) {
+      s_pre[tid * kPerThread + k] = run;
+      s_off[tid * kPerThread + k] = off[k];
+      run += cnt[k];
+    }
+    __syncthreads();
+    // chunks of this workgroup that reach into the staged tensors
+    for (int64_t x0 = (int64_t)blockIdx.x * kFlatChunk; x0 < carry + (int64_t)staged;
+         x0 += (int64_t)gridDim.x * kFlatChunk) {
+      if (x0 + kFlatChunk <= carry) continue;
+      int64_t slot[kFlatPer];
+#pragma unroll
+      for (int k = 0; k < kFlatPer; ++k) {
+        const int64_t q = x0 + tid + k * kFlatThreads - carry;
+        slot[k] = -1;
+        if (q >= 0 && q < (int64_t)staged) {
+          int lo = 0, hi = kFlatTensors - 1;  // largest i with s_pre[i] <= q
+          while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if ((int64_t)s_pre[mid] <= q) lo = mid;
+            else hi = mid - 1;
+          }
+          slot[k] = s_off[lo] + (q - (int64_t)s_pre[lo]);
+        }
+      }
+      int32_t i[kFlatPer];
+      float x[kFlatPer];
+#pragma unroll
+      for (int k = 0; k < kFlatPer; ++k) {
+        i[k] = slot[k] >= 0 ? idx[slot[k]] : 0;
+        x[k] = (slot[k] >= 0 && mode != kScatterClear) ? val[slot[k]] : 0.0f;
+      }
+#pragma unroll
+      for (int k = 0; k < kFlatPer; ++k)
+        if (slot[k] >= 0) scatter_one(dense, n, i[k], x[k], scale, mode, diag_flags);
+    }
+    carry += staged;
+    __syncthreads();
   }
 }
 
@@ -1465,13 +1533,15 @@ hipError_t launch_scatter_pairs(float* dense, int64_t n, const PairPayloads& p, 
 
 hipError_t launch_scatter_regions(float* dense, int64_t n, const RegionPayloads& p, int32_t first,
                                   int32_t num, const int64_t* out_offsets_dev, int32_t num_tensors,
-                                  int64_t max_capacity, ScatterMode mode, float scale,
+                                  int64_t total_capacity, ScatterMode mode, float scale,
                                   uint32_t* diag_flags, hipStream_t stream) {
-  if (num <= 0 || max_capacity <= 0) return hipSuccess;
-  const int64_t chunks = ceil_div(max_capacity, kScatterChunk);
-  if (chunks > 65535 || num_tensors > 65535) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(scatter_regions_kernel, dim3((unsigned)chunks, (unsigned)num_tensors, (unsigned)num),
-                     dim3(256), 0, stream, dense, n, p, first, out_offsets_dev, mode, scale, diag_flags);
+  if (num <= 0 || total_capacity <= 0) return hipSuccess;
+  // a quarter of the capacity: regions sized as recommended hold eight times the expected
+  // pairs, so most workgroups find one chunk; fuller regions make them loop
+  int64_t chunks = ceil_div(total_capacity, 4 * kFlatChunk);
+  if (chunks > 65536) chunks = 65536;
+  hipLaunchKernelGGL(scatter_regions_kernel, dim3((unsigned)chunks, (unsigned)num), dim3(kFlatThreads), 0, stream,
+                     dense, n, p, first, out_offsets_dev, num_tensors, mode, scale, diag_flags);
   return hipGetLastError();
 }
 
