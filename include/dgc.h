@@ -308,6 +308,15 @@ dgc_status dgc_profile_collect(dgc_handle* h, int32_t* calls, double* norm_ms, d
                                double* stream_ms, double* emit_ms);
 dgc_status dgc_profile_disable(dgc_handle* h);
 
+/*
+ * Yardstick for measurement harnesses: one launch of a kernel with the memory traffic of
+ * the streaming pass and nothing else (b <- b + a, c <- c + b over the floor(n / 1024)
+ * whole tiles of 1024 elements; three arrays read, two written, 20 bytes per element).
+ * What it reaches on a given box is the practical ceiling the streaming pass is compared
+ * with besides the nominal HBM peak.  a, b, c: device, n floats, 16-byte aligned.
+ */
+dgc_status dgc_profile_stream_ceiling(const float* a, float* b, float* c, int64_t n, void* stream);
+
 /* Library version, major * 1000 + minor. */
 int32_t dgc_version(void);
 

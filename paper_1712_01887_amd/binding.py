@@ -44,7 +44,7 @@ EXPORTS = [
     "dgc_decompress_accumulate", "dgc_decompress_accumulate_regions", "dgc_dense_clear_regions",
     "dgc_version", "dgc_last_error_string", "dgc_profile_enable", "dgc_profile_collect",
     "dgc_profile_disable", "dgc_sparse_sgd_apply", "dgc_sparse_sgd_apply_regions",
-    "dgc_encode_max_entries", "dgc_encode", "dgc_decode_accumulate",
+    "dgc_encode_max_entries", "dgc_encode", "dgc_decode_accumulate", "dgc_profile_stream_ceiling",
 ]
 
 
@@ -138,6 +138,8 @@ def load() -> C.CDLL:
     lib.dgc_encode.argtypes = [vp, vp, vp, vp, P(i64), vp, vp, i64, vp, vp, C.c_size_t, vp]
     lib.dgc_decode_accumulate.restype = i32
     lib.dgc_decode_accumulate.argtypes = [vp, vp, i64, i32, P(vp), P(vp), P(i64), vp, vp, C.c_size_t, vp]
+    lib.dgc_profile_stream_ceiling.restype = i32
+    lib.dgc_profile_stream_ceiling.argtypes = [vp, vp, vp, i64, vp]
     lib.dgc_profile_enable.restype = i32
     lib.dgc_profile_enable.argtypes = [vp, i32]
     lib.dgc_profile_collect.restype = i32
@@ -185,6 +187,12 @@ def _stream() -> int:
 
 def _ptr_array(tensors) -> "C.Array":
     return (C.c_void_p * len(tensors))(*[_ptr(t) for t in tensors])
+
+
+def dgc_profile_stream_ceiling(a, b, c) -> None:
+    """One launch of the bare three-read / two-write kernel over a, b, c (same length)."""
+    _check(load().dgc_profile_stream_ceiling(_ptr(a), _ptr(b), _ptr(c), int(a.numel()), _stream()),
+           "dgc_profile_stream_ceiling")
 
 
 class Dgc:

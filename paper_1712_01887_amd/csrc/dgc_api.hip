@@ -23,6 +23,7 @@ struct dgc_handle {
   std::vector<int64_t> k;            // T
   std::vector<int64_t> draws;        // T
   std::vector<uint32_t> tile_info;   // ceil(n / kWaveTile)
+  std::vector<float> tile_thr_init;  // ceil(n / kWaveTile): NaN where a tile is not wholly inside one tensor
   std::vector<EmitBlock> emit_blocks;  // work list of the emit pass
   WorkspaceLayout lay{};
   // what the bound workspace currently holds
@@ -125,6 +126,7 @@ void build_layout(dgc_handle* h) {
   l.plans = off;        off = align_up(off + sizeof(TensorPlan) * T);
   l.thr = off;          off = align_up(off + sizeof(float) * T);
   l.tile_info = off;    off = align_up(off + sizeof(uint32_t) * tiles);
+  l.tile_thr = off;     off = align_up(off + sizeof(float) * tiles);
   l.emit_blocks = off;  off = align_up(off + sizeof(EmitBlock) * h->emit_blocks.size());
   l.counters = off;     off = align_up(off + sizeof(uint32_t) * kCounterStride * T);
   l.refine_counters = off; off = align_up(off + sizeof(uint32_t) * kCounterStride * T);
@@ -186,6 +188,10 @@ dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_
     if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.tile_info), h->tile_info.data(),
                                sizeof(uint32_t) * h->tile_info.size(), hipMemcpyHostToDevice, stream),
                 "upload tile table"))
+      return DGC_ERR_HIP;
+    if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.tile_thr), h->tile_thr_init.data(),
+                               sizeof(float) * h->tile_thr_init.size(), hipMemcpyHostToDevice, stream),
+                "upload tile thresholds"))
       return DGC_ERR_HIP;
     if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.emit_blocks), h->emit_blocks.data(),
                                sizeof(EmitBlock) * h->emit_blocks.size(), hipMemcpyHostToDevice, stream),
@@ -295,6 +301,7 @@ dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tenso
     h->draws.resize(num_tensors);
     const int64_t tiles = (h->n + kWaveTile - 1) / kWaveTile;
     h->tile_info.resize((size_t)tiles);
+    h->tile_thr_init.resize((size_t)tiles);
     int32_t j = 0;
     for (int64_t t = 0; t < tiles; ++t) {
       const int64_t first = t * kWaveTile;
@@ -302,6 +309,7 @@ dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tenso
       while (h->offsets[j + 1] <= first) ++j;
       const bool whole = last <= h->n && last <= h->offsets[j + 1];
       h->tile_info[(size_t)t] = (uint32_t)j | (whole ? 0u : kTileMixed);
+      h->tile_thr_init[(size_t)t] = whole ? 0.0f : std::nanf("");
     }
     for (int32_t t = 0; t < num_tensors; ++t) {
       const int64_t t0 = h->offsets[t] / kWaveTile;
@@ -432,6 +440,7 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   sa.state = state;
   sa.thr = at<float>(workspace, h->lay.thr);
   sa.out_thr = out_thr;
+  sa.tile_thr = at<float>(workspace, h->lay.tile_thr);
   sa.momentum = c.momentum;
   sa.scale_const = scale_const;
   sa.scale_from_state = clip ? 1 : 0;
@@ -454,6 +463,7 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   ta.offsets = at<int64_t>(workspace, h->lay.offsets);
   ta.thr = sa.thr;
   ta.tile_info = at<uint32_t>(workspace, h->lay.tile_info);
+  ta.tile_thr = sa.tile_thr;
   ta.state = state;
   ta.n = h->n;
   ta.num_tensors = h->num_tensors;
@@ -566,6 +576,14 @@ dgc_status dgc_profile_collect(dgc_handle* h, int32_t* calls, double* norm_ms, d
 dgc_status dgc_profile_disable(dgc_handle* h) {
   if (!h) return DGC_ERR_INVALID_ARG;
   profile_release(h);
+  return DGC_OK;
+}
+
+dgc_status dgc_profile_stream_ceiling(const float* a, float* b, float* c, int64_t n, void* stream) {
+  if (!a || !b || !c || n < 0 || n >= (int64_t)1 << 31) return DGC_ERR_INVALID_ARG;
+  if (!aligned(a, 16) || !aligned(b, 16) || !aligned(c, 16)) return DGC_ERR_ALIGNMENT;
+  if (!hip_ok(launch_ceiling(a, b, c, n, static_cast<hipStream_t>(stream)), "launch ceiling kernel"))
+    return DGC_ERR_HIP;
   return DGC_OK;
 }
 

@@ -87,7 +87,7 @@ struct TensorPlan {
 };
 
 struct WorkspaceLayout {
-  size_t state, partials, offsets, out_offsets, plans, thr, tile_info, emit_blocks, counters, refine_counters,
+  size_t state, partials, offsets, out_offsets, plans, thr, tile_info, tile_thr, emit_blocks, counters, refine_counters,
       block_counts, wire_first_block, wire_sums, mask, total;
 };
 
@@ -99,6 +99,8 @@ struct SelectArgs {
   DeviceState* state;
   float* thr;
   float* out_thr;       // may be null
+  float* tile_thr;      // device, one word per wave tile: the threshold of every tile that lies
+                        // wholly inside one tensor; the others hold a NaN put there once by the host
   float momentum;
   float scale_const;
   int32_t scale_from_state;  // 1: the norm kernel ran and left the scale in `state`
@@ -115,6 +117,7 @@ struct StreamArgs {
   const int64_t* offsets;      // device, T + 1
   const float* thr;            // device, T
   const uint32_t* tile_info;   // device, ceil(n / kWaveTile), see kTileMixed
+  const float* tile_thr;       // device, ceil(n / kWaveTile), see SelectArgs
   const DeviceState* state;
   int64_t n;
   int32_t num_tensors;
@@ -226,6 +229,7 @@ hipError_t launch_norm(const float* g, int64_t n, DeviceState* state, double* pa
                        double thr_local, float scale_override, hipStream_t stream);
 hipError_t launch_select(const SelectArgs& a, int32_t num_tensors, hipStream_t stream);
 hipError_t launch_stream(const StreamArgs& a, hipStream_t stream);
+hipError_t launch_ceiling(const float* a, float* b, float* c, int64_t n, hipStream_t stream);
 hipError_t launch_refine(const RefineArgs& a, int32_t num_blocks, hipStream_t stream);
 hipError_t launch_count(const CountArgs& a, int32_t num_blocks, hipStream_t stream);
 hipError_t launch_emit(const EmitArgs& a, int32_t num_blocks, bool sorted, hipStream_t stream);
