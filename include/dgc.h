@@ -121,7 +121,11 @@ dgc_status dgc_set_density(dgc_handle* h, double density);
 /* Replace the warm-up table (host, len >= 1 densities in (0, 1]).  The default
  * table is {0.25, 0.0625, 0.015625, 0.004, 0.001}. */
 dgc_status dgc_set_warmup_schedule(dgc_handle* h, const double* densities_host, int32_t len);
-/* density <- table[min(iteration, len - 1)]. */
+/* Iterations every table entry is held (default 1).  The paper's runs hold a warm-up
+ * sparsity for one epoch (Section 4.1: a warm-up period of 4 epochs for the four values
+ * before the final one): pass the iterations of an epoch. */
+dgc_status dgc_set_warmup_stage_length(dgc_handle* h, int64_t iterations_per_stage);
+/* density <- table[min(iteration / stage length, len - 1)]. */
 dgc_status dgc_set_iteration_density(dgc_handle* h, int64_t iteration);
 
 /*

@@ -81,9 +81,10 @@ WARMUP_DENSITIES = (0.25, 0.0625, 0.015625, 0.004, 0.001)
 """Section 4.1: sparsity 75 %, 93.75 %, 98.4375 %, 99.6 %, 99.9 % as densities."""
 
 
-def warmup_density(schedule: Sequence[float], iteration: int) -> float:
-    """Density for an iteration: the schedule entry, held at the last one."""
-    return float(schedule[min(int(iteration), len(schedule) - 1)])
+def warmup_density(schedule: Sequence[float], iteration: int, stage_length: int = 1) -> float:
+    """Density for an iteration: every schedule entry is held for `stage_length`
+    iterations (an epoch in the paper's runs), the last one for good."""
+    return float(schedule[min(int(iteration) // int(stage_length), len(schedule) - 1)])
 
 
 # --------------------------------------------------------------------------

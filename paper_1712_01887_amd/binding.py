@@ -39,7 +39,7 @@ DGC_DIAG_UNSORTED = 1 << 3
 
 EXPORTS = [
     "dgc_config_default", "dgc_status_string", "dgc_create", "dgc_destroy", "dgc_set_density",
-    "dgc_set_warmup_schedule", "dgc_set_iteration_density", "dgc_query_plan", "dgc_workspace_bytes",
+    "dgc_set_warmup_schedule", "dgc_set_warmup_stage_length", "dgc_set_iteration_density", "dgc_query_plan", "dgc_workspace_bytes",
     "dgc_recommended_payload_layout", "dgc_compress", "dgc_get_diagnostics",
     "dgc_decompress_accumulate", "dgc_decompress_accumulate_regions", "dgc_dense_clear_regions",
     "dgc_version", "dgc_last_error_string", "dgc_profile_enable", "dgc_profile_collect",
@@ -108,6 +108,8 @@ def load() -> C.CDLL:
     lib.dgc_set_density.argtypes = [vp, dbl]
     lib.dgc_set_warmup_schedule.restype = i32
     lib.dgc_set_warmup_schedule.argtypes = [vp, P(dbl), i32]
+    lib.dgc_set_warmup_stage_length.restype = i32
+    lib.dgc_set_warmup_stage_length.argtypes = [vp, i64]
     lib.dgc_set_iteration_density.restype = i32
     lib.dgc_set_iteration_density.argtypes = [vp, i64]
     lib.dgc_query_plan.restype = i32
@@ -229,6 +231,10 @@ class Dgc:
     def dgc_set_warmup_schedule(self, densities: Sequence[float]) -> None:
         arr = (C.c_double * len(densities))(*[float(d) for d in densities])
         _check(self.lib.dgc_set_warmup_schedule(self._h, arr, len(densities)), "dgc_set_warmup_schedule")
+
+    def dgc_set_warmup_stage_length(self, iterations_per_stage: int) -> None:
+        _check(self.lib.dgc_set_warmup_stage_length(self._h, int(iterations_per_stage)),
+               "dgc_set_warmup_stage_length")
 
     def dgc_set_iteration_density(self, iteration: int) -> None:
         _check(self.lib.dgc_set_iteration_density(self._h, int(iteration)), "dgc_set_iteration_density")

@@ -18,6 +18,7 @@ struct dgc_handle {
   int64_t n = 0;
   std::vector<int64_t> offsets;      // T + 1
   std::vector<double> warmup;        // densities
+  int64_t warmup_stage_len = 1;      // iterations every entry of the table is held
   // plan under cfg.density
   std::vector<TensorPlan> plans;     // T
   std::vector<int64_t> k;            // T
@@ -354,10 +355,17 @@ dgc_status dgc_set_warmup_schedule(dgc_handle* h, const double* densities_host, 
   return DGC_OK;
 }
 
+dgc_status dgc_set_warmup_stage_length(dgc_handle* h, int64_t iterations_per_stage) {
+  if (!h || iterations_per_stage < 1) return DGC_ERR_INVALID_ARG;
+  h->warmup_stage_len = iterations_per_stage;
+  return DGC_OK;
+}
+
 dgc_status dgc_set_iteration_density(dgc_handle* h, int64_t iteration) {
   if (!h || iteration < 0) return DGC_ERR_INVALID_ARG;
   const size_t last = h->warmup.size() - 1;
-  const size_t i = (uint64_t)iteration < last ? (size_t)iteration : last;
+  const uint64_t stage = (uint64_t)(iteration / h->warmup_stage_len);
+  const size_t i = stage < last ? (size_t)stage : last;
   return dgc_set_density(h, h->warmup[i]);
 }
 

@@ -137,6 +137,15 @@ def test_density_control_and_warmup(dgc_lib):
     assert d.dgc_query_plan(0)[0] == 2361600
     d.dgc_set_iteration_density(9)
     assert d.dgc_query_plan(0)[0] == 472320
+    # every entry held for an "epoch" of 391 iterations (Section 4.1: one warm-up sparsity per epoch)
+    d.dgc_set_warmup_schedule(list(O.WARMUP_DENSITIES))
+    d.dgc_set_warmup_stage_length(391)
+    for it, stage in [(0, 0), (390, 0), (391, 1), (4 * 391 - 1, 3), (4 * 391, 4), (10 ** 6, 4)]:
+        d.dgc_set_iteration_density(it)
+        assert d.dgc_query_plan(0)[0] == O.topk_count(O.WARMUP_DENSITIES[stage], 4723200)
+        assert O.warmup_density(O.WARMUP_DENSITIES, it, 391) == O.WARMUP_DENSITIES[stage]
+    with pytest.raises(B.DgcError):
+        d.dgc_set_warmup_stage_length(0)
     with pytest.raises(B.DgcError):
         d.dgc_set_density(0.0)
     with pytest.raises(B.DgcError):
@@ -146,4 +155,35 @@ def test_density_control_and_warmup(dgc_lib):
     with pytest.raises(B.DgcError):
         d.dgc_query_plan(1)
     assert d.dgc_workspace_bytes() > 0 and d.dgc_workspace_bytes() % 256 == 0
+    d.close()
+
+
+def test_wire_format_entry_points_validate_before_touching_the_device(dgc_lib):
+    d = B.Dgc(B.dgc_config_default(), [0, 64, 200000])
+    assert d.dgc_encode_max_entries(0) == 3 and d.dgc_encode_max_entries(1000) == 1003   # 200000 >> 16 fillers
+    lay = (C.c_int64 * 3)(0, 64, 1000)
+    a = 0x10000
+    n32 = C.c_void_p(a)
+    enc = dgc_lib.dgc_encode
+    assert enc(d._h, None, a, a, lay, a, a, 10, a, a, 1 << 24, None) == B.DGC_ERR_INVALID_ARG
+    assert enc(d._h, a, a, a, lay, a, a, -1, a, a, 1 << 24, None) == B.DGC_ERR_INVALID_ARG
+    assert enc(d._h, a, a, a, lay, a + 1, a, 10, a, a, 1 << 24, None) == B.DGC_ERR_ALIGNMENT
+    bad = (C.c_int64 * 3)(0, 64, 10)
+    assert enc(d._h, a, a, a, bad, a, a, 10, a, a, 1 << 24, None) == B.DGC_ERR_INVALID_ARG
+    assert enc(d._h, a, a, a, lay, a, a, 10, a, None, 1 << 24, None) == B.DGC_ERR_INVALID_ARG
+    assert enc(d._h, a, a, a, lay, a, a, 10, a, a, 16, None) == B.DGC_ERR_CAPACITY
+    dec = dgc_lib.dgc_decode_accumulate
+    ptrs = (C.c_void_p * 1)(a)
+    cnt = (C.c_int64 * 1)(5)
+    assert dec(d._h, None, 10, 1, ptrs, ptrs, cnt, None, a, 1 << 24, None) == B.DGC_ERR_INVALID_ARG
+    assert dec(d._h, a, 0, 1, ptrs, ptrs, cnt, None, a, 1 << 24, None) == B.DGC_ERR_INVALID_ARG
+    assert dec(d._h, a, 10, 65, ptrs, ptrs, cnt, None, a, 1 << 24, None) == B.DGC_ERR_CAPACITY
+    neg = (C.c_int64 * 1)(-1)
+    assert dec(d._h, a, 10, 1, ptrs, ptrs, neg, None, a, 1 << 24, None) == B.DGC_ERR_INVALID_ARG
+    huge = (C.c_int64 * 1)(1 << 30)      # more entries than a set of 200064 elements can need
+    assert dec(d._h, a, 10, 1, ptrs, ptrs, huge, None, a, 1 << 24, None) == B.DGC_ERR_CAPACITY
+    odd = (C.c_void_p * 1)(a + 1)
+    assert dec(d._h, a, 10, 1, odd, ptrs, cnt, None, a, 1 << 24, None) == B.DGC_ERR_ALIGNMENT
+    assert dgc_lib.dgc_profile_stream_ceiling(None, a, a, 10, None) == B.DGC_ERR_INVALID_ARG
+    assert dgc_lib.dgc_profile_stream_ceiling(a, a + 4, a, 10, None) == B.DGC_ERR_ALIGNMENT
     d.close()
