@@ -160,3 +160,45 @@ def test_encode_resnet50_set_and_sixteen_payload_decode():
     assert np.array_equal(dense.cpu().numpy().view(np.uint32), expect.view(np.uint32))
     for p in keep:
         p.close()
+
+
+def test_thousands_of_tiny_tensors_through_every_pass():
+    # more tensors than a tile has lanes, than the receive side stages at a time, and than
+    # the encoder looks back at once: 1-element tensors by the hundred inside one tile
+    import torch
+    rng = np.random.default_rng(17)
+    sizes = [1] * 1500 + [3] * 700 + [5000] + [2] * 900 + [70000] + [1] * 130 + [7]
+    offsets = np.concatenate([[0], np.cumsum(sizes)])
+    n = int(offsets[-1])
+    T = len(sizes)
+    kw = dict(layout_density=1.0, momentum=0.9, density=0.02, seed=4, sample_min=64, sample_max=256,
+              flags=SORTED)
+    workers = [Pair(offsets, **kw) for _ in range(2)]
+    enc, oracle_entries, payloads = [], [], []
+    for it in range(2):
+        enc, oracle_entries, payloads = [], [], []
+        for w, p in enumerate(workers):
+            g = rng.standard_t(3, n).astype(np.float32)
+            g[rng.random(n) < 0.5] = 0.0                       # many tensors send nothing at all
+            res = p.step(g, it, label=f"tiny tensors w{w} it{it}")
+            runs, vals, e = check_against_oracle(p, res, f"tiny tensors w{w} it{it}")
+            enc.append((runs, vals, e))
+            oracle_entries.append(O.encode(*O.flatten_payload(res)))
+            payloads.append(O.flatten_payload(res))
+    expect = np.zeros(n, np.float32)
+    O.decompress_accumulate(expect, payloads)
+    cfg_kw = {k: v for k, v in kw.items() if k != "layout_density"}
+    det = B.Dgc(B.make_config(**{**cfg_kw, "flags": SORTED | B.DGC_FLAG_DETERMINISTIC_ACCUMULATE}), offsets)
+    det.set_layout(workers[0].layout)
+    dense = torch.zeros(n, device="cuda")
+    det.dgc_decompress_accumulate_regions(dense, [p.out_idx for p in workers], [p.out_val for p in workers],
+                                          [p.out_counts for p in workers])
+    assert np.array_equal(dense.cpu().numpy().view(np.uint32), expect.view(np.uint32))
+    dense.zero_()
+    det.dgc_decode_accumulate(dense, [r for r, _, _ in enc], [x for _, x, _ in enc], [e for _, _, e in enc])
+    assert np.array_equal(dense.cpu().numpy().view(np.uint32), expect.view(np.uint32))
+    det.dgc_dense_clear_regions(dense, [p.out_idx for p in workers], [p.out_counts for p in workers])
+    assert not dense.cpu().numpy().any()
+    det.close()
+    for p in workers:
+        p.close()
