@@ -1,0 +1,80 @@
+"""The compress and accumulate calls under HIP graph capture: the library allocates
+nothing and synchronises nothing on the hot path, and every counter its kernels use is
+left at zero by the kernels themselves, so a captured step can be replayed.  Every
+replay is checked against the oracle, with eager work and synchronisations between the
+replays.  Run with `-m gpu` on an MI355X."""
+
+import numpy as np
+import pytest
+
+from oracle import dgc_oracle as O
+from paper_1712_01887_amd import binding as B
+from paper_1712_01887_amd import synthetic as S
+from tests.parity import oracle_config, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("flags,extra", [
+    (0, dict(clip_threshold=0.05, num_workers=4)),
+    (B.DGC_FLAG_SORTED_OUTPUT, dict(refine_alpha=1.0, sample_min=64, sample_max=64, sample_block=4)),
+])
+def test_captured_step_replays_match_the_oracle(flags, extra):
+    import torch
+    gs = S.ragged_set(19, tensors=14, max_numel=150000)
+    n = gs.numel
+    kw = dict(momentum=0.9, density=0.01, seed=6, flags=flags, **extra)
+    dgc = B.Dgc(B.make_config(**kw), gs.offsets)
+    layout = dgc.dgc_recommended_payload_layout(0.05)
+    dgc.set_layout(layout)
+    caps = [layout[j + 1] - layout[j] for j in range(len(gs.sizes))]
+    ocfg = oracle_config(**kw)
+    u = torch.zeros(n, device="cuda")
+    v = torch.zeros(n, device="cuda")
+    g_static = torch.zeros(n, device="cuda")
+    dense = torch.zeros(n, device="cuda")
+    out_idx, out_val, out_counts, out_thr = dgc.alloc_payload("cuda")
+    iteration = 5                                          # frozen into the captured launch arguments
+    grads = [S.gradient(gs, 33, 0, it) for it in range(5)]
+
+    # first use uploads the tables (host copies): outside the capture
+    g_static.copy_(torch.from_numpy(grads[4]))
+    dgc.dgc_compress(g_static, u, v, out_idx, out_val, out_counts, out_thr, iteration)
+    dgc.dgc_decompress_accumulate_regions(dense, [out_idx], [out_val], [out_counts])
+    torch.cuda.synchronize()
+    u.zero_(); v.zero_(); dense.zero_()
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        dgc.dgc_compress(g_static, u, v, out_idx, out_val, out_counts, out_thr, iteration)
+        dgc.dgc_decompress_accumulate_regions(dense, [out_idx], [out_val], [out_counts])
+    u.zero_(); v.zero_(); dense.zero_()                     # capture does not run the kernels; be explicit anyway
+
+    ou = np.zeros(n, np.float32)
+    ov = np.zeros(n, np.float32)
+    expect_dense = np.zeros(n, np.float32)
+    for rep in range(4):
+        g_static.copy_(torch.from_numpy(grads[rep]))
+        graph.replay()
+        torch.cuda.synchronize()
+        res = O.compress(grads[rep], ou, ov, gs.offsets, ocfg, iteration, caps)
+        per_idx, per_val, counts = B.gather_payload(layout, out_idx, out_val, out_counts)
+        diag = dgc.dgc_get_diagnostics()
+        if ocfg.clip_threshold > 0:
+            assert abs(diag.norm - res.norm) <= 1e-6 * res.norm
+            assert np.float32(diag.scale) == res.scale          # else this seed needs the re-run of tests/parity.py
+        assert np.array_equal(out_thr.cpu().numpy().view(np.uint32), res.thresholds.view(np.uint32)), rep
+        assert np.array_equal(counts.astype(np.int64), res.counts), rep
+        assert not res.overflow
+        for j in range(len(gs.sizes)):
+            assert np.array_equal(per_idx[j], res.indices[j]), (rep, j)
+            assert np.array_equal(per_val[j].view(np.uint32), res.values[j].view(np.uint32)), (rep, j)
+        assert np.array_equal(u.cpu().numpy().view(np.uint32), ou.view(np.uint32)), rep
+        assert np.array_equal(v.cpu().numpy().view(np.uint32), ov.view(np.uint32)), rep
+        O.decompress_accumulate(expect_dense, [O.flatten_payload(res)])
+        assert np.array_equal(dense.cpu().numpy().view(np.uint32), expect_dense.view(np.uint32)), rep
+        # the program's own eager work between replays
+        scratch = torch.randn(100000, device="cuda")
+        assert torch.isfinite(scratch.sum()).item()
+        say(f"[graph] replay {rep}: {int(counts.sum())} pairs, refined {sum(res.refined)}")
+    dgc.close()
