@@ -131,7 +131,7 @@ void build_layout(dgc_handle* h) {
   l.emit_blocks = off;  off = align_up(off + sizeof(EmitBlock) * h->emit_blocks.size());
   l.counters = off;     off = align_up(off + sizeof(uint32_t) * kCounterStride * T);
   l.refine_counters = off; off = align_up(off + sizeof(uint32_t) * kCounterStride * T);
-  l.block_counts = off; off = align_up(off + sizeof(uint32_t) * h->emit_blocks.size());
+  l.tile_count = off;   off = align_up(off + sizeof(uint32_t) * tiles);
   // wire format: one block sum per kWireChunk pairs of every region (encoder, at most
   // n / kWireChunk + T) or per kWireChunk entries of every payload (decoder, an entry
   // stream of a set of n elements has at most n + (n >> 16) entries)
@@ -472,6 +472,7 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   ta.thr = sa.thr;
   ta.tile_info = at<uint32_t>(workspace, h->lay.tile_info);
   ta.tile_thr = sa.tile_thr;
+  ta.tile_count = at<uint32_t>(workspace, h->lay.tile_count);
   ta.state = state;
   ta.n = h->n;
   ta.num_tensors = h->num_tensors;
@@ -497,26 +498,16 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
     ra.out_val = out_val;
     ra.thr = sa.thr;
     ra.out_thr = out_thr;
+    ra.tile_count = ta.tile_count;
     if (!hip_ok(launch_refine(ra, (int32_t)h->emit_blocks.size(), stream), "launch refine kernel"))
       return DGC_ERR_HIP;
   }
 
-  // Sorted output: a count pass over the final mask tells every emit workgroup where its
-  // part of the tensor's region starts.
   const bool sorted = (c.flags & DGC_FLAG_SORTED_OUTPUT) != 0;
-  if (sorted) {
-    CountArgs ca{};
-    ca.blocks = at<EmitBlock>(workspace, h->lay.emit_blocks);
-    ca.mask = ta.mask;
-    ca.offsets = ta.offsets;
-    ca.block_counts = at<uint32_t>(workspace, h->lay.block_counts);
-    if (!hip_ok(launch_count(ca, (int32_t)h->emit_blocks.size(), stream), "launch count kernel"))
-      return DGC_ERR_HIP;
-  }
 
   EmitArgs ea{};
   ea.blocks = at<EmitBlock>(workspace, h->lay.emit_blocks);
-  ea.block_counts = at<uint32_t>(workspace, h->lay.block_counts);
+  ea.tile_count = at<uint32_t>(workspace, h->lay.tile_count);
   ea.counters = at<uint32_t>(workspace, h->lay.counters);
   ea.u = u;
   ea.v = v;

@@ -88,7 +88,7 @@ struct TensorPlan {
 
 struct WorkspaceLayout {
   size_t state, partials, offsets, out_offsets, plans, thr, tile_info, tile_thr, emit_blocks, counters, refine_counters,
-      block_counts, wire_first_block, wire_sums, mask, total;
+      tile_count, wire_first_block, wire_sums, mask, total;
 };
 
 struct SelectArgs {
@@ -118,6 +118,7 @@ struct StreamArgs {
   const float* thr;            // device, T
   const uint32_t* tile_info;   // device, ceil(n / kWaveTile), see kTileMixed
   const float* tile_thr;       // device, ceil(n / kWaveTile), see SelectArgs
+  uint32_t* tile_count;        // device, ceil(n / kWaveTile): mask bits set in every tile
   const DeviceState* state;
   int64_t n;
   int32_t num_tensors;
@@ -146,6 +147,7 @@ struct RefineArgs {
   float* out_val;
   float* thr;
   float* out_thr;              // may be null
+  uint32_t* tile_count;        // kept in step with the mask bits the pass clears
 };
 
 struct EmitArgs {
@@ -161,14 +163,7 @@ struct EmitArgs {
   int32_t* out_counts;         // device, T
   DeviceState* state;
   int32_t factor_masking;
-  const uint32_t* block_counts;  // sorted output: mask bits of every workgroup's run (count pass)
-};
-
-struct CountArgs {
-  const EmitBlock* blocks;
-  const uint16_t* mask;
-  const int64_t* offsets;
-  uint32_t* block_counts;      // device, one word per entry of the emit work list
+  const uint32_t* tile_count;  // sorted output: mask bits per tile, left by the streaming pass
 };
 
 struct PairPayloads {
@@ -231,7 +226,6 @@ hipError_t launch_select(const SelectArgs& a, int32_t num_tensors, hipStream_t s
 hipError_t launch_stream(const StreamArgs& a, hipStream_t stream);
 hipError_t launch_ceiling(const float* a, float* b, float* c, int64_t n, hipStream_t stream);
 hipError_t launch_refine(const RefineArgs& a, int32_t num_blocks, hipStream_t stream);
-hipError_t launch_count(const CountArgs& a, int32_t num_blocks, hipStream_t stream);
 hipError_t launch_emit(const EmitArgs& a, int32_t num_blocks, bool sorted, hipStream_t stream);
 hipError_t launch_scatter_pairs(float* dense, int64_t n, const PairPayloads& p, int32_t first,
                                 int32_t num, int64_t max_count, ScatterMode mode, float scale,

@@ -597,6 +597,10 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs a) {
     cand = mixed_tile_mask(a, base, lane, j0, z);
   }
   a.mask[tile * 64 + lane] = (uint16_t)cand;
+  // bits set in the tile, for the index-ordered emit pass (measured: no cost here)
+  int bits = __popc(cand);
+  for (int d = 32; d >= 1; d >>= 1) bits += __shfl_xor(bits, d);
+  if (lane == 0) a.tile_count[tile] = (uint32_t)bits;
 }
 
 // Yardstick for the streaming pass: the same traffic (three arrays read, two written,
@@ -816,6 +820,7 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
         const int64_t h = tile * 64 + ((r & 255) >> 2);        // the lane's 16-bit word
         const int q = (r >> 8) * 4 + (r & 3);
         atomicAnd(&mask32[h >> 1], ~((1u << q) << (16 * (int)(h & 1))));
+        atomicSub(&a.tile_count[tile], 1u);
       }
     }
   } else {
@@ -861,6 +866,7 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
       if (drop) {
         const int64_t h = tile * 64 + l;  // index of the 16-bit word
         atomicAnd(&mask32[h >> 1], ~(drop << (16 * (int)(h & 1))));
+        atomicSub(&a.tile_count[tile], (uint32_t)__popc(drop));
       }
     }
   }
@@ -885,11 +891,11 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
 // Two ways of handing out the slots:
 //   unordered  ONE atomic per workgroup on the tensor's counter reserves the slots
 //              in order of arrival; pairs land in unspecified order.
-//   sorted     a count pass has left every workgroup's number of bits in
-//              block_counts; a workgroup starts after the sum of its predecessors
-//              within the tensor and places its own elements in index order, so a
-//              region holds ascending indices, the result is the same on every
-//              run, and a full region keeps the lowest indices.
+//   sorted     the streaming pass has left the number of mask bits of every tile; a
+//              workgroup starts after the sum over the tensor's tiles before its own
+//              and places its own elements in index order, so a region holds
+//              ascending indices, the result is the same on every run, and a full
+//              region keeps the lowest indices.
 
 // This lane's mask word of tile t with the bits outside tensor [lo, hi) removed.
 __device__ __forceinline__ uint32_t tensor_tile_word(const uint16_t* __restrict__ mask, int64_t t, int lane,
@@ -906,33 +912,6 @@ __device__ __forceinline__ uint32_t tensor_tile_word(const uint16_t* __restrict_
     w &= keep;
   }
   return w;
-}
-
-// Count pass of the sorted output: mask bits of every emit workgroup's run.
-__global__ __launch_bounds__(kEmitThreads) void count_kernel(CountArgs a) {
-  constexpr int kWaves = kEmitThreads / 64;
-  constexpr int kPerWave = kEmitTiles / kWaves;
-  __shared__ int red[kWaves];
-  const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
-  const EmitBlock blk = a.blocks[blockIdx.x];
-  const int64_t lo = a.offsets[blk.tensor];
-  const int64_t hi = a.offsets[blk.tensor + 1];
-  const int64_t t1 = (hi - 1) / kWaveTile;
-  int cnt = 0;
-#pragma unroll
-  for (int i = 0; i < kPerWave; ++i) {
-    const int64_t t = (int64_t)blk.first_tile + wave + i * kWaves;
-    if (t <= t1) cnt += __popc(tensor_tile_word(a.mask, t, lane, lo, hi));
-  }
-  for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_down(cnt, d);
-  if (lane == 0) red[wave] = cnt;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int total = 0;
-    for (int w = 0; w < kWaves; ++w) total += red[w];
-    a.block_counts[blockIdx.x] = (uint32_t)total;
-  }
 }
 
 // Moves the `in_win` elements listed in `list` to slots slot0, slot0 + 1, ... of the
@@ -1079,12 +1058,28 @@ __global__ __launch_bounds__(kEmitThreads) void emit_sorted_kernel(EmitArgs a) {
   const int64_t t1 = (hi - 1) / kWaveTile;
   const int64_t first = blk.first_tile;
 
-  // slots taken by the workgroups before this one within the tensor (count pass)
-  const int in_tensor = (int)((first - lo / kWaveTile) / kEmitTiles);
-  const uint32_t* __restrict__ prior = a.block_counts + ((int64_t)blockIdx.x - in_tensor);
+  // Slots taken by the tiles of this tensor before the workgroup's first one.  Every tile
+  // strictly between the tensor's first tile and this workgroup's lies wholly inside the
+  // tensor, so its count left by the streaming pass (and kept up by the re-threshold pass)
+  // is what it contributes; the tensor's first tile may be shared with the tensor before
+  // and is recounted from its mask words.
+  const int64_t t0 = lo / kWaveTile;
+  const int in_tensor = (int)((first - t0) / kEmitTiles);
   int before = 0;
-  for (int b = threadIdx.x; b < in_tensor; b += kEmitThreads) before += (int)prior[b];
-
+  {
+    // eight loads in flight per thread: a big tensor has thousands of tiles before its last workgroups
+    const uint32_t* __restrict__ tc = a.tile_count;
+    int64_t t = t0 + 1 + threadIdx.x;
+    for (; t + 7 * kEmitThreads < first; t += 8 * kEmitThreads) {
+      uint32_t c[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) c[k] = tc[t + k * kEmitThreads];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) before += (int)c[k];
+    }
+    for (; t < first; t += kEmitThreads) before += (int)tc[t];
+  }
+  if (first > t0 && wave == 0) before += __popc(tensor_tile_word(a.mask, t0, lane, lo, hi));
   static_assert(kPerWave % 2 == 0, "tile totals are reduced two to a register");
   {
     uint32_t word[kPerWave];
@@ -1589,11 +1584,6 @@ hipError_t launch_ceiling(const float* a, float* b, float* c, int64_t n, hipStre
 
 hipError_t launch_refine(const RefineArgs& a, int32_t num_blocks, hipStream_t stream) {
   hipLaunchKernelGGL(refine_kernel, dim3((unsigned)num_blocks), dim3(kRefineThreads), 0, stream, a);
-  return hipGetLastError();
-}
-
-hipError_t launch_count(const CountArgs& a, int32_t num_blocks, hipStream_t stream) {
-  hipLaunchKernelGGL(count_kernel, dim3((unsigned)num_blocks), dim3(kEmitThreads), 0, stream, a);
   return hipGetLastError();
 }
 
