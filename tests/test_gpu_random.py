@@ -1,0 +1,58 @@
+"""Seeded random configurations of the whole path against the oracle: tensor sizes from
+one element to a few tiles, every flag combination, densities from 0.1 % to 100 %,
+sample blocks from 1 to 64, clipping on and off, payload capacities that overflow.
+Run with `-m gpu` on an MI355X."""
+
+import numpy as np
+import pytest
+
+from oracle import dgc_oracle as O
+from paper_1712_01887_amd import binding as B
+from tests.parity import Pair, check_overflow_invariants
+
+pytestmark = pytest.mark.gpu
+
+
+def random_case(seed: int):
+    rng = np.random.default_rng([seed, 4242])
+    T = int(rng.integers(1, 12))
+    sizes = [int(np.exp(rng.uniform(0.0, np.log(40000.0)))) for _ in range(T)]
+    offsets = np.concatenate([[0], np.cumsum(sizes)])
+    flags = 0
+    for f in (B.DGC_FLAG_NESTEROV, B.DGC_FLAG_NO_FACTOR_MASKING, B.DGC_FLAG_EXACT_SELECT, B.DGC_FLAG_SORTED_OUTPUT):
+        if rng.random() < 0.4:
+            flags |= f
+    block = int(rng.choice([1, 2, 8, 32, 64]))
+    smin = int(rng.choice([64, 256, 4096]))
+    kw = dict(momentum=float(rng.choice([0.0, 0.5, 0.9])), density=float(rng.choice([0.001, 0.01, 0.1, 0.5, 1.0])),
+              seed=int(rng.integers(0, 2 ** 40)), flags=flags, sample_block=block, sample_min=max(smin, block),
+              sample_max=max(smin, block) * int(rng.choice([1, 4])), sample_ratio=float(rng.choice([0.01, 0.1])))
+    if rng.random() < 0.4:
+        kw.update(clip_threshold=float(rng.choice([0.01, 1.0, 100.0])), num_workers=int(rng.integers(1, 9)))
+    if rng.random() < 0.3:
+        kw.update(refine_alpha=float(rng.choice([1.0, 1.5, 3.0])))
+    tight = rng.random() < 0.25                           # capacities below what will pass
+    return rng, offsets, sizes, kw, tight
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_configuration(seed):
+    rng, offsets, sizes, kw, tight = random_case(seed)
+    n = int(offsets[-1])
+    if tight:
+        caps = [max(1, O.topk_count(kw["density"], s) // 2) for s in sizes]
+        p = Pair(offsets, capacities=caps, **kw)
+    else:
+        p = Pair(offsets, layout_density=1.0, **kw)       # room for anything a small sample lets through
+    scale = float(rng.choice([1e-3, 1.0, 30.0]))
+    for it in range(3):
+        g = (scale * rng.standard_t(3, n)).astype(np.float32)
+        if rng.random() < 0.3:
+            g[rng.random(n) < 0.7] = 0.0                  # mostly zero: thresholds of 0, empty regions
+        u0 = p.u.cpu().numpy().copy()
+        v0 = p.v.cpu().numpy().copy()
+        res = p.step(g, it + int(rng.integers(0, 1000)) * (it == 2), label=f"random seed={seed} it{it} {kw}")
+        if res.overflow and not p.sorted:
+            check_overflow_invariants(p, g, u0, v0)
+            break                                         # the two sides' states differ from here on (order-dependent)
+    p.close()
