@@ -430,11 +430,10 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   }
 
   // paper: Appendix C equation 12 -- the local threshold is N^-1/2 times the global one.
+  // paper: Appendix C equation 12 -- the local threshold is N^-1/2 times the global one.
+  const double thr_local = clip ? (double)c.clip_threshold / std::sqrt((double)c.num_workers) : 0.0;
   if (clip) {
-    const double thr_local = (double)c.clip_threshold / std::sqrt((double)c.num_workers);
-    if (!hip_ok(launch_norm(g, h->n, state, at<double>(workspace, h->lay.partials), thr_local,
-                            c.scale_override, stream),
-                "launch norm kernel"))
+    if (!hip_ok(launch_norm(g, h->n, at<double>(workspace, h->lay.partials), stream), "launch norm kernel"))
       return DGC_ERR_HIP;
   }
   if (ev && !hip_ok(hipEventRecord(ev[1], stream), "record event")) return DGC_ERR_HIP;
@@ -449,6 +448,10 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   sa.thr = at<float>(workspace, h->lay.thr);
   sa.out_thr = out_thr;
   sa.tile_thr = at<float>(workspace, h->lay.tile_thr);
+  sa.partials = at<double>(workspace, h->lay.partials);
+  sa.thr_local = thr_local;
+  sa.num_partials = clip ? norm_blocks(h->n) : 0;
+  sa.scale_override = c.scale_override;
   sa.momentum = c.momentum;
   sa.scale_const = scale_const;
   sa.scale_from_state = clip ? 1 : 0;

@@ -70,8 +70,7 @@ struct DeviceState {
   double norm;           // L2 norm of g (clipping on)
   float scale;           // factor applied to g
   uint32_t flags;        // DGC_DIAG_*
-  uint32_t norm_ticket;  // workgroups of the norm kernel that have finished
-  uint32_t pad[3];
+  uint32_t pad[4];
 };
 
 // Per-tensor selection plan (host arithmetic, uploaded when the density changes).
@@ -101,9 +100,13 @@ struct SelectArgs {
   float* out_thr;       // may be null
   float* tile_thr;      // device, one word per wave tile: the threshold of every tile that lies
                         // wholly inside one tensor; the others hold a NaN put there once by the host
+  const double* partials;  // partial sums of the squared norm (clipping on)
+  double thr_local;        // thr_G / sqrt(N)
+  int32_t num_partials;
+  float scale_override;    // NaN: unused
   float momentum;
   float scale_const;
-  int32_t scale_from_state;  // 1: the norm kernel ran and left the scale in `state`
+  int32_t scale_from_state;  // 1: clipping is on; the scale comes from `partials` and is filed in `state`
   int32_t nesterov;
   int32_t block_shift;  // log2(sample_block)
   uint32_t seed_lo, seed_hi, iter_lo, iter_hi;
@@ -220,8 +223,8 @@ enum ScatterMode : int32_t {
 };
 
 // ---- launchers (dgc_kernels.hip) ---------------------------------------------
-hipError_t launch_norm(const float* g, int64_t n, DeviceState* state, double* partials,
-                       double thr_local, float scale_override, hipStream_t stream);
+int32_t norm_blocks(int64_t n);  // partial sums launch_norm leaves
+hipError_t launch_norm(const float* g, int64_t n, double* partials, hipStream_t stream);
 hipError_t launch_select(const SelectArgs& a, int32_t num_tensors, hipStream_t stream);
 hipError_t launch_stream(const StreamArgs& a, hipStream_t stream);
 hipError_t launch_ceiling(const float* a, float* b, float* c, int64_t n, hipStream_t stream);
