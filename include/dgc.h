@@ -50,7 +50,9 @@ enum {
   DGC_FLAG_DETERMINISTIC_ACCUMULATE = 1u << 3, /* receive side adds workers in order      */
   DGC_FLAG_SORTED_OUTPUT = 1u << 4      /* pairs of a tensor in ascending index order; the
                                            payload is then identical on every run, and a full
-                                           region keeps the lowest indices                   */
+                                           region keeps the lowest indices.  On the receive side
+                                           the flag states that every payload handed to
+                                           dgc_decompress_accumulate_regions is in that order   */
 };
 
 /* dgc_diagnostics.flags */
@@ -216,6 +218,10 @@ dgc_status dgc_decompress_accumulate(dgc_handle* h, float* dense, int64_t n, int
  * `out_offsets_host`; counts_w is the device int32[num_tensors] written by
  * dgc_compress (clamped to each region's capacity here).
  *   workspace    device workspace of this handle (holds the layout copy)
+ * With DGC_FLAG_SORTED_OUTPUT (every region ascending) and a density of at most 0.5 % the
+ * payloads are merged by index range in on-chip memory, workers added in the order given:
+ * one launch, no float atomics, and the result of the plain definition bit for bit.  A
+ * region that does not ascend then gives wrong sums (never an access out of bounds).
  */
 dgc_status dgc_decompress_accumulate_regions(dgc_handle* h, float* dense, int32_t num_payloads,
                                              const int32_t* const* idx_ptrs_host,

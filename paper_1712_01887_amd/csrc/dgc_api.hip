@@ -26,6 +26,7 @@ struct dgc_handle {
   std::vector<uint32_t> tile_info;   // ceil(n / kWaveTile)
   std::vector<float> tile_thr_init;  // ceil(n / kWaveTile): NaN where a tile is not wholly inside one tensor
   std::vector<EmitBlock> emit_blocks;  // work list of the emit pass
+  std::vector<MergeBlock> merge_blocks;  // work list of the receive side for sorted payloads
   WorkspaceLayout lay{};
   // what the bound workspace currently holds
   void* ws = nullptr;
@@ -55,6 +56,7 @@ bool hip_ok(hipError_t e, const char* what) {
 }
 
 constexpr size_t kAlign = 256;
+constexpr double kMergeMaxDensity = 0.005;  // receive side: LDS merge of sorted payloads up to here
 constexpr int kProfEvents = 5;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -132,6 +134,7 @@ void build_layout(dgc_handle* h) {
   l.counters = off;     off = align_up(off + sizeof(uint32_t) * kCounterStride * T);
   l.refine_counters = off; off = align_up(off + sizeof(uint32_t) * kCounterStride * T);
   l.tile_count = off;   off = align_up(off + sizeof(uint32_t) * tiles);
+  l.merge_blocks = off; off = align_up(off + sizeof(MergeBlock) * h->merge_blocks.size());
   // wire format: one block sum per kWireChunk pairs of every region (encoder, at most
   // n / kWireChunk + T) or per kWireChunk entries of every payload (decoder, an entry
   // stream of a set of n elements has at most n + (n >> 16) entries)
@@ -197,6 +200,10 @@ dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_
     if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.emit_blocks), h->emit_blocks.data(),
                                sizeof(EmitBlock) * h->emit_blocks.size(), hipMemcpyHostToDevice, stream),
                 "upload emit work list"))
+      return DGC_ERR_HIP;
+    if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.merge_blocks), h->merge_blocks.data(),
+                               sizeof(MergeBlock) * h->merge_blocks.size(), hipMemcpyHostToDevice, stream),
+                "upload merge work list"))
       return DGC_ERR_HIP;
     h->ws_static_valid = true;
   }
@@ -317,6 +324,19 @@ dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tenso
       const int64_t t1 = (h->offsets[t + 1] - 1) / kWaveTile;
       const int32_t nb = (int32_t)((t1 - t0) / kEmitTiles + 1);
       for (int64_t f = t0; f <= t1; f += kEmitTiles) h->emit_blocks.push_back(EmitBlock{t, (int32_t)f, nb, 0});
+    }
+    {
+      // element ranges of the receive side for sorted payloads: about kMergeTargetBlocks of them
+      // over the set, none across a tensor boundary
+      int64_t width = (h->n + kMergeTargetBlocks - 1) / kMergeTargetBlocks;
+      width = (width + 1023) / 1024 * 1024;
+      if (width < kMergeMinRange) width = kMergeMinRange;
+      if (width > kMergeMaxRange) width = kMergeMaxRange;
+      for (int32_t t = 0; t < num_tensors; ++t)
+        for (int64_t b = h->offsets[t]; b < h->offsets[t + 1]; b += width) {
+          const int64_t e = b + width < h->offsets[t + 1] ? b + width : h->offsets[t + 1];
+          h->merge_blocks.push_back(MergeBlock{b, e, t, 0});
+        }
     }
     h->ws_out_offsets.resize(num_tensors + 1);
     h->wire_first_block.resize(num_tensors + 1);
@@ -692,6 +712,16 @@ static dgc_status scatter_regions(dgc_handle* h, float* dense, int32_t num_paylo
   if (st != DGC_OK) return st;
   const int64_t* oo = at<int64_t>(workspace, h->lay.out_offsets);
   const int64_t widest = out_offsets_host[h->num_tensors];  // pairs a payload can hold
+  // Sorted payloads at the densities the method runs at: merged in LDS, workers in order,
+  // no atomics.  (At warm-up densities the pairs of a range outgrow LDS; the atomic path
+  // is the faster one there.)
+  if (op == ScatterOp::kAccumulate && (h->cfg.flags & DGC_FLAG_SORTED_OUTPUT) && h->cfg.density <= kMergeMaxDensity) {
+    if (!hip_ok(launch_merge_regions(dense, p, num_payloads, oo, at<MergeBlock>(workspace, h->lay.merge_blocks),
+                                     (int32_t)h->merge_blocks.size(), stream),
+                "launch merge kernel"))
+      return DGC_ERR_HIP;
+    return DGC_OK;
+  }
   if (clear) {
     if (!hip_ok(launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, widest,
                                        kScatterClear, 0.0f, nullptr, stream),

@@ -45,6 +45,17 @@ constexpr int kFlatPer = 4;
 constexpr int kFlatChunk = kFlatThreads * kFlatPer;
 constexpr int kFlatTensors = 1024;
 
+// Receive side for sorted payloads: a workgroup owns a range of one tensor's elements,
+// gathers the pairs of every payload that fall into it (found by search, the regions are
+// ascending) into LDS, and adds them up there.
+constexpr int kMergeThreads = 1024;
+constexpr int kMergeWaves = kMergeThreads / 64;
+constexpr int kMergeCap = 6144;          // pairs a workgroup takes into registers, slots of its LDS accumulator
+constexpr int kMergeMinRange = 65536;    // elements per workgroup, at least ...
+constexpr int kMergeMaxRange = 131072;   // ... and at most (one bitmap bit each)
+constexpr int kMergeTargetBlocks = 200;  // ranges aimed at over the whole set
+static_assert(kMergeCap % kMergeThreads == 0 && (kMergeMaxRange / 32) % kMergeThreads == 0, "dealt evenly to threads");
+
 // Wire format (32-bit values + 16-bit zero-run lengths): pairs or entries handled by one
 // workgroup, kWirePerThread consecutive ones per thread.
 constexpr int kWireThreads = 256;
@@ -87,7 +98,7 @@ struct TensorPlan {
 
 struct WorkspaceLayout {
   size_t state, partials, offsets, out_offsets, plans, thr, tile_info, tile_thr, emit_blocks, counters, refine_counters,
-      tile_count, wire_first_block, wire_sums, mask, total;
+      tile_count, merge_blocks, wire_first_block, wire_sums, mask, total;
 };
 
 struct SelectArgs {
@@ -169,6 +180,13 @@ struct EmitArgs {
   const uint32_t* tile_count;  // sorted output: mask bits per tile, left by the streaming pass
 };
 
+struct MergeBlock {
+  int64_t begin;   // first element (flat index) of the range
+  int64_t end;     // one past its last element; the range lies inside one tensor
+  int32_t tensor;
+  int32_t pad;
+};
+
 struct PairPayloads {
   const int32_t* idx[kMaxPayloads];
   const float* val[kMaxPayloads];
@@ -238,6 +256,8 @@ hipError_t launch_scatter_regions(float* dense, int64_t n, const RegionPayloads&
                                   int64_t total_capacity, ScatterMode mode, float scale,
                                   uint32_t* diag_flags, hipStream_t stream);
 
+hipError_t launch_merge_regions(float* dense, const RegionPayloads& p, int32_t num, const int64_t* out_offsets_dev,
+                                const MergeBlock* blocks, int32_t num_blocks, hipStream_t stream);
 hipError_t launch_encode(const EncodeArgs& a, int64_t widest_region, int32_t total_blocks, hipStream_t stream);
 hipError_t launch_decode(const DecodeArgs& a, int32_t first, int32_t num, bool atomic, hipStream_t stream);
 

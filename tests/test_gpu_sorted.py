@@ -105,3 +105,55 @@ def test_sorted_resnet50_set_and_high_density_speech():
         say(f"[sorted speech] iteration {it} density {d}")
         p.step(S.gradient(gs, 51, 0, it, scales), it, check_state=(it == 1), label=f"sorted speech it{it}")
     p.close()
+
+
+def _merge_case(gs, N, density, seed, scales=None, preset=None, **extra):
+    """N sorted payloads from correlated streams, accumulated by a handle that carries the
+    sorted flag (LDS merge, workers in order): bit-exact against the oracle's ordered sum."""
+    import torch
+    kw = dict(momentum=0.9, density=density, seed=seed, num_workers=N, flags=SORTED, **extra)
+    shared = S.gradient(gs, seed, 999, 0, scales)
+    pairs, payloads = [], []
+    for w in range(N):
+        p = Pair(gs.offsets, **kw)
+        res = p.step(S.correlated_gradient(gs, seed, w, 0, shared, scales=scales), 0, check_state=False,
+                     label=f"merge N={N} w{w}")
+        assert not res.overflow
+        p.u = p.v = None
+        p.ou = p.ov = None
+        payloads.append(O.flatten_payload(res))
+        pairs.append(p)
+    n = gs.numel
+    rng = np.random.default_rng(seed)
+    start = rng.standard_normal(n).astype(np.float32) if preset else np.zeros(n, np.float32)
+    expect = start.copy()
+    O.decompress_accumulate(expect, payloads)
+    acc = B.Dgc(B.make_config(**{k: v for k, v in kw.items() if k != "layout_density"}), gs.offsets)
+    acc.set_layout(pairs[0].layout)
+    dense = torch.from_numpy(start).cuda()
+    acc.dgc_decompress_accumulate_regions(dense, [p.out_idx for p in pairs], [p.out_val for p in pairs],
+                                          [p.out_counts for p in pairs])
+    got = dense.cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), expect.view(np.uint32)), \
+        np.flatnonzero(got.view(np.uint32) != expect.view(np.uint32))[:5]
+    overlap = S.topk_overlap(payloads[0][0], payloads[-1][0]) if N > 1 else 0.0
+    acc.close()
+    for p in pairs:
+        p.close()
+    return sum(i.size for i, _ in payloads), overlap
+
+
+@pytest.mark.parametrize("N,density,preset", [(1, 0.001, False), (4, 0.002, True), (16, 0.001, False),
+                                               (40, 0.001, True), (48, 0.005, False)])
+def test_sorted_payloads_are_merged_in_worker_order(N, density, preset):
+    gs = S.ragged_set(22, tensors=12, max_numel=400000)
+    total, overlap = _merge_case(gs, N, density, 70 + N, preset=preset, layout_density=max(density, 0.01) * 4,
+                                 sample_min=1024, sample_max=8192)
+    say(f"[merge] N={N} d={density}: {total} pairs, overlap first/last {overlap:.2f}")
+
+
+def test_sorted_sixteen_worker_merge_resnet50_shape():
+    gs = S.resnet50_set()
+    total, overlap = _merge_case(gs, 16, 0.001, 61, scales=S.tensor_scales(gs, 61))
+    say(f"[merge] resnet50 N=16: {total} pairs, overlap {overlap:.2f}")
+    assert 0.15 < overlap < 0.5
