@@ -52,10 +52,10 @@ WORKLOADS = {
 
 # HBM traffic of one streaming-kernel launch on the default workload from rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs, each scaled by what the same counter reads for a
-# device copy of n floats): 308.3 MB read + 207.7 MB written.  The counters cannot be
+# device copy of n floats): 308.3 MB read + 207.9 MB written.  The counters cannot be
 # read from inside this process; profiles/stream_kernel_resnet50_hbm_traffic.txt holds
 # the run this number comes from.
-MEASURED_TRAFFIC_BYTES = {"resnet50": 515988930}
+MEASURED_TRAFFIC_BYTES = {"resnet50": 516171480}
 
 
 def parse_args():
