@@ -248,7 +248,9 @@ dgc_status dgc_dense_clear_regions(dgc_handle* h, float* dense, int32_t num_payl
  * so that no dense aggregate is formed and none has to be cleared.  Arguments as for
  * dgc_decompress_accumulate / dgc_decompress_accumulate_regions, theta (device, n floats) in
  * place of dense.  Each pair is applied on its own (theta - lr*v1 - lr*v2 rather than
- * theta - lr*(v1 + v2)); with DGC_FLAG_DETERMINISTIC_ACCUMULATE workers are applied in order.
+ * theta - lr*(v1 + v2)); with DGC_FLAG_DETERMINISTIC_ACCUMULATE workers are applied in order,
+ * and so they are by dgc_sparse_sgd_apply_regions under the conditions of the merge path of
+ * dgc_decompress_accumulate_regions (DGC_FLAG_SORTED_OUTPUT, density at most 0.5 %).
  */
 dgc_status dgc_sparse_sgd_apply(dgc_handle* h, float* theta, int64_t n, float learning_rate,
                                 int32_t num_payloads, const int32_t* const* idx_ptrs_host,

@@ -715,9 +715,9 @@ static dgc_status scatter_regions(dgc_handle* h, float* dense, int32_t num_paylo
   // Sorted payloads at the densities the method runs at: merged in LDS, workers in order,
   // no atomics.  (At warm-up densities the pairs of a range outgrow LDS; the atomic path
   // is the faster one there.)
-  if (op == ScatterOp::kAccumulate && (h->cfg.flags & DGC_FLAG_SORTED_OUTPUT) && h->cfg.density <= kMergeMaxDensity) {
+  if (!clear && (h->cfg.flags & DGC_FLAG_SORTED_OUTPUT) && h->cfg.density <= kMergeMaxDensity) {
     if (!hip_ok(launch_merge_regions(dense, p, num_payloads, oo, at<MergeBlock>(workspace, h->lay.merge_blocks),
-                                     (int32_t)h->merge_blocks.size(), stream),
+                                     (int32_t)h->merge_blocks.size(), sgd, scale, stream),
                 "launch merge kernel"))
       return DGC_ERR_HIP;
     return DGC_OK;

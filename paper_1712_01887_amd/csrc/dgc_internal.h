@@ -257,7 +257,8 @@ hipError_t launch_scatter_regions(float* dense, int64_t n, const RegionPayloads&
                                   uint32_t* diag_flags, hipStream_t stream);
 
 hipError_t launch_merge_regions(float* dense, const RegionPayloads& p, int32_t num, const int64_t* out_offsets_dev,
-                                const MergeBlock* blocks, int32_t num_blocks, hipStream_t stream);
+                                const MergeBlock* blocks, int32_t num_blocks, bool scaled, float scale,
+                                hipStream_t stream);
 hipError_t launch_encode(const EncodeArgs& a, int64_t widest_region, int32_t total_blocks, hipStream_t stream);
 hipError_t launch_decode(const DecodeArgs& a, int32_t first, int32_t num, bool atomic, hipStream_t stream);
 

@@ -1365,10 +1365,13 @@ struct MergeShared {
   int64_t slot[kMaxPayloads];       // where payload w's pairs inside the range start in its arrays
 };
 
+// `scale` multiplies every value first (1 for the plain sum; -learning rate for the SGD
+// apply, where `dense` is the parameter vector).
 __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __restrict__ dense, RegionPayloads p,
                                                                       int32_t num_payloads,
                                                                       const int64_t* __restrict__ out_offsets,
-                                                                      const MergeBlock* __restrict__ blocks) {
+                                                                      const MergeBlock* __restrict__ blocks,
+                                                                      float scale, int32_t scaled) {
   constexpr int kPerThread = kMergeCap / kMergeThreads;
   constexpr int kWordsPerThread = kMergeMaxRange / 32 / kMergeThreads;
   __shared__ MergeShared sh;
@@ -1427,7 +1430,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
         }
         const int64_t src = sh.slot[w] + (q - sh.begin[w]);
         const int64_t r = (int64_t)p.idx[w][src] - blk.begin;
-        x[k] = p.val[w][src];
+        x[k] = scaled ? scale * p.val[w][src] : p.val[w][src];
         pw[k] = w;
         if (r >= 0 && r < length) {  // anything else can only come from a region that does not ascend
           rel[k] = (int32_t)r;
@@ -1507,7 +1510,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
         if (b < len && L[b] == i) owner = false;
       }
       if (!owner) continue;
-      float d = dense[i] + p.val[w][src];
+      float d = dense[i] + (scaled ? scale * p.val[w][src] : p.val[w][src]);
       for (int v = w + 1; v < num_payloads; ++v) {
         const int32_t* L = p.idx[v] + sh.slot[v];
         int b = 0, en = sh.begin[v + 1] - sh.begin[v];
@@ -1517,7 +1520,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
           if (L[mid] < i) b = mid + 1;
           else en = mid;
         }
-        if (b < len && L[b] == i) d = d + p.val[v][sh.slot[v] + b];
+        if (b < len && L[b] == i) d = d + (scaled ? scale * p.val[v][sh.slot[v] + b] : p.val[v][sh.slot[v] + b]);
       }
       dense[i] = d;
     }
@@ -1837,10 +1840,11 @@ hipError_t launch_scatter_regions(float* dense, int64_t n, const RegionPayloads&
 }
 
 hipError_t launch_merge_regions(float* dense, const RegionPayloads& p, int32_t num, const int64_t* out_offsets_dev,
-                                const MergeBlock* blocks, int32_t num_blocks, hipStream_t stream) {
+                                const MergeBlock* blocks, int32_t num_blocks, bool scaled, float scale,
+                                hipStream_t stream) {
   if (num <= 0 || num_blocks <= 0) return hipSuccess;
   hipLaunchKernelGGL(merge_regions_kernel, dim3((unsigned)num_blocks), dim3(kMergeThreads), 0, stream, dense, p, num,
-                     out_offsets_dev, blocks);
+                     out_offsets_dev, blocks, scale, scaled ? 1 : 0);
   return hipGetLastError();
 }
 

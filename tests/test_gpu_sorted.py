@@ -157,3 +157,30 @@ def test_sorted_sixteen_worker_merge_resnet50_shape():
     total, overlap = _merge_case(gs, 16, 0.001, 61, scales=S.tensor_scales(gs, 61))
     say(f"[merge] resnet50 N=16: {total} pairs, overlap {overlap:.2f}")
     assert 0.15 < overlap < 0.5
+
+
+def test_sorted_sparse_sgd_apply_is_merged_in_worker_order():
+    import torch
+    gs = S.ragged_set(23, tensors=9, max_numel=300000)
+    N, lr = 6, 0.05
+    kw = dict(momentum=0.9, density=0.002, seed=12, num_workers=N, flags=SORTED, sample_min=1024, sample_max=8192)
+    shared = S.gradient(gs, 29, 99, 0)
+    pairs, payloads = [], []
+    for w in range(N):
+        p = Pair(gs.offsets, layout_density=0.02, **kw)
+        res = p.step(S.correlated_gradient(gs, 29, w, 0, shared), 0, label=f"sorted sgd w{w}")
+        payloads.append(O.flatten_payload(res))
+        pairs.append(p)
+    rng = np.random.default_rng(5)
+    theta0 = rng.standard_normal(gs.numel).astype(np.float32)
+    expect = theta0.copy()
+    O.sparse_sgd_apply(expect, payloads, lr)
+    opt = B.Dgc(B.make_config(**kw), gs.offsets)
+    opt.set_layout(pairs[0].layout)
+    theta = torch.from_numpy(theta0).cuda()
+    opt.dgc_sparse_sgd_apply_regions(theta, lr, [p.out_idx for p in pairs], [p.out_val for p in pairs],
+                                     [p.out_counts for p in pairs])
+    assert np.array_equal(theta.cpu().numpy().view(np.uint32), expect.view(np.uint32))
+    opt.close()
+    for p in pairs:
+        p.close()
