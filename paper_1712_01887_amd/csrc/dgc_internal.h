@@ -24,7 +24,7 @@ constexpr int kStreamThreads = 256;                 // 4 wavefronts per workgrou
 constexpr int kStreamWaves = kStreamThreads / 64;
 // Tile table: one int32 per wave tile = index of the tensor that holds the tile's
 // first element, with the top bit set when the tile is not wholly inside one
-// tensor or is the ragged last tile (such tiles take the general path).
+// tensor or is the ragged last tile (such tiles look up every element's tensor).
 constexpr uint32_t kTileMixed = 0x80000000u;
 
 // Emit pass: a workgroup takes kEmitTiles consecutive wave tiles of one tensor.
