@@ -68,6 +68,7 @@ constexpr int kSelectThreads = 1024;
 constexpr int kSelectRegKeys = 32;    // candidate keys a thread keeps in registers (32 * 1024 in all)
 constexpr int kSelectDirect = 256;    // a bin with at most this many members is ranked directly
 constexpr int kSelectBins = 2048;     // 11-bit digits
+constexpr int kSelectFloorRounds = 8; // ranks below 16 * this take the short cut over the threads' largest keys
 constexpr int kSelectInFlight = 8;    // candidates each thread gathers before using any
 
 // Clipping norm: a fixed number of partial sums keeps the result reproducible.

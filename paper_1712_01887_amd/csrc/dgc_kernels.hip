@@ -154,7 +154,7 @@ struct SelectShared {
   float scale;
   uint32_t hist[kSelectBins];
   uint32_t wave_tot[kSelectThreads / 64];
-  uint32_t surv[kSelectDirect];
+  uint32_t surv[kSelectThreads];
   uint32_t sel[3];
   uint32_t surv_n, result;
 };
@@ -214,6 +214,52 @@ __device__ __forceinline__ uint32_t rank_directly(SelectShared& sh, int tid, uin
   }
   __syncthreads();
   return sh.result;
+}
+
+// Key of descending rank `rank` among the keys a workgroup holds in registers (NKEYS per
+// thread), ignoring empty slots (kNoKey) and keys below `floor_key`; the caller
+// guarantees that more than `rank` keys are considered.  Every thread returns the same.
+constexpr uint32_t kNoKey = 0xFFFFFFFFu;  // real keys have the sign bit clear
+
+template <int NKEYS>
+__device__ __forceinline__ uint32_t select_in_registers(SelectShared& sh, const uint32_t (&key)[NKEYS],
+                                                        uint32_t floor_key, uint32_t rank, int tid) {
+  uint32_t prefix = 0;
+  int consumed = 0;  // key bits fixed so far (below the sign bit)
+#pragma unroll 1
+  for (int pass = 0; pass < 3; ++pass) {
+    const int bits = pass == 2 ? 9 : 11;
+    const int shift = 31 - consumed - bits;
+    const uint32_t digit_mask = (1u << bits) - 1u;
+    for (int i = tid; i < kSelectBins; i += kSelectThreads) sh.hist[i] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NKEYS; ++i) {
+      const uint32_t k = key[i];
+      if (k != kNoKey && k >= floor_key && (pass == 0 || (k >> (shift + bits)) == prefix))
+        atomicAdd(&sh.hist[(k >> shift) & digit_mask], 1u);
+    }
+    __syncthreads();
+    uint32_t bin, above, members;
+    find_bin<kSelectThreads>(sh.hist, sh.wave_tot, sh.sel, tid, rank, bin, above, members);
+    prefix = (prefix << bits) | bin;
+    rank -= above;
+    consumed += bits;
+    if (consumed == 31) return prefix;
+    if (members <= (uint32_t)kSelectDirect) {
+      if (tid == 0) sh.surv_n = 0;
+      __syncthreads();
+      const int low = 31 - consumed;  // key bits not yet fixed
+#pragma unroll
+      for (int i = 0; i < NKEYS; ++i) {
+        const uint32_t k = key[i];
+        if (k != kNoKey && k >= floor_key && (k >> low) == prefix) sh.surv[atomicAdd(&sh.surv_n, 1u)] = k;
+      }
+      __syncthreads();
+      return rank_directly(sh, tid, members, rank);
+    }
+  }
+  return prefix;
 }
 
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
@@ -296,14 +342,10 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
 
   if (count <= kSelectRegKeys * kSelectThreads) {
     // ---- candidates in registers ------------------------------------------------
-    constexpr uint32_t kNoKey = 0xFFFFFFFFu;  // real keys have the sign bit clear
     uint32_t key[kSelectRegKeys];
 #pragma unroll
     for (int i = 0; i < kSelectRegKeys; ++i) key[i] = kNoKey;
-    for (int i = tid; i < kSelectBins; i += kSelectThreads) sh.hist[i] = 0;
-    __syncthreads();
-    // Gather: kSelectInFlight candidates per thread are loaded before any is used; the
-    // gathers are random cache-line reads, so latency, not bandwidth, sets the pace.
+    // Gather: kSelectInFlight candidates per thread are loaded before any is used.
 #pragma unroll
     for (int r = 0; r < kSelectRegKeys / kSelectInFlight; ++r) {
       if (r * kSelectInFlight * kSelectThreads < count) {  // uniform
@@ -325,54 +367,62 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
           if (p < count) {
             float u1, v1;
             momentum_update(gg[q], uu[q], vv[q], c.m, c.scale, c.nesterov, u1, v1);
-            const uint32_t k = __float_as_uint(v1) & 0x7FFFFFFFu;
-            key[r * kSelectInFlight + q] = k;
-            atomicAdd(&sh.hist[k >> 20], 1u);
+            key[r * kSelectInFlight + q] = __float_as_uint(v1) & 0x7FFFFFFFu;
           }
         }
       }
     }
-    __syncthreads();
-    int consumed = 0;  // key bits fixed so far (below the sign bit)
-#pragma unroll 1
-    for (int pass = 0; pass < 3; ++pass) {
-      const int bits = pass == 2 ? 9 : 11;
-      const int shift = 31 - consumed - bits;
-      if (pass > 0) {
-        for (int i = tid; i < kSelectBins; i += kSelectThreads) sh.hist[i] = 0;
-        __syncthreads();
-        const uint32_t digit_mask = (1u << bits) - 1u;
+    // Gradients of one tensor share a few exponents, so a histogram over the leading key
+    // bits of all candidates piles tens of thousands of LDS atomics on a handful of bins,
+    // and every histogram pass costs half a dozen barriers of 1024 threads (ranking 32 Ki
+    // keys that way took 20 us, against 3 us this way).  At the paper's densities the
+    // rank r is a few dozen, and a floor below which no key matters is cheap to get: if
+    // every one of the 16 wavefronts names the t-th largest of its threads' largest
+    // keys, 16 t > r, then the smallest of the 16 answers has more than r keys at or
+    // above it.  What lies at or above that floor (a few times r keys) is listed in LDS
+    // and ranked by direct counting.  Anything that does not fit this pattern takes the
+    // histogram passes.
+    constexpr int kWaves = kSelectThreads / 64;
+    const uint32_t t_rounds = rank / kWaves + 1;  // kWaves * t_rounds > rank
+    bool done = false;
+    if (count > 2 * kSelectThreads && t_rounds <= (uint32_t)kSelectFloorRounds) {
+      const int lane = tid & 63;
+      uint32_t top = 0;  // this thread's largest key (every thread has keys: count > 2048)
 #pragma unroll
-        for (int i = 0; i < kSelectRegKeys; ++i) {
-          const uint32_t k = key[i];
-          if (k != kNoKey && (k >> (shift + bits)) == prefix)
-            atomicAdd(&sh.hist[(k >> shift) & digit_mask], 1u);
+      for (int i = 0; i < kSelectRegKeys; ++i)
+        if (key[i] != kNoKey) top = key[i] > top ? key[i] : top;
+      uint32_t tth = 0;
+      for (uint32_t round = 0; round < t_rounds; ++round) {
+        uint32_t m = top;
+        for (int d = 32; d >= 1; d >>= 1) {
+          const uint32_t o = __shfl_xor(m, d);
+          m = o > m ? o : m;
         }
-        __syncthreads();
+        tth = m;
+        const unsigned long long holders = __ballot(top == m);
+        if (lane == __ffsll((long long)holders) - 1) top = 0;  // one holder of the maximum steps down
       }
-      uint32_t bin, above, members;
-      find_bin<kSelectThreads>(sh.hist, sh.wave_tot, sh.sel, tid, rank, bin, above, members);
-      prefix = (prefix << bits) | bin;
-      rank -= above;
-      consumed += bits;
-      if (consumed == 31) {
-        thr_bits = prefix;
-        break;
-      }
-      if (members <= (uint32_t)kSelectDirect) {
-        if (tid == 0) sh.surv_n = 0;
-        __syncthreads();
-        const int low = 31 - consumed;  // key bits not yet fixed
+      if (lane == 0) sh.wave_tot[tid >> 6] = tth;
+      if (tid == 0) sh.surv_n = 0;
+      __syncthreads();
+      uint32_t floor_key = sh.wave_tot[0];
 #pragma unroll
-        for (int i = 0; i < kSelectRegKeys; ++i) {
-          const uint32_t k = key[i];
-          if (k != kNoKey && (k >> low) == prefix) sh.surv[atomicAdd(&sh.surv_n, 1u)] = k;
+      for (int w = 1; w < kWaves; ++w) floor_key = sh.wave_tot[w] < floor_key ? sh.wave_tot[w] : floor_key;
+#pragma unroll
+      for (int i = 0; i < kSelectRegKeys; ++i)
+        if (key[i] != kNoKey && key[i] >= floor_key) {
+          const uint32_t pos = atomicAdd(&sh.surv_n, 1u);
+          if (pos < (uint32_t)kSelectThreads) sh.surv[pos] = key[i];
         }
-        __syncthreads();
-        thr_bits = rank_directly(sh, tid, members, rank);
-        break;
+      __syncthreads();
+      const uint32_t listed = sh.surv_n;
+      if (listed <= (uint32_t)kSelectThreads) {
+        thr_bits = rank_directly(sh, tid, listed, rank);
+        done = true;
       }
+      __syncthreads();
     }
+    if (!done) thr_bits = select_in_registers<kSelectRegKeys>(sh, key, 0u, rank, tid);
   } else {
     // ---- candidates re-evaluated in every pass -----------------------------------
     int consumed = 0;
