@@ -50,9 +50,7 @@ enum {
   DGC_FLAG_DETERMINISTIC_ACCUMULATE = 1u << 3, /* receive side adds workers in order      */
   DGC_FLAG_SORTED_OUTPUT = 1u << 4      /* pairs of a tensor in ascending index order; the
                                            payload is then identical on every run, and a full
-                                           region keeps the lowest indices.  On the receive side
-                                           the flag states that every payload handed to
-                                           dgc_decompress_accumulate_regions is in that order   */
+                                           region keeps the lowest indices                      */
 };
 
 /* dgc_diagnostics.flags */
@@ -171,11 +169,12 @@ dgc_status dgc_recommended_payload_layout(const dgc_handle* h, double density,
  *              region; read during the call (the caller may reuse it afterwards)
  *   out_counts device, int32[num_tensors]: elements of tensor j that passed the
  *              mask.  Pairs [out_offsets[j], out_offsets[j] + min(count_j, capacity_j))
- *              are valid, in unspecified order (ascending indices with
- *              DGC_FLAG_SORTED_OUTPUT).  An element that passed but found the
+ *              are valid: the same pairs in the same order on every run, the parts of
+ *              consecutive blocks of 32768 elements in index order, ascending throughout
+ *              with DGC_FLAG_SORTED_OUTPUT.  An element that passed but found the
  *              region full is neither emitted nor cleared (it stays in u, v) and
- *              DGC_DIAG_OVERFLOW is raised; which elements those are depends on the
- *              order of arrival, with DGC_FLAG_SORTED_OUTPUT they are the highest indices.
+ *              DGC_DIAG_OVERFLOW is raised; with DGC_FLAG_SORTED_OUTPUT those are the
+ *              highest indices.
  *   out_thr    device, float[num_tensors], or NULL
  *   iteration  t: with the seed and the tensor index it fixes the sample positions
  *   workspace  device, >= dgc_workspace_bytes, 256-byte aligned; it must not be
@@ -218,10 +217,15 @@ dgc_status dgc_decompress_accumulate(dgc_handle* h, float* dense, int64_t n, int
  * `out_offsets_host`; counts_w is the device int32[num_tensors] written by
  * dgc_compress (clamped to each region's capacity here).
  *   workspace    device workspace of this handle (holds the layout copy)
- * With DGC_FLAG_SORTED_OUTPUT (every region ascending) and a density of at most 0.5 % the
- * payloads are merged by index range in on-chip memory, workers added in the order given:
- * one launch, no float atomics, and the result of the plain definition bit for bit.  A
- * region that does not ascend then gives wrong sums (never an access out of bounds).
+ * The regions must be as dgc_compress of this library writes them (the parts of
+ * consecutive blocks of 32768 elements of a tensor follow each other in index order; the
+ * order inside a part is free): at a density of at most 0.5 % the payloads are merged by
+ * element range in on-chip memory, workers added in the order given, in one launch and
+ * without float atomics, which gives the result of the plain definition bit for bit.  A
+ * region laid out otherwise then gives wrong sums (never an access out of bounds); for
+ * arbitrary pair lists there is dgc_decompress_accumulate.  At higher densities the
+ * additions are float atomics in arbitrary order, or one launch per worker with
+ * DGC_FLAG_DETERMINISTIC_ACCUMULATE.
  */
 dgc_status dgc_decompress_accumulate_regions(dgc_handle* h, float* dense, int32_t num_payloads,
                                              const int32_t* const* idx_ptrs_host,
@@ -249,8 +253,8 @@ dgc_status dgc_dense_clear_regions(dgc_handle* h, float* dense, int32_t num_payl
  * dgc_decompress_accumulate / dgc_decompress_accumulate_regions, theta (device, n floats) in
  * place of dense.  Each pair is applied on its own (theta - lr*v1 - lr*v2 rather than
  * theta - lr*(v1 + v2)); with DGC_FLAG_DETERMINISTIC_ACCUMULATE workers are applied in order,
- * and so they are by dgc_sparse_sgd_apply_regions under the conditions of the merge path of
- * dgc_decompress_accumulate_regions (DGC_FLAG_SORTED_OUTPUT, density at most 0.5 %).
+ * and so they are by dgc_sparse_sgd_apply_regions at a density of at most 0.5 % (see
+ * dgc_decompress_accumulate_regions).
  */
 dgc_status dgc_sparse_sgd_apply(dgc_handle* h, float* theta, int64_t n, float learning_rate,
                                 int32_t num_payloads, const int32_t* const* idx_ptrs_host,

@@ -56,7 +56,7 @@ bool hip_ok(hipError_t e, const char* what) {
 }
 
 constexpr size_t kAlign = 256;
-constexpr double kMergeMaxDensity = 0.005;  // receive side: LDS merge of sorted payloads up to here
+constexpr double kMergeMaxDensity = 0.005;  // receive side: merge by element range in LDS up to here
 constexpr int kProfEvents = 5;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -131,7 +131,6 @@ void build_layout(dgc_handle* h) {
   l.tile_info = off;    off = align_up(off + sizeof(uint32_t) * tiles);
   l.tile_thr = off;     off = align_up(off + sizeof(float) * tiles);
   l.emit_blocks = off;  off = align_up(off + sizeof(EmitBlock) * h->emit_blocks.size());
-  l.counters = off;     off = align_up(off + sizeof(uint32_t) * kCounterStride * T);
   l.refine_counters = off; off = align_up(off + sizeof(uint32_t) * kCounterStride * T);
   l.tile_count = off;   off = align_up(off + sizeof(uint32_t) * tiles);
   l.merge_blocks = off; off = align_up(off + sizeof(MergeBlock) * h->merge_blocks.size());
@@ -181,9 +180,9 @@ dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_
     if (!hip_ok(hipMemsetAsync(at<char>(ws, h->lay.state), 0, sizeof(DeviceState), stream),
                 "clear workspace state"))
       return DGC_ERR_HIP;
-    if (!hip_ok(hipMemsetAsync(at<char>(ws, h->lay.counters), 0, 2 * align_up(sizeof(uint32_t) * kCounterStride * T),
+    if (!hip_ok(hipMemsetAsync(at<char>(ws, h->lay.refine_counters), 0, align_up(sizeof(uint32_t) * kCounterStride * T),
                                stream),
-                "clear emit counters"))
+                "clear re-threshold counters"))
       return DGC_ERR_HIP;
     if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.offsets), h->offsets.data(),
                                sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, stream),
@@ -325,18 +324,17 @@ dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tenso
       const int32_t nb = (int32_t)((t1 - t0) / kEmitTiles + 1);
       for (int64_t f = t0; f <= t1; f += kEmitTiles) h->emit_blocks.push_back(EmitBlock{t, (int32_t)f, nb, 0});
     }
-    {
-      // element ranges of the receive side for sorted payloads: about kMergeTargetBlocks of them
-      // over the set, none across a tensor boundary
-      int64_t width = (h->n + kMergeTargetBlocks - 1) / kMergeTargetBlocks;
-      width = (width + 1023) / 1024 * 1024;
-      if (width < kMergeMinRange) width = kMergeMinRange;
-      if (width > kMergeMaxRange) width = kMergeMaxRange;
-      for (int32_t t = 0; t < num_tensors; ++t)
-        for (int64_t b = h->offsets[t]; b < h->offsets[t + 1]; b += width) {
-          const int64_t e = b + width < h->offsets[t + 1] ? b + width : h->offsets[t + 1];
-          h->merge_blocks.push_back(MergeBlock{b, e, t, 0});
-        }
+    // element ranges of the receive side: kMergeEmitBlocks consecutive emit workgroups' parts of one tensor
+    for (size_t b = 0; b < h->emit_blocks.size();) {
+      const int32_t t = h->emit_blocks[b].tensor;
+      size_t e = b;
+      while (e < h->emit_blocks.size() && e < b + kMergeEmitBlocks && h->emit_blocks[e].tensor == t) ++e;
+      int64_t begin = (int64_t)h->emit_blocks[b].first_tile * kWaveTile;
+      int64_t end = (int64_t)(h->emit_blocks[e - 1].first_tile + kEmitTiles) * kWaveTile;
+      if (begin < h->offsets[t]) begin = h->offsets[t];
+      if (end > h->offsets[t + 1]) end = h->offsets[t + 1];
+      h->merge_blocks.push_back(MergeBlock{begin, end, t, 0});
+      b = e;
     }
     h->ws_out_offsets.resize(num_tensors + 1);
     h->wire_first_block.resize(num_tensors + 1);
@@ -531,7 +529,6 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   EmitArgs ea{};
   ea.blocks = at<EmitBlock>(workspace, h->lay.emit_blocks);
   ea.tile_count = at<uint32_t>(workspace, h->lay.tile_count);
-  ea.counters = at<uint32_t>(workspace, h->lay.counters);
   ea.u = u;
   ea.v = v;
   ea.mask = ta.mask;
@@ -712,10 +709,10 @@ static dgc_status scatter_regions(dgc_handle* h, float* dense, int32_t num_paylo
   if (st != DGC_OK) return st;
   const int64_t* oo = at<int64_t>(workspace, h->lay.out_offsets);
   const int64_t widest = out_offsets_host[h->num_tensors];  // pairs a payload can hold
-  // Sorted payloads at the densities the method runs at: merged in LDS, workers in order,
-  // no atomics.  (At warm-up densities the pairs of a range outgrow LDS; the atomic path
-  // is the faster one there.)
-  if (!clear && (h->cfg.flags & DGC_FLAG_SORTED_OUTPUT) && h->cfg.density <= kMergeMaxDensity) {
+  // At the densities the method runs at: merged by element range in LDS, workers in order, no
+  // atomics.  (At warm-up densities the pairs of a range outgrow LDS and the scattered
+  // kernels are the faster ones.)
+  if (!clear && h->cfg.density <= kMergeMaxDensity) {
     if (!hip_ok(launch_merge_regions(dense, p, num_payloads, oo, at<MergeBlock>(workspace, h->lay.merge_blocks),
                                      (int32_t)h->merge_blocks.size(), sgd, scale, stream),
                 "launch merge kernel"))

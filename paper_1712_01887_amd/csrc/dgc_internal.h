@@ -34,7 +34,7 @@ constexpr int kEmitTiles = kEmitElements / kWaveTile;
 static_assert(kEmitTiles % (kEmitThreads / 64) == 0, "tiles are dealt round-robin to wavefronts");
 constexpr int kEmitList = 4096;                       // elements listed in LDS at a time
 constexpr int kRefineThreads = 1024;                  // the re-threshold pass shares the emit work list
-// Per-tensor counters of the emit pass live one per 128-byte line so that atomics
+// Per-tensor counters of the re-threshold pass live one per 128-byte line so that atomics
 // on different tensors do not serialise on a shared line.
 constexpr int kCounterStride = 32;  // uint32 words
 
@@ -45,15 +45,15 @@ constexpr int kFlatPer = 4;
 constexpr int kFlatChunk = kFlatThreads * kFlatPer;
 constexpr int kFlatTensors = 1024;
 
-// Receive side for sorted payloads: a workgroup owns a range of one tensor's elements,
-// gathers the pairs of every payload that fall into it (found by search, the regions are
-// ascending) into LDS, and adds them up there.
+// Receive side without atomics: a workgroup owns a range of one tensor's elements (a
+// whole number of emit workgroups' parts, which follow each other in index order in
+// every payload's region), finds the pairs of every payload that fall into it by search,
+// and adds them up in LDS.
 constexpr int kMergeThreads = 1024;
 constexpr int kMergeWaves = kMergeThreads / 64;
 constexpr int kMergeCap = 6144;          // pairs a workgroup takes into registers, slots of its LDS accumulator
-constexpr int kMergeMinRange = 65536;    // elements per workgroup, at least ...
-constexpr int kMergeMaxRange = 131072;   // ... and at most (one bitmap bit each)
-constexpr int kMergeTargetBlocks = 200;  // ranges aimed at over the whole set
+constexpr int kMergeMaxRange = 131072;   // elements per workgroup at most (one bitmap bit each)
+constexpr int kMergeEmitBlocks = kMergeMaxRange / kEmitElements;  // emit workgroups' parts per range
 static_assert(kMergeCap % kMergeThreads == 0 && (kMergeMaxRange / 32) % kMergeThreads == 0, "dealt evenly to threads");
 
 // Wire format (32-bit values + 16-bit zero-run lengths): pairs or entries handled by one
@@ -98,7 +98,7 @@ struct TensorPlan {
 };
 
 struct WorkspaceLayout {
-  size_t state, partials, offsets, out_offsets, plans, thr, tile_info, tile_thr, emit_blocks, counters, refine_counters,
+  size_t state, partials, offsets, out_offsets, plans, thr, tile_info, tile_thr, emit_blocks, refine_counters,
       tile_count, merge_blocks, wire_first_block, wire_sums, mask, total;
 };
 
@@ -167,7 +167,6 @@ struct RefineArgs {
 
 struct EmitArgs {
   const EmitBlock* blocks;     // device, one entry per workgroup
-  uint32_t* counters;          // device, kCounterStride words per tensor, zero between calls
   float* u;
   float* v;
   const uint16_t* mask;
@@ -178,7 +177,7 @@ struct EmitArgs {
   int32_t* out_counts;         // device, T
   DeviceState* state;
   int32_t factor_masking;
-  const uint32_t* tile_count;  // sorted output: mask bits per tile, left by the streaming pass
+  const uint32_t* tile_count;  // mask bits per tile, left by the streaming pass
 };
 
 struct MergeBlock {

@@ -940,14 +940,16 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
 // finds the region full is left untouched (it stays in u, v) and the overflow flag
 // is set.
 //
-// Two ways of handing out the slots:
-//   unordered  ONE atomic per workgroup on the tensor's counter reserves the slots
-//              in order of arrival; pairs land in unspecified order.
-//   sorted     the streaming pass has left the number of mask bits of every tile; a
-//              workgroup starts after the sum over the tensor's tiles before its own
-//              and places its own elements in index order, so a region holds
-//              ascending indices, the result is the same on every run, and a full
-//              region keeps the lowest indices.
+// The streaming pass has left the number of mask bits of every tile; a workgroup starts
+// after the sum over the tensor's tiles before its own, so the workgroups' parts follow
+// each other in index order and the region is the same on every run.  Inside its part a
+// workgroup places its elements
+//   plain   in the order wavefront, lane, tile, bit (whatever is cheapest), or
+//   sorted  in index order (DGC_FLAG_SORTED_OUTPUT): the whole region ascends, and a
+//           full region keeps the lowest indices.
+// (A first version reserved slots with one atomic per workgroup in order of arrival; the
+// receive side can find a range of elements in a region by search only if the parts are
+// in order.)
 
 // This lane's mask word of tile t with the bits outside tensor [lo, hi) removed.
 __device__ __forceinline__ uint32_t tensor_tile_word(const uint16_t* __restrict__ mask, int64_t t, int lane,
@@ -1007,6 +1009,7 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
   constexpr int kWaves = kEmitThreads / 64;
   constexpr int kPerWave = kEmitTiles / kWaves;
   __shared__ int wave_tot[kWaves];
+  __shared__ int pre_tot[kWaves];
   __shared__ int block_base;
   __shared__ int32_t list[kEmitList];
 
@@ -1042,17 +1045,33 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
     if (w < wave) before += t;
     total += t;
   }
-  if (threadIdx.x == 0) {
-    // One 64-bit atomic both reserves the slots (low word: elements passed so far) and
-    // takes the arrival ticket (high word: workgroups done).  The workgroup that arrives
-    // last for this tensor publishes the count and leaves the counter at zero for the
-    // next call.  Only atomics carry information between workgroups, so no fence is needed.
-    unsigned long long* ctr = reinterpret_cast<unsigned long long*>(a.counters + (size_t)j * kCounterStride);
-    const unsigned long long old = atomicAdd(ctr, (unsigned long long)(uint32_t)total | (1ull << 32));
-    block_base = (int)(uint32_t)old;
-    if ((uint32_t)(old >> 32) == (uint32_t)blk.tensor_blocks - 1u) {
-      a.out_counts[j] = (int32_t)((uint32_t)old + (uint32_t)total);
-      atomicExch(ctr, 0ull);
+  // Slots taken by the tiles of this tensor before the workgroup's first one: the counts
+  // the streaming pass has left (every tile strictly between the tensor's first tile and
+  // this workgroup's lies wholly inside the tensor), plus the tensor's share of its first
+  // tile, recounted from the mask words.  No atomics, no tickets: the workgroups of a
+  // tensor fill its region in index order, so the region is the same on every run.
+  {
+    const int64_t t0 = lo / kWaveTile;
+    int pre = 0;
+    const uint32_t* __restrict__ tc = a.tile_count;
+    int64_t t = t0 + 1 + threadIdx.x;
+    for (; t + 7 * kEmitThreads < first; t += 8 * kEmitThreads) {  // eight loads in flight per thread
+      uint32_t c[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) c[k] = tc[t + k * kEmitThreads];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) pre += (int)c[k];
+    }
+    for (; t < first; t += kEmitThreads) pre += (int)tc[t];
+    if (first > t0 && wave == 0) pre += __popc(tensor_tile_word(a.mask, t0, lane, lo, hi));
+    for (int d = 32; d >= 1; d >>= 1) pre += __shfl_xor(pre, d);
+    if (lane == 0) pre_tot[wave] = pre;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int base = 0;
+      for (int w = 0; w < kWaves; ++w) base += pre_tot[w];
+      block_base = base;
+      if ((int)((first - t0) / kEmitTiles) == blk.tensor_blocks - 1) a.out_counts[j] = base + total;
     }
   }
   if (total == 0) return;
@@ -1362,23 +1381,25 @@ __global__ __launch_bounds__(kFlatThreads) void scatter_regions_kernel(float* de
   }
 }
 
-// Receive side without float atomics, for payloads whose regions ascend
-// (DGC_FLAG_SORTED_OUTPUT): workers are added in the order given, so the result is
-// that of the plain definition, bit for bit, in one launch.
+// Receive side without float atomics: workers are added in the order given, so the
+// result is that of the plain definition, bit for bit, in one launch.
 //
-// A workgroup owns a range of one tensor's elements.  One wavefront per payload finds
-// the payload's pairs inside the range (both ends at once: half the lanes probe for
-// each, 32 probes per round).  Every thread then takes a few of the pairs into
-// registers and marks their indices in an LDS bitmap of the range; a prefix sum over the
-// bitmap numbers the distinct indices, which gives every index a slot in an LDS
-// accumulator.  The slots start from dense[idx], the payloads are added one after the
-// other with a barrier between them (inside one payload the indices are distinct), and
-// the sums are stored.  Every index belongs to one workgroup, so plain loads and stores
-// do.  (Float atomics complete at about 20 G/s on this part wherever they are executed,
-// plain scattered stores at 80 G/s.)
+// A workgroup owns a range of one tensor's elements that consists of whole parts of emit
+// workgroups; in every payload's region those parts follow each other in index order
+// (inside a part the order is free), so "index below the range's end" is monotone along
+// a region and the payload's pairs inside the range are found by search: one wavefront
+// per payload, both ends at once (half the lanes probe for each, 32 probes per round).
+// Every thread then takes a few of the pairs into registers and marks their indices in
+// an LDS bitmap of the range; a prefix sum over the bitmap numbers the distinct
+// indices, which gives every index a slot in an LDS accumulator.  The slots start from
+// dense[idx], the payloads are added one after the other with a barrier between them
+// (inside one payload the indices are distinct), and the sums are stored.  Every index
+// belongs to one workgroup, so plain loads and stores do.  (Float atomics complete at
+// about 20 G/s on this part wherever they are executed, plain scattered stores at 80 G/s.)
 //
-// Positions [lo, hi) of the sorted list L[0, m) whose values lie in [xa, xb); every lane
-// of the wavefront takes part and gets the same answer.
+// Positions [lo, hi) of the list L[0, m) whose values lie in [xa, xb), for a list in which
+// "value < xa" and "value < xb" are monotone; every lane of the wavefront takes part and
+// gets the same answer.
 __device__ __forceinline__ void wave_equal_range(const int32_t* __restrict__ L, int m, int32_t xa, int32_t xb,
                                                  int lane, int& out_lo, int& out_hi) {
   const int half = lane >> 5;  // 0: lower bound of xa, 1: lower bound of xb
@@ -1533,46 +1554,94 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
     for (int k = 0; k < kPerThread; ++k)
       if (id[k] >= 0) dense[blk.begin + rel[k]] = sh.acc[id[k]];
   } else {
-    // More pairs than the accumulator holds (a dense warm-up step): every pair looks for
-    // its index in the other payloads by bisection straight on their arrays; the pair of
-    // the lowest payload that holds an index adds all of them up in order.  Slow, exact,
-    // and not the case this kernel is chosen for.
-    for (int q = tid; q < total; q += kMergeThreads) {
-      int w = 0, e = num_payloads;
-      while (e - w > 1) {
-        const int mid = (w + e) >> 1;
-        if (sh.begin[mid] <= q) w = mid;
+    // More pairs than a thread's registers and the accumulator hold (many workers, or a
+    // density above what this kernel is chosen for): the same steps with the pairs read
+    // from the payloads' arrays each time, the distinct indices taken kMergeCap at a time.
+    auto pair_of = [&](int q, int& w, int64_t& src) {
+      int lo_w = 0, e = num_payloads;  // largest w with begin[w] <= q
+      while (e - lo_w > 1) {
+        const int mid = (lo_w + e) >> 1;
+        if (sh.begin[mid] <= q) lo_w = mid;
         else e = mid;
       }
-      const int64_t src = sh.slot[w] + (q - sh.begin[w]);
-      const int32_t i = p.idx[w][src];
-      if (i < blk.begin || i >= blk.end) continue;
-      bool owner = true;
-      for (int v = 0; v < w && owner; ++v) {
-        const int32_t* L = p.idx[v] + sh.slot[v];
-        int b = 0, en = sh.begin[v + 1] - sh.begin[v];
-        const int len = en;
-        while (b < en) {
-          const int mid = (b + en) >> 1;
-          if (L[mid] < i) b = mid + 1;
-          else en = mid;
-        }
-        if (b < len && L[b] == i) owner = false;
+      w = lo_w;
+      src = sh.slot[w] + (q - sh.begin[w]);
+    };
+    auto slot_of = [&](int64_t r) {  // number of the distinct index r among those of the range
+      const uint32_t word = sh.bitmap[r >> 5];
+      return (int)(sh.prefix[r >> 5] + (uint32_t)__popc(word & ((1u << (r & 31)) - 1u)));
+    };
+    for (int q = tid; q < total; q += kMergeThreads) {
+      int w;
+      int64_t src;
+      pair_of(q, w, src);
+      const int64_t r = (int64_t)p.idx[w][src] - blk.begin;
+      if (r >= 0 && r < length) atomicOr(&sh.bitmap[r >> 5], 1u << (r & 31));
+    }
+    __syncthreads();
+    int distinct;
+    {
+      uint32_t mine = 0, c[kWordsPerThread];
+#pragma unroll
+      for (int k = 0; k < kWordsPerThread; ++k) {
+        c[k] = (uint32_t)__popc(sh.bitmap[tid * kWordsPerThread + k]);
+        mine += c[k];
       }
-      if (!owner) continue;
-      float d = dense[i] + (scaled ? scale * p.val[w][src] : p.val[w][src]);
-      for (int v = w + 1; v < num_payloads; ++v) {
-        const int32_t* L = p.idx[v] + sh.slot[v];
-        int b = 0, en = sh.begin[v + 1] - sh.begin[v];
-        const int len = en;
-        while (b < en) {
-          const int mid = (b + en) >> 1;
-          if (L[mid] < i) b = mid + 1;
-          else en = mid;
-        }
-        if (b < len && L[b] == i) d = d + (scaled ? scale * p.val[v][sh.slot[v] + b] : p.val[v][sh.slot[v] + b]);
+      uint32_t incl = mine;
+      for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t t = __shfl_up(incl, d);
+        if (lane >= d) incl += t;
       }
-      dense[i] = d;
+      if (lane == 63) sh.wave_sums[wave] = incl;
+      __syncthreads();
+      uint32_t run = incl - mine, all = 0;
+      for (int v = 0; v < kMergeWaves; ++v) {
+        if (v < wave) run += sh.wave_sums[v];
+        all += sh.wave_sums[v];
+      }
+      distinct = (int)all;
+#pragma unroll
+      for (int k = 0; k < kWordsPerThread; ++k) {
+        sh.prefix[tid * kWordsPerThread + k] = run;
+        run += c[k];
+      }
+    }
+    __syncthreads();
+    for (int first_slot = 0; first_slot < distinct; first_slot += kMergeCap) {
+      for (int q = tid; q < total; q += kMergeThreads) {
+        int w;
+        int64_t src;
+        pair_of(q, w, src);
+        const int64_t r = (int64_t)p.idx[w][src] - blk.begin;
+        if (r < 0 || r >= length) continue;
+        const int id = slot_of(r) - first_slot;
+        if (id >= 0 && id < kMergeCap) sh.acc[id] = dense[blk.begin + r];
+      }
+      __syncthreads();
+      for (int w = 0; w < num_payloads; ++w) {  // payloads in the order given
+        const int len = sh.begin[w + 1] - sh.begin[w];
+        for (int q = tid; q < len; q += kMergeThreads) {
+          const int64_t src = sh.slot[w] + q;
+          const int64_t r = (int64_t)p.idx[w][src] - blk.begin;
+          if (r < 0 || r >= length) continue;
+          const int id = slot_of(r) - first_slot;
+          if (id >= 0 && id < kMergeCap) {
+            const float x = scaled ? scale * p.val[w][src] : p.val[w][src];
+            sh.acc[id] = sh.acc[id] + x;
+          }
+        }
+        __syncthreads();
+      }
+      for (int q = tid; q < total; q += kMergeThreads) {
+        int w;
+        int64_t src;
+        pair_of(q, w, src);
+        const int64_t r = (int64_t)p.idx[w][src] - blk.begin;
+        if (r < 0 || r >= length) continue;
+        const int id = slot_of(r) - first_slot;
+        if (id >= 0 && id < kMergeCap) dense[blk.begin + r] = sh.acc[id];
+      }
+      __syncthreads();
     }
   }
 }

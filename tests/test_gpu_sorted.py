@@ -1,6 +1,7 @@
 """GPU parity of the sorted payload (DGC_FLAG_SORTED_OUTPUT): every tensor's region
 must hold the oracle's pairs in the oracle's order (ascending index), without any
-sorting on the test's side, and a full region must keep the lowest indices.
+sorting on the test's side, and a full region must keep the lowest indices.  Also the
+receive side that merges payloads by element range, with and without the flag.
 Run with `-m gpu` on an MI355X."""
 
 import numpy as np
@@ -65,11 +66,12 @@ def test_sorted_with_rethreshold():
     p.close()
 
 
-def test_sorted_payload_is_identical_on_every_run():
+@pytest.mark.parametrize("flags", [SORTED, 0])
+def test_payload_is_identical_on_every_run(flags):
     import torch
     gs = S.ragged_set(15, tensors=16, max_numel=300000)
     kw = dict(layout_density=0.02, momentum=0.9, density=0.01, seed=5, sample_min=256, sample_max=2048,
-              flags=SORTED)
+              flags=flags)
     g = [S.gradient(gs, 28, 0, it) for it in range(3)]
     runs = []
     for rep in range(3):
@@ -107,11 +109,12 @@ def test_sorted_resnet50_set_and_high_density_speech():
     p.close()
 
 
-def _merge_case(gs, N, density, seed, scales=None, preset=None, **extra):
-    """N sorted payloads from correlated streams, accumulated by a handle that carries the
-    sorted flag (LDS merge, workers in order): bit-exact against the oracle's ordered sum."""
+def _merge_case(gs, N, density, seed, scales=None, preset=None, flags=SORTED, **extra):
+    """N payloads from correlated streams, accumulated at a density where the receive side
+    merges by element range in LDS, workers in order: bit-exact against the oracle's
+    ordered sum, whether the regions ascend throughout or only part by part."""
     import torch
-    kw = dict(momentum=0.9, density=density, seed=seed, num_workers=N, flags=SORTED, **extra)
+    kw = dict(momentum=0.9, density=density, seed=seed, num_workers=N, flags=flags, **extra)
     shared = S.gradient(gs, seed, 999, 0, scales)
     pairs, payloads = [], []
     for w in range(N):
@@ -143,18 +146,20 @@ def _merge_case(gs, N, density, seed, scales=None, preset=None, **extra):
     return sum(i.size for i, _ in payloads), overlap
 
 
+@pytest.mark.parametrize("flags", [SORTED, 0, B.DGC_FLAG_DETERMINISTIC_ACCUMULATE])
 @pytest.mark.parametrize("N,density,preset", [(1, 0.001, False), (4, 0.002, True), (16, 0.001, False),
                                                (40, 0.001, True), (48, 0.005, False)])
-def test_sorted_payloads_are_merged_in_worker_order(N, density, preset):
+def test_payloads_are_merged_in_worker_order(N, density, preset, flags):
     gs = S.ragged_set(22, tensors=12, max_numel=400000)
-    total, overlap = _merge_case(gs, N, density, 70 + N, preset=preset, layout_density=max(density, 0.01) * 4,
-                                 sample_min=1024, sample_max=8192)
+    total, overlap = _merge_case(gs, N, density, 70 + N, preset=preset, flags=flags,
+                                 layout_density=max(density, 0.01) * 4, sample_min=1024, sample_max=8192)
     say(f"[merge] N={N} d={density}: {total} pairs, overlap first/last {overlap:.2f}")
 
 
-def test_sorted_sixteen_worker_merge_resnet50_shape():
+@pytest.mark.parametrize("flags", [SORTED, 0])
+def test_sixteen_worker_merge_resnet50_shape(flags):
     gs = S.resnet50_set()
-    total, overlap = _merge_case(gs, 16, 0.001, 61, scales=S.tensor_scales(gs, 61))
+    total, overlap = _merge_case(gs, 16, 0.001, 61, scales=S.tensor_scales(gs, 61), flags=flags)
     say(f"[merge] resnet50 N=16: {total} pairs, overlap {overlap:.2f}")
     assert 0.15 < overlap < 0.5
 
