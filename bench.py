@@ -6,7 +6,8 @@ paper-shaped gradient set: dgc_compress of the worker's gradient (clipping norm
 when the configuration clips, sampled thresholds, streaming update + mask,
 emit = extraction + residual + factor masking), then
 dgc_decompress_accumulate_regions of N payloads (the fresh one and N - 1 from
-other seeded, correlated streams) into the dense aggregate, then
+other seeded, correlated streams) into the dense aggregate (merged by element
+range on chip, workers in order, no float atomics), then
 dgc_dense_clear_regions to return the aggregate to zero.  Four workers' states
 (g, u, v) rotate so that no step finds its operands in the 256 MB last-level
 cache.  Inputs are generated on the host once, seeded, and are resident in HBM
@@ -55,7 +56,7 @@ WORKLOADS = {
 # device copy of n floats): 308.3 MB read + 207.9 MB written.  The counters cannot be
 # read from inside this process; profiles/stream_kernel_resnet50_hbm_traffic.txt holds
 # the run this number comes from.
-MEASURED_TRAFFIC_BYTES = {"resnet50": 516171471}
+MEASURED_TRAFFIC_BYTES = {"resnet50": 516175108}
 
 
 def parse_args():
