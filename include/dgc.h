@@ -219,13 +219,14 @@ dgc_status dgc_decompress_accumulate(dgc_handle* h, float* dense, int64_t n, int
  *   workspace    device workspace of this handle (holds the layout copy)
  * The regions must be as dgc_compress of this library writes them (the parts of
  * consecutive blocks of 32768 elements of a tensor follow each other in index order; the
- * order inside a part is free): at a density of at most 0.5 % the payloads are merged by
- * element range in on-chip memory, workers added in the order given, in one launch and
- * without float atomics, which gives the result of the plain definition bit for bit.  A
- * region laid out otherwise then gives wrong sums (never an access out of bounds); for
- * arbitrary pair lists there is dgc_decompress_accumulate.  At higher densities the
- * additions are float atomics in arbitrary order, or one launch per worker with
- * DGC_FLAG_DETERMINISTIC_ACCUMULATE.
+ * order inside a part is free, the indices of one payload are distinct).  The payloads are
+ * merged by element range in on-chip memory, workers added in the order given, without
+ * float atomics, which gives the result of the plain definition bit for bit at every
+ * density: up to 0.5 % a workgroup touches only the elements that occur in a range of up to
+ * 131072; above (the warm-up densities of Section 4) it keeps one part's whole range of
+ * `dense` on chip, after a launch that finds every payload's pairs of every part.  A
+ * region laid out otherwise gives wrong sums (never an access out of bounds); for
+ * arbitrary pair lists there is dgc_decompress_accumulate.
  */
 dgc_status dgc_decompress_accumulate_regions(dgc_handle* h, float* dense, int32_t num_payloads,
                                              const int32_t* const* idx_ptrs_host,
@@ -237,7 +238,10 @@ dgc_status dgc_decompress_accumulate_regions(dgc_handle* h, float* dense, int32_
 /*
  * dense[idx] = 0 for every pair of the given region-layout payloads: returns a
  * dense aggregate to all-zero after it has been consumed at the cost of the
- * payload size instead of a full fill.  Arguments as above.
+ * payload size instead of a full fill.  Arguments as above.  Above a density of 0.5 %
+ * the regions must be as dgc_compress writes them (see above): the indices of a part are
+ * marked in a bitmap on chip and every 64-byte sector with a marked element is written
+ * once, whole (its other elements are read and written back unchanged).
  */
 dgc_status dgc_dense_clear_regions(dgc_handle* h, float* dense, int32_t num_payloads,
                                    const int32_t* const* idx_ptrs_host,
@@ -253,7 +257,7 @@ dgc_status dgc_dense_clear_regions(dgc_handle* h, float* dense, int32_t num_payl
  * dgc_decompress_accumulate / dgc_decompress_accumulate_regions, theta (device, n floats) in
  * place of dense.  Each pair is applied on its own (theta - lr*v1 - lr*v2 rather than
  * theta - lr*(v1 + v2)); with DGC_FLAG_DETERMINISTIC_ACCUMULATE workers are applied in order,
- * and so they are by dgc_sparse_sgd_apply_regions at a density of at most 0.5 % (see
+ * and so they always are by dgc_sparse_sgd_apply_regions (see
  * dgc_decompress_accumulate_regions).
  */
 dgc_status dgc_sparse_sgd_apply(dgc_handle* h, float* theta, int64_t n, float learning_rate,

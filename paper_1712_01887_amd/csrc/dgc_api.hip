@@ -26,7 +26,8 @@ struct dgc_handle {
   std::vector<uint32_t> tile_info;   // ceil(n / kWaveTile)
   std::vector<float> tile_thr_init;  // ceil(n / kWaveTile): NaN where a tile is not wholly inside one tensor
   std::vector<EmitBlock> emit_blocks;  // work list of the emit pass
-  std::vector<MergeBlock> merge_blocks;  // work list of the receive side for sorted payloads
+  std::vector<MergeBlock> merge_blocks;  // work list of the receive side: ranges of several emit parts
+  std::vector<MergeBlock> part_blocks;   // the same with one emit part per range (warm-up densities)
   WorkspaceLayout lay{};
   // what the bound workspace currently holds
   void* ws = nullptr;
@@ -134,6 +135,9 @@ void build_layout(dgc_handle* h) {
   l.refine_counters = off; off = align_up(off + sizeof(uint32_t) * kCounterStride * T);
   l.tile_count = off;   off = align_up(off + sizeof(uint32_t) * tiles);
   l.merge_blocks = off; off = align_up(off + sizeof(MergeBlock) * h->merge_blocks.size());
+  l.part_blocks = off;  off = align_up(off + sizeof(MergeBlock) * h->part_blocks.size());
+  // (first pair, pairs) of every payload inside every part, left by the search that precedes the part kernels
+  l.part_found = off;   off = align_up(off + 2 * sizeof(int32_t) * kMaxPayloads * h->part_blocks.size());
   // wire format: one block sum per kWireChunk pairs of every region (encoder, at most
   // n / kWireChunk + T) or per kWireChunk entries of every payload (decoder, an entry
   // stream of a set of n elements has at most n + (n >> 16) entries)
@@ -203,6 +207,10 @@ dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_
     if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.merge_blocks), h->merge_blocks.data(),
                                sizeof(MergeBlock) * h->merge_blocks.size(), hipMemcpyHostToDevice, stream),
                 "upload merge work list"))
+      return DGC_ERR_HIP;
+    if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.part_blocks), h->part_blocks.data(),
+                               sizeof(MergeBlock) * h->part_blocks.size(), hipMemcpyHostToDevice, stream),
+                "upload part work list"))
       return DGC_ERR_HIP;
     h->ws_static_valid = true;
   }
@@ -335,6 +343,13 @@ dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tenso
       if (end > h->offsets[t + 1]) end = h->offsets[t + 1];
       h->merge_blocks.push_back(MergeBlock{begin, end, t, 0});
       b = e;
+    }
+    for (const EmitBlock& eb : h->emit_blocks) {
+      int64_t begin = (int64_t)eb.first_tile * kWaveTile;
+      int64_t end = (int64_t)(eb.first_tile + kEmitTiles) * kWaveTile;
+      if (begin < h->offsets[eb.tensor]) begin = h->offsets[eb.tensor];
+      if (end > h->offsets[eb.tensor + 1]) end = h->offsets[eb.tensor + 1];
+      h->part_blocks.push_back(MergeBlock{begin, end, eb.tensor, 0});
     }
     h->ws_out_offsets.resize(num_tensors + 1);
     h->wire_first_block.resize(num_tensors + 1);
@@ -709,32 +724,32 @@ static dgc_status scatter_regions(dgc_handle* h, float* dense, int32_t num_paylo
   if (st != DGC_OK) return st;
   const int64_t* oo = at<int64_t>(workspace, h->lay.out_offsets);
   const int64_t widest = out_offsets_host[h->num_tensors];  // pairs a payload can hold
-  // At the densities the method runs at: merged by element range in LDS, workers in order, no
-  // atomics.  (At warm-up densities the pairs of a range outgrow LDS and the scattered
-  // kernels are the faster ones.)
-  if (!clear && h->cfg.density <= kMergeMaxDensity) {
+  // No atomics at any density, workers in order.  At the densities the method runs at, a
+  // workgroup merges the pairs of a range of up to 128 Ki elements in LDS and touches only
+  // the elements that occur; at warm-up densities a workgroup keeps one emit part's whole
+  // range of `dense` in LDS.
+  const bool few = h->cfg.density <= kMergeMaxDensity;
+  const MergeBlock* parts = at<MergeBlock>(workspace, h->lay.part_blocks);
+  const int32_t num_parts = (int32_t)h->part_blocks.size();
+  void* found = at<char>(workspace, h->lay.part_found);
+  if (clear) {
+    if (few) {
+      if (!hip_ok(launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, widest,
+                                         kScatterClear, 0.0f, nullptr, stream),
+                  "launch scatter kernel"))
+        return DGC_ERR_HIP;
+    } else if (!hip_ok(launch_clear_parts(dense, p, num_payloads, oo, parts, num_parts, found, stream),
+                       "launch clear kernel")) {
+      return DGC_ERR_HIP;
+    }
+  } else if (few) {
     if (!hip_ok(launch_merge_regions(dense, p, num_payloads, oo, at<MergeBlock>(workspace, h->lay.merge_blocks),
                                      (int32_t)h->merge_blocks.size(), sgd, scale, stream),
                 "launch merge kernel"))
       return DGC_ERR_HIP;
-    return DGC_OK;
-  }
-  if (clear) {
-    if (!hip_ok(launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, widest,
-                                       kScatterClear, 0.0f, nullptr, stream),
-                "launch scatter kernel"))
-      return DGC_ERR_HIP;
-  } else if (h->cfg.flags & DGC_FLAG_DETERMINISTIC_ACCUMULATE) {
-    for (int32_t w = 0; w < num_payloads; ++w)
-      if (!hip_ok(launch_scatter_regions(dense, h->n, p, w, 1, oo, h->num_tensors, widest,
-                                         sgd ? kScatterPlainSgd : kScatterPlainAdd, scale, nullptr, stream),
-                  "launch scatter kernel"))
-        return DGC_ERR_HIP;
-  } else {
-    if (!hip_ok(launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, widest,
-                                       sgd ? kScatterAtomicSgd : kScatterAtomicAdd, scale, nullptr, stream),
-                "launch scatter kernel"))
-      return DGC_ERR_HIP;
+  } else if (!hip_ok(launch_merge_parts(dense, p, num_payloads, oo, parts, num_parts, found, sgd, scale, stream),
+                     "launch merge kernel")) {
+    return DGC_ERR_HIP;
   }
   return DGC_OK;
 }

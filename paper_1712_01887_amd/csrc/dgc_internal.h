@@ -56,6 +56,14 @@ constexpr int kMergeMaxRange = 131072;   // elements per workgroup at most (one 
 constexpr int kMergeEmitBlocks = kMergeMaxRange / kEmitElements;  // emit workgroups' parts per range
 static_assert(kMergeCap % kMergeThreads == 0 && (kMergeMaxRange / 32) % kMergeThreads == 0, "dealt evenly to threads");
 
+// Receive side at warm-up densities: a workgroup owns one emit workgroup's part and keeps
+// the whole range of the dense vector in LDS.
+constexpr int kPartThreads = 1024;
+constexpr int kPartPer = 8;  // pairs a thread holds per round
+constexpr int kPartRound = kPartThreads * kPartPer;
+constexpr int kPartClearThreads = 256;
+static_assert(kEmitElements <= 65536 && kEmitElements % kPartThreads == 0 && (kEmitElements / 32) % kPartClearThreads == 0, "dealt evenly");
+
 // Wire format (32-bit values + 16-bit zero-run lengths): pairs or entries handled by one
 // workgroup, kWirePerThread consecutive ones per thread.
 constexpr int kWireThreads = 256;
@@ -76,6 +84,7 @@ constexpr int kNormThreads = 256;
 constexpr int kNormMaxBlocks = 512;
 
 constexpr int kMaxPayloads = 64;
+static_assert(kMaxPayloads <= 32768, "a payload's number is packed above a 16-bit index");
 
 // ---- device-resident state (start of the workspace) ------------------------
 struct DeviceState {
@@ -99,7 +108,7 @@ struct TensorPlan {
 
 struct WorkspaceLayout {
   size_t state, partials, offsets, out_offsets, plans, thr, tile_info, tile_thr, emit_blocks, refine_counters,
-      tile_count, merge_blocks, wire_first_block, wire_sums, mask, total;
+      tile_count, merge_blocks, part_blocks, part_found, wire_first_block, wire_sums, mask, total;
 };
 
 struct SelectArgs {
@@ -259,6 +268,11 @@ hipError_t launch_scatter_regions(float* dense, int64_t n, const RegionPayloads&
 hipError_t launch_merge_regions(float* dense, const RegionPayloads& p, int32_t num, const int64_t* out_offsets_dev,
                                 const MergeBlock* blocks, int32_t num_blocks, bool scaled, float scale,
                                 hipStream_t stream);
+hipError_t launch_merge_parts(float* dense, const RegionPayloads& p, int32_t num, const int64_t* out_offsets_dev,
+                              const MergeBlock* parts, int32_t num_parts, void* found, bool scaled, float scale,
+                              hipStream_t stream);
+hipError_t launch_clear_parts(float* dense, const RegionPayloads& p, int32_t num, const int64_t* out_offsets_dev,
+                              const MergeBlock* parts, int32_t num_parts, void* found, hipStream_t stream);
 hipError_t launch_encode(const EncodeArgs& a, int64_t widest_region, int32_t total_blocks, hipStream_t stream);
 hipError_t launch_decode(const DecodeArgs& a, int32_t first, int32_t num, bool atomic, hipStream_t stream);
 

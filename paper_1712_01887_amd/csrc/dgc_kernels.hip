@@ -1427,13 +1427,59 @@ __device__ __forceinline__ void wave_equal_range(const int32_t* __restrict__ L, 
   out_hi = __shfl(lo, 32);
 }
 
+// Finds every payload's pairs inside [blk.begin, blk.end) and fills begin[], idx_at[] and
+// val_at[] (in LDS: a payload's pointers looked up per pair in the kernel's argument block
+// would put a load from memory in front of every pair load).
+template <typename Shared>
+__device__ __forceinline__ int locate_pairs(Shared& sh, const RegionPayloads& p, int32_t num_payloads, int64_t region,
+                                            int64_t cap, const MergeBlock& blk, int tid, int waves) {
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  for (int w = wave; w < num_payloads; w += waves) {
+    int64_t cnt = p.counts[w][blk.tensor];
+    if (cnt > cap) cnt = cap;
+    if (cnt < 0) cnt = 0;
+    int lo, hi;
+    wave_equal_range(p.idx[w] + region, (int)cnt, (int32_t)blk.begin, (int32_t)blk.end, lane, lo, hi);
+    if (lane == 0) {
+      sh.idx_at[w] = p.idx[w] + region + lo;
+      sh.val_at[w] = p.val[w] ? p.val[w] + region + lo : nullptr;
+      sh.begin[w + 1] = hi - lo;  // length for now
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    sh.begin[0] = 0;
+    for (int w = 0; w < num_payloads; ++w) {
+      const int len = sh.begin[w + 1];
+      sh.begin[w + 1] = run + len;
+      run += len;
+    }
+  }
+  __syncthreads();
+  return sh.begin[num_payloads];
+}
+
+// Largest w with begin[w] <= q.
+__device__ __forceinline__ int payload_of(const int32_t* begin, int num_payloads, int q) {
+  int w = 0, e = num_payloads;
+  while (e - w > 1) {
+    const int mid = (w + e) >> 1;
+    if (begin[mid] <= q) w = mid;
+    else e = mid;
+  }
+  return w;
+}
+
 struct MergeShared {
   uint32_t bitmap[kMergeMaxRange / 32];
   uint32_t prefix[kMergeMaxRange / 32];  // distinct indices before each bitmap word
   float acc[kMergeCap];
   uint32_t wave_sums[kMergeWaves];
   int32_t begin[kMaxPayloads + 1];  // number of pairs of the payloads before w inside the range
-  int64_t slot[kMaxPayloads];       // where payload w's pairs inside the range start in its arrays
+  const int32_t* idx_at[kMaxPayloads];  // payload w's first pair inside the range
+  const float* val_at[kMaxPayloads];
 };
 
 // `scale` multiplies every value first (1 for the plain sum; -learning rate for the SGD
@@ -1456,29 +1502,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
   const int32_t length = (int32_t)(blk.end - blk.begin);  // <= kMergeMaxRange
 #pragma unroll
   for (int k = 0; k < kWordsPerThread; ++k) sh.bitmap[tid * kWordsPerThread + k] = 0;
-  for (int w = wave; w < num_payloads; w += kMergeWaves) {
-    int64_t cnt = p.counts[w][j];
-    if (cnt > cap) cnt = cap;
-    if (cnt < 0) cnt = 0;
-    int lo, hi;
-    wave_equal_range(p.idx[w] + region, (int)cnt, (int32_t)blk.begin, (int32_t)blk.end, lane, lo, hi);
-    if (lane == 0) {
-      sh.slot[w] = region + lo;
-      sh.begin[w + 1] = hi - lo;  // length for now
-    }
-  }
-  __syncthreads();
-  if (tid == 0) {
-    int run = 0;
-    sh.begin[0] = 0;
-    for (int w = 0; w < num_payloads; ++w) {
-      const int len = sh.begin[w + 1];
-      sh.begin[w + 1] = run + len;
-      run += len;
-    }
-  }
-  __syncthreads();
-  const int total = sh.begin[num_payloads];
+  const int total = locate_pairs(sh, p, num_payloads, region, cap, blk, tid, kMergeWaves);
   if (total == 0) return;
 
   if (total <= kMergeCap) {
@@ -1499,9 +1523,10 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
           if (sh.begin[mid] <= q) w = mid;
           else e = mid;
         }
-        const int64_t src = sh.slot[w] + (q - sh.begin[w]);
-        const int64_t r = (int64_t)p.idx[w][src] - blk.begin;
-        x[k] = scaled ? scale * p.val[w][src] : p.val[w][src];
+        const int src = q - sh.begin[w];
+        const int64_t r = (int64_t)sh.idx_at[w][src] - blk.begin;
+        const float value = sh.val_at[w][src];
+        x[k] = scaled ? scale * value : value;
         pw[k] = w;
         if (r >= 0 && r < length) {  // anything else can only come from a region that does not ascend
           rel[k] = (int32_t)r;
@@ -1557,7 +1582,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
     // More pairs than a thread's registers and the accumulator hold (many workers, or a
     // density above what this kernel is chosen for): the same steps with the pairs read
     // from the payloads' arrays each time, the distinct indices taken kMergeCap at a time.
-    auto pair_of = [&](int q, int& w, int64_t& src) {
+    auto pair_of = [&](int q, int& w, int& src) {
       int lo_w = 0, e = num_payloads;  // largest w with begin[w] <= q
       while (e - lo_w > 1) {
         const int mid = (lo_w + e) >> 1;
@@ -1565,7 +1590,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
         else e = mid;
       }
       w = lo_w;
-      src = sh.slot[w] + (q - sh.begin[w]);
+      src = q - sh.begin[w];
     };
     auto slot_of = [&](int64_t r) {  // number of the distinct index r among those of the range
       const uint32_t word = sh.bitmap[r >> 5];
@@ -1573,9 +1598,9 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
     };
     for (int q = tid; q < total; q += kMergeThreads) {
       int w;
-      int64_t src;
+      int src;
       pair_of(q, w, src);
-      const int64_t r = (int64_t)p.idx[w][src] - blk.begin;
+      const int64_t r = (int64_t)sh.idx_at[w][src] - blk.begin;
       if (r >= 0 && r < length) atomicOr(&sh.bitmap[r >> 5], 1u << (r & 31));
     }
     __syncthreads();
@@ -1610,9 +1635,9 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
     for (int first_slot = 0; first_slot < distinct; first_slot += kMergeCap) {
       for (int q = tid; q < total; q += kMergeThreads) {
         int w;
-        int64_t src;
+        int src;
         pair_of(q, w, src);
-        const int64_t r = (int64_t)p.idx[w][src] - blk.begin;
+        const int64_t r = (int64_t)sh.idx_at[w][src] - blk.begin;
         if (r < 0 || r >= length) continue;
         const int id = slot_of(r) - first_slot;
         if (id >= 0 && id < kMergeCap) sh.acc[id] = dense[blk.begin + r];
@@ -1621,12 +1646,12 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
       for (int w = 0; w < num_payloads; ++w) {  // payloads in the order given
         const int len = sh.begin[w + 1] - sh.begin[w];
         for (int q = tid; q < len; q += kMergeThreads) {
-          const int64_t src = sh.slot[w] + q;
-          const int64_t r = (int64_t)p.idx[w][src] - blk.begin;
+          const int64_t r = (int64_t)sh.idx_at[w][q] - blk.begin;
           if (r < 0 || r >= length) continue;
           const int id = slot_of(r) - first_slot;
           if (id >= 0 && id < kMergeCap) {
-            const float x = scaled ? scale * p.val[w][src] : p.val[w][src];
+            const float value = sh.val_at[w][q];
+            const float x = scaled ? scale * value : value;
             sh.acc[id] = sh.acc[id] + x;
           }
         }
@@ -1634,14 +1659,317 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
       }
       for (int q = tid; q < total; q += kMergeThreads) {
         int w;
-        int64_t src;
+        int src;
         pair_of(q, w, src);
-        const int64_t r = (int64_t)p.idx[w][src] - blk.begin;
+        const int64_t r = (int64_t)sh.idx_at[w][src] - blk.begin;
         if (r < 0 || r >= length) continue;
         const int id = slot_of(r) - first_slot;
         if (id >= 0 && id < kMergeCap) dense[blk.begin + r] = sh.acc[id];
       }
       __syncthreads();
+    }
+  }
+}
+
+// Receive side at warm-up densities (paper: Section 4, warm-up training -- 25 % down to
+// 0.4 % of the elements are sent during the first epochs): with millions of pairs per
+// payload, adding them one by one to `dense` costs a scattered read-modify-write each.
+// Here a workgroup owns one emit workgroup's part of a tensor (at most kEmitElements
+// elements, contiguous in index order in every payload's region, see above), keeps the
+// whole range of `dense` in LDS, adds the payloads' pairs to it in the order of the
+// payloads, and writes the range back: `dense` is read and written once, coalesced,
+// the pairs are read once, coalesced, and the sums are those of the plain definition,
+// bit for bit.
+//
+// The pairs are taken a round at a time: up to kPartRound consecutive pairs of one
+// payload, kPartPer per thread, with the loads of the next two rounds in flight.  Pairs
+// of one payload have distinct indices and are added without synchronisation; a
+// barrier separates one payload from the next.
+// At these densities a region holds up to millions of pairs and the search for a part's
+// pairs is four rounds of dependent loads: with one workgroup per compute unit (the
+// accumulator fills LDS) nothing else would run meanwhile.  So the searches of all parts
+// and payloads run first, one wavefront each, spread over the chip, and leave (first
+// pair, number of pairs) in a table.
+__global__ __launch_bounds__(kFlatThreads) void locate_parts_kernel(RegionPayloads p, int32_t num_payloads,
+                                                                    const int64_t* __restrict__ out_offsets,
+                                                                    const MergeBlock* __restrict__ blocks,
+                                                                    int32_t num_blocks, int2* __restrict__ found) {
+  const int lane = threadIdx.x & 63;
+  const int64_t id = (int64_t)blockIdx.x * (kFlatThreads / 64) + (threadIdx.x >> 6);
+  if (id >= (int64_t)num_blocks * num_payloads) return;
+  const int b = (int)(id / num_payloads);
+  const int w = (int)(id % num_payloads);
+  const MergeBlock blk = blocks[b];
+  const int64_t region = out_offsets[blk.tensor];
+  const int64_t cap = out_offsets[blk.tensor + 1] - region;
+  int64_t cnt = p.counts[w][blk.tensor];
+  if (cnt > cap) cnt = cap;
+  if (cnt < 0) cnt = 0;
+  int lo, hi;
+  wave_equal_range(p.idx[w] + region, (int)cnt, (int32_t)blk.begin, (int32_t)blk.end, lane, lo, hi);
+  if (lane == 0) found[id] = make_int2(lo, hi - lo);
+}
+
+// Fills begin[], idx_at[] and val_at[] from that table; returns the number of pairs.
+template <typename Shared>
+__device__ __forceinline__ int located_pairs(Shared& sh, const RegionPayloads& p, int32_t num_payloads, int64_t region,
+                                             const int2* __restrict__ found, int tid) {
+  if (tid < num_payloads) {
+    const int2 f = found[(int64_t)blockIdx.x * num_payloads + tid];
+    sh.idx_at[tid] = p.idx[tid] + region + f.x;
+    sh.val_at[tid] = p.val[tid] ? p.val[tid] + region + f.x : nullptr;
+    sh.begin[tid + 1] = f.y;  // length for now
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    sh.begin[0] = 0;
+    for (int w = 0; w < num_payloads; ++w) {
+      const int len = sh.begin[w + 1];
+      sh.begin[w + 1] = run + len;
+      run += len;
+    }
+  }
+  __syncthreads();
+  return sh.begin[num_payloads];
+}
+
+struct PartShared {
+  float acc[kEmitElements];
+  int32_t begin[kMaxPayloads + 1];  // number of pairs of the payloads before w inside the range
+  const int32_t* idx_at[kMaxPayloads];  // payload w's first pair inside the range
+  const float* val_at[kMaxPayloads];
+};
+
+__global__ __launch_bounds__(kPartThreads) void merge_parts_kernel(float* __restrict__ dense, RegionPayloads p,
+                                                                   int32_t num_payloads,
+                                                                   const int64_t* __restrict__ out_offsets,
+                                                                   const MergeBlock* __restrict__ blocks,
+                                                                   const int2* __restrict__ found, float scale,
+                                                                   int32_t scaled) {
+  constexpr int kElems = kEmitElements / kPartThreads;
+  __shared__ PartShared sh;
+  const int tid = threadIdx.x;
+  const MergeBlock blk = blocks[blockIdx.x];
+  const int j = blk.tensor;
+  const int64_t region = out_offsets[j];
+  const int64_t cap = out_offsets[j + 1] - region;
+  const int32_t length = (int32_t)(blk.end - blk.begin);  // <= kEmitElements
+  float* __restrict__ range = dense + blk.begin;
+  // the range of `dense` is on its way while the pairs are located
+  float d[kElems];
+#pragma unroll
+  for (int k = 0; k < kElems; ++k) {
+    const int e = tid + k * kPartThreads;
+    d[k] = e < length ? __builtin_nontemporal_load(range + e) : 0.0f;
+  }
+  const int total = located_pairs(sh, p, num_payloads, region, found, tid);
+  if (total == 0) return;
+#pragma unroll
+  for (int k = 0; k < kElems; ++k) sh.acc[tid + k * kPartThreads] = d[k];
+
+  if (total <= kPartRound) {
+    // Few pairs (many payloads of a low density): all of them at once, whatever payload they
+    // belong to, so that their loads are one wait; then payload after payload from registers.
+    int32_t at[kPartPer];  // payload << 16 | index relative to the range; -1: none
+    float x[kPartPer];
+#pragma unroll
+    for (int k = 0; k < kPartPer; ++k) {
+      const int q = tid + k * kPartThreads;
+      at[k] = -1;
+      x[k] = 0.0f;
+      if (q < total) {
+        const int w = payload_of(sh.begin, num_payloads, q);
+        const int src = q - sh.begin[w];
+        const int64_t r = (int64_t)__builtin_nontemporal_load(sh.idx_at[w] + src) - blk.begin;
+        const float value = __builtin_nontemporal_load(sh.val_at[w] + src);
+        x[k] = scaled ? scale * value : value;
+        if (r >= 0 && r < length) at[k] = (int32_t)r | (w << 16);  // anything else: a foreign region
+      }
+    }
+    __syncthreads();  // the accumulator is filled
+    for (int w = 0; w < num_payloads; ++w) {  // payloads in the order given
+      if (sh.begin[w + 1] == sh.begin[w]) continue;
+      float sum[kPartPer];
+#pragma unroll
+      for (int k = 0; k < kPartPer; ++k)
+        sum[k] = (at[k] >= 0 && (at[k] >> 16) == w) ? sh.acc[at[k] & 0xFFFF] + x[k] : 0.0f;
+#pragma unroll
+      for (int k = 0; k < kPartPer; ++k)
+        if (at[k] >= 0 && (at[k] >> 16) == w) sh.acc[at[k] & 0xFFFF] = sum[k];
+      __syncthreads();
+    }
+  } else {
+  // A round: up to kPartRound consecutive pairs of one payload.  Two rounds are on their way
+  // while a third is added, and nothing in fetch() depends on the loaded words.
+  struct Loaded {
+    int32_t idx[kPartPer];
+    float x[kPartPer];
+    int w;  // payload
+    int n;  // pairs of the round; 0: there is no further round
+  };
+  int cursor_w = 0, cursor_at = 0;  // next pair to fetch: payload, position among its pairs inside the range
+  auto fetch = [&](Loaded& L) {
+    L.n = 0;
+    L.w = 0;
+    while (cursor_w < num_payloads) {
+      const int len = sh.begin[cursor_w + 1] - sh.begin[cursor_w];
+      if (cursor_at < len) break;
+      ++cursor_w;
+      cursor_at = 0;
+    }
+    if (cursor_w >= num_payloads) return;
+    const int left = sh.begin[cursor_w + 1] - sh.begin[cursor_w] - cursor_at;
+    L.w = cursor_w;
+    L.n = left < kPartRound ? left : kPartRound;
+    const int32_t* __restrict__ ip = sh.idx_at[cursor_w] + cursor_at;
+    const float* __restrict__ vp = sh.val_at[cursor_w] + cursor_at;
+    cursor_at += L.n;
+#pragma unroll
+    for (int k = 0; k < kPartPer; ++k) {
+      const int q = tid + k * kPartThreads;
+      L.idx[k] = 0;
+      L.x[k] = 0.0f;
+      if (q < L.n) {
+        L.idx[k] = __builtin_nontemporal_load(ip + q);
+        L.x[k] = __builtin_nontemporal_load(vp + q);
+      }
+    }
+  };
+  int last_w = -1;
+  // Adds the round in L and refills L with the next round to fetch.
+  auto add = [&](Loaded& L) {
+    int32_t at[kPartPer];  // index relative to the range; -1: none
+    float x[kPartPer];
+#pragma unroll
+    for (int k = 0; k < kPartPer; ++k) {
+      const int64_t r = (int64_t)L.idx[k] - blk.begin;
+      // an index outside the range can only come from a foreign region
+      at[k] = (tid + k * kPartThreads < L.n && r >= 0 && r < length) ? (int32_t)r : -1;
+      x[k] = scaled ? scale * L.x[k] : L.x[k];
+    }
+    const int w = L.w;
+    fetch(L);
+    if (w != last_w) __syncthreads();  // the payload before is added (the first time: the accumulator is filled)
+    last_w = w;
+    // the indices of one payload are distinct: all reads, then all writes, no barrier between its rounds
+    float sum[kPartPer];
+#pragma unroll
+    for (int k = 0; k < kPartPer; ++k) sum[k] = at[k] >= 0 ? sh.acc[at[k]] + x[k] : 0.0f;
+#pragma unroll
+    for (int k = 0; k < kPartPer; ++k)
+      if (at[k] >= 0) sh.acc[at[k]] = sum[k];
+  };
+  Loaded A, B;
+  fetch(A);
+  fetch(B);
+  for (;;) {
+    if (A.n == 0) break;
+    add(A);
+    if (B.n == 0) break;
+    add(B);
+  }
+  __syncthreads();
+  }
+#pragma unroll
+  for (int k = 0; k < kElems; ++k) {
+    const int e = tid + k * kPartThreads;
+    if (e < length) __builtin_nontemporal_store(sh.acc[e], range + e);
+  }
+}
+
+// The sparse clear at the same densities: the indices of all payloads inside the part
+// are marked in an LDS bitmap and zeros stored where a bit is set, every element once.
+struct PartClearShared {
+  uint32_t bitmap[kEmitElements / 32];
+  int32_t begin[kMaxPayloads + 1];
+  const int32_t* idx_at[kMaxPayloads];
+  const float* val_at[kMaxPayloads];
+};
+
+__global__ __launch_bounds__(kPartClearThreads) void clear_parts_kernel(float* __restrict__ dense, RegionPayloads p,
+                                                                        int32_t num_payloads,
+                                                                        const int64_t* __restrict__ out_offsets,
+                                                                        const MergeBlock* __restrict__ blocks,
+                                                                        const int2* __restrict__ found) {
+  constexpr int kWords = kEmitElements / 32 / kPartClearThreads;
+  __shared__ PartClearShared sh;
+  const int tid = threadIdx.x;
+  const MergeBlock blk = blocks[blockIdx.x];
+  const int j = blk.tensor;
+  const int64_t region = out_offsets[j];
+  const int64_t cap = out_offsets[j + 1] - region;
+  const int32_t length = (int32_t)(blk.end - blk.begin);
+#pragma unroll
+  for (int k = 0; k < kWords; ++k) sh.bitmap[tid + k * kPartClearThreads] = 0;
+  const int total = located_pairs(sh, p, num_payloads, region, found, tid);
+  if (total == 0) return;
+  for (int w = 0; w < num_payloads; ++w) {
+    const int n = sh.begin[w + 1] - sh.begin[w];
+    const int32_t* __restrict__ ip = sh.idx_at[w];
+    for (int first = 0; first < n; first += kPartClearThreads * kPartPer) {
+      int32_t r[kPartPer];
+#pragma unroll
+      for (int k = 0; k < kPartPer; ++k) {
+        const int q = first + tid + k * kPartClearThreads;
+        r[k] = q < n ? __builtin_nontemporal_load(ip + q) : -1;
+      }
+#pragma unroll
+      for (int k = 0; k < kPartPer; ++k) {
+        const int64_t rr = (int64_t)r[k] - blk.begin;  // outside the range: a foreign region, or no pair
+        if (r[k] >= 0 && rr >= 0 && rr < length) atomicOr(&sh.bitmap[rr >> 5], 1u << (rr & 31));
+      }
+    }
+  }
+  __syncthreads();
+  float* __restrict__ range = dense + blk.begin;
+  // Lane after lane along the range, four consecutive elements per lane.  A store of part
+  // of a 64-byte sector costs the memory system a read-modify-write of its own, so a sector
+  // with any element to clear is written whole by its four lanes, each of which reads its
+  // 16 bytes first unless all of them are cleared.
+  const bool aligned = ((reinterpret_cast<uintptr_t>(range) & 15) == 0);
+  if (aligned) {
+    constexpr int kGroups = kEmitElements / 4 / kPartClearThreads;
+    constexpr int kBatch = 8;
+    for (int i0 = 0; i0 < kGroups; i0 += kBatch) {
+      uint32_t nib[kBatch];
+      bool touch[kBatch];  // the lane's sector has an element to clear
+      float4 old[kBatch];
+#pragma unroll
+      for (int i = 0; i < kBatch; ++i) {
+        const int e4 = tid + (i0 + i) * kPartClearThreads;
+        const int e = e4 * 4;
+        const uint32_t word = e < length ? sh.bitmap[e4 >> 3] : 0u;
+        nib[i] = (word >> ((e4 & 7) * 4)) & 15u;
+        touch[i] = ((word >> ((e4 & 4) * 4)) & 0xFFFFu) != 0;
+        old[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (touch[i] && nib[i] != 15u && e + 4 <= length) old[i] = *reinterpret_cast<const float4*>(range + e);
+      }
+#pragma unroll
+      for (int i = 0; i < kBatch; ++i) {
+        if (!touch[i]) continue;
+        const int e = (tid + (i0 + i) * kPartClearThreads) * 4;
+        if (e + 4 <= length) {
+          float4 v = old[i];
+          if (nib[i] & 1u) v.x = 0.0f;
+          if (nib[i] & 2u) v.y = 0.0f;
+          if (nib[i] & 4u) v.z = 0.0f;
+          if (nib[i] & 8u) v.w = 0.0f;
+          *reinterpret_cast<float4*>(range + e) = v;
+        } else {  // the last, incomplete group of the range
+#pragma unroll
+          for (int b = 0; b < 4; ++b)
+            if (((nib[i] >> b) & 1u) && e + b < length) range[e + b] = 0.0f;
+        }
+      }
+    }
+  } else {
+    for (int e4 = tid; e4 * 4 < length; e4 += kPartClearThreads) {
+      const uint32_t nib = (sh.bitmap[e4 >> 3] >> ((e4 & 7) * 4)) & 15u;
+      const int e = e4 * 4;
+#pragma unroll
+      for (int b = 0; b < 4; ++b)
+        if (((nib >> b) & 1u) && e + b < length) range[e + b] = 0.0f;
     }
   }
 }
@@ -1964,6 +2292,32 @@ hipError_t launch_merge_regions(float* dense, const RegionPayloads& p, int32_t n
   if (num <= 0 || num_blocks <= 0) return hipSuccess;
   hipLaunchKernelGGL(merge_regions_kernel, dim3((unsigned)num_blocks), dim3(kMergeThreads), 0, stream, dense, p, num,
                      out_offsets_dev, blocks, scale, scaled ? 1 : 0);
+  return hipGetLastError();
+}
+
+static void launch_locate_parts(const RegionPayloads& p, int32_t num, const int64_t* out_offsets_dev,
+                                const MergeBlock* parts, int32_t num_parts, int2* found, hipStream_t stream) {
+  const int64_t waves = (int64_t)num_parts * num;
+  hipLaunchKernelGGL(locate_parts_kernel, dim3((unsigned)ceil_div(waves, kFlatThreads / 64)), dim3(kFlatThreads), 0,
+                     stream, p, num, out_offsets_dev, parts, num_parts, found);
+}
+
+hipError_t launch_merge_parts(float* dense, const RegionPayloads& p, int32_t num, const int64_t* out_offsets_dev,
+                              const MergeBlock* parts, int32_t num_parts, void* found, bool scaled, float scale,
+                              hipStream_t stream) {
+  if (num <= 0 || num_parts <= 0) return hipSuccess;
+  launch_locate_parts(p, num, out_offsets_dev, parts, num_parts, static_cast<int2*>(found), stream);
+  hipLaunchKernelGGL(merge_parts_kernel, dim3((unsigned)num_parts), dim3(kPartThreads), 0, stream, dense, p, num,
+                     out_offsets_dev, parts, static_cast<const int2*>(found), scale, scaled ? 1 : 0);
+  return hipGetLastError();
+}
+
+hipError_t launch_clear_parts(float* dense, const RegionPayloads& p, int32_t num, const int64_t* out_offsets_dev,
+                              const MergeBlock* parts, int32_t num_parts, void* found, hipStream_t stream) {
+  if (num <= 0 || num_parts <= 0) return hipSuccess;
+  launch_locate_parts(p, num, out_offsets_dev, parts, num_parts, static_cast<int2*>(found), stream);
+  hipLaunchKernelGGL(clear_parts_kernel, dim3((unsigned)num_parts), dim3(kPartClearThreads), 0, stream, dense, p, num,
+                     out_offsets_dev, parts, static_cast<const int2*>(found));
   return hipGetLastError();
 }
 

@@ -140,6 +140,12 @@ def _merge_case(gs, N, density, seed, scales=None, preset=None, flags=SORTED, **
     assert np.array_equal(got.view(np.uint32), expect.view(np.uint32)), \
         np.flatnonzero(got.view(np.uint32) != expect.view(np.uint32))[:5]
     overlap = S.topk_overlap(payloads[0][0], payloads[-1][0]) if N > 1 else 0.0
+    # the sparse clear: zero at every index of a payload, nothing else touched
+    for i, _ in payloads:
+        expect[i] = 0.0
+    acc.dgc_dense_clear_regions(dense, [p.out_idx for p in pairs], [p.out_counts for p in pairs])
+    got = dense.cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), expect.view(np.uint32))
     acc.close()
     for p in pairs:
         p.close()
@@ -154,6 +160,24 @@ def test_payloads_are_merged_in_worker_order(N, density, preset, flags):
     total, overlap = _merge_case(gs, N, density, 70 + N, preset=preset, flags=flags,
                                  layout_density=max(density, 0.01) * 4, sample_min=1024, sample_max=8192)
     say(f"[merge] N={N} d={density}: {total} pairs, overlap first/last {overlap:.2f}")
+
+
+@pytest.mark.parametrize("flags", [SORTED, 0])
+@pytest.mark.parametrize("N,density,preset", [(1, 0.02, True), (3, 0.0625, False), (8, 0.25, True), (3, 1.0, True),
+                                               (20, 0.25, False)])
+def test_payloads_are_merged_part_by_part_at_warmup_densities(N, density, preset, flags):
+    """Above 0.5 % the receive side keeps one emit part's range of the dense vector in LDS:
+    the same bit-exact ordered sum, and the sparse clear by bitmap."""
+    gs = S.ragged_set(24, tensors=12, max_numel=400000)
+    total, overlap = _merge_case(gs, N, density, 170 + N, preset=preset, flags=flags, layout_density=density,
+                                 sample_min=1024, sample_max=8192)
+    say(f"[merge parts] N={N} d={density}: {total} pairs, overlap first/last {overlap:.2f}")
+
+
+def test_part_merge_of_many_tiny_tensors():
+    sizes = [1 + (7 * i) % 300 for i in range(1500)] + [40000, 3, 70001]
+    gs = S.GradientSet("tiny", tuple(S.TensorSpec(f"t{i}", (s,)) for i, s in enumerate(sizes)))
+    _merge_case(gs, 4, 0.1, 77, preset=True, flags=0, layout_density=0.1, sample_min=64, sample_max=512)
 
 
 @pytest.mark.parametrize("flags", [SORTED, 0])
