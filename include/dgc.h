@@ -143,6 +143,18 @@ dgc_status dgc_query_plan(const dgc_handle* h, int32_t j, int64_t* k, int64_t* s
 dgc_status dgc_workspace_bytes(const dgc_handle* h, size_t* bytes);
 
 /*
+ * Bytes of a workspace that also holds two staging arrays of n floats each (Section 4,
+ * warm-up training: 25 % down to 0.4 % of the elements are sent during the first epochs).
+ * Given a workspace of at least this size, dgc_compress at a density above 0.5 % masks u
+ * and v inside its streaming pass and parks the selected values in the staging arrays, so
+ * that the emit pass does not come back to u and v (1017 -> about 600 us at 25 % on a
+ * 122 M-element set); every region of the payload is then in ascending index order.  With
+ * the smaller workspace, or with re_threshold on, the same results are computed the slower
+ * way.  Results do not depend on which workspace is given.
+ */
+dgc_status dgc_workspace_bytes_warmup(const dgc_handle* h, size_t* bytes);
+
+/*
  * A payload layout for `density`: out_offsets_host (host, num_tensors + 1) receives
  * the start of each tensor's pair region, capacity_j = min(n_j, max(8 k_j, k_j + 256)).
  */

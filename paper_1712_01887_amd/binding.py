@@ -39,7 +39,7 @@ DGC_DIAG_UNSORTED = 1 << 3
 
 EXPORTS = [
     "dgc_config_default", "dgc_status_string", "dgc_create", "dgc_destroy", "dgc_set_density",
-    "dgc_set_warmup_schedule", "dgc_set_warmup_stage_length", "dgc_set_iteration_density", "dgc_query_plan", "dgc_workspace_bytes",
+    "dgc_set_warmup_schedule", "dgc_set_warmup_stage_length", "dgc_set_iteration_density", "dgc_query_plan", "dgc_workspace_bytes", "dgc_workspace_bytes_warmup",
     "dgc_recommended_payload_layout", "dgc_compress", "dgc_get_diagnostics",
     "dgc_decompress_accumulate", "dgc_decompress_accumulate_regions", "dgc_dense_clear_regions",
     "dgc_version", "dgc_last_error_string", "dgc_profile_enable", "dgc_profile_collect",
@@ -116,6 +116,8 @@ def load() -> C.CDLL:
     lib.dgc_query_plan.argtypes = [vp, i32, P(i64), P(i64), P(i64), P(i64)]
     lib.dgc_workspace_bytes.restype = i32
     lib.dgc_workspace_bytes.argtypes = [vp, P(C.c_size_t)]
+    lib.dgc_workspace_bytes_warmup.restype = i32
+    lib.dgc_workspace_bytes_warmup.argtypes = [vp, P(C.c_size_t)]
     lib.dgc_recommended_payload_layout.restype = i32
     lib.dgc_recommended_payload_layout.argtypes = [vp, dbl, P(i64)]
     lib.dgc_compress.restype = i32
@@ -200,9 +202,11 @@ def dgc_profile_stream_ceiling(a, b, c) -> None:
 class Dgc:
     """One gradient set on one worker: the handle of the C ABI plus its workspace."""
 
-    def __init__(self, cfg: DgcConfig, offsets: Sequence[int]):
+    def __init__(self, cfg: DgcConfig, offsets: Sequence[int], warmup_workspace: bool = False):
         self.lib = load()
         self.cfg = cfg
+        # allocate the workspace with the staging arrays that speed up compress above 0.5 % density
+        self.warmup_workspace = bool(warmup_workspace)
         self.offsets = [int(x) for x in offsets]
         self.num_tensors = len(self.offsets) - 1
         self.n = self.offsets[-1]
@@ -250,6 +254,11 @@ class Dgc:
         _check(self.lib.dgc_workspace_bytes(self._h, C.byref(b)), "dgc_workspace_bytes")
         return int(b.value)
 
+    def dgc_workspace_bytes_warmup(self) -> int:
+        b = C.c_size_t()
+        _check(self.lib.dgc_workspace_bytes_warmup(self._h, C.byref(b)), "dgc_workspace_bytes_warmup")
+        return int(b.value)
+
     def dgc_recommended_payload_layout(self, density: float) -> List[int]:
         arr = (C.c_int64 * (self.num_tensors + 1))()
         _check(self.lib.dgc_recommended_payload_layout(self._h, float(density), arr),
@@ -264,7 +273,7 @@ class Dgc:
     def ensure_workspace(self, device="cuda"):
         import torch
         if self.workspace is None:
-            nbytes = self.dgc_workspace_bytes()
+            nbytes = self.dgc_workspace_bytes_warmup() if self.warmup_workspace else self.dgc_workspace_bytes()
             self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
             base = self.workspace.data_ptr()
             self._ws_ptr = (base + 255) // 256 * 256

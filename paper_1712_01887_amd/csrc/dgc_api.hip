@@ -28,6 +28,7 @@ struct dgc_handle {
   std::vector<EmitBlock> emit_blocks;  // work list of the emit pass
   std::vector<MergeBlock> merge_blocks;  // work list of the receive side: ranges of several emit parts
   std::vector<MergeBlock> part_blocks;   // the same with one emit part per range (warm-up densities)
+  bool layout_may_overflow = true;       // some region of the registered layout is smaller than its tensor
   WorkspaceLayout lay{};
   // what the bound workspace currently holds
   void* ws = nullptr;
@@ -57,7 +58,8 @@ bool hip_ok(hipError_t e, const char* what) {
 }
 
 constexpr size_t kAlign = 256;
-constexpr double kMergeMaxDensity = 0.005;  // receive side: merge by element range in LDS up to here
+constexpr double kMergeMaxDensity = 0.005;
+constexpr double kStagedMinDensity = 0.005;  // compress: staged streaming pass above this density  // receive side: merge by element range in LDS up to here
 constexpr int kProfEvents = 5;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -150,6 +152,10 @@ void build_layout(dgc_handle* h) {
   l.wire_sums = off;    off = align_up(off + sizeof(uint32_t) * h->wire_slots);
   l.mask = off;         off = align_up(off + sizeof(uint16_t) * 64 * tiles);
   l.total = off;
+  // optional: staging arrays of the streaming pass at warm-up densities
+  l.stage_v = off;      off = align_up(off + sizeof(float) * (size_t)h->n);
+  l.stage_u = off;      off = align_up(off + sizeof(float) * (size_t)h->n);
+  l.total_staged = off;
 }
 
 template <typename T>
@@ -230,6 +236,9 @@ dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_
                                  sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, stream),
                   "upload payload layout"))
         return DGC_ERR_HIP;
+      h->layout_may_overflow = false;
+      for (size_t j = 0; j < T; ++j)
+        if (out_offsets[j + 1] - out_offsets[j] < h->offsets[j + 1] - h->offsets[j]) h->layout_may_overflow = true;
       uint64_t slots = 0;
       for (size_t j = 0; j < T; ++j) {
         h->wire_first_block[j] = (uint32_t)slots;
@@ -418,6 +427,12 @@ dgc_status dgc_workspace_bytes(const dgc_handle* h, size_t* bytes) {
   return DGC_OK;
 }
 
+dgc_status dgc_workspace_bytes_warmup(const dgc_handle* h, size_t* bytes) {
+  if (!h || !bytes) return DGC_ERR_INVALID_ARG;
+  *bytes = h->lay.total_staged;
+  return DGC_OK;
+}
+
 dgc_status dgc_recommended_payload_layout(const dgc_handle* h, double density,
                                           int64_t* out_offsets_host) {
   if (!h || !out_offsets_host || !valid_density(density)) return DGC_ERR_INVALID_ARG;
@@ -462,7 +477,6 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
     if (!hip_ok(hipEventRecord(ev[0], stream), "record event")) return DGC_ERR_HIP;
   }
 
-  // paper: Appendix C equation 12 -- the local threshold is N^-1/2 times the global one.
   // paper: Appendix C equation 12 -- the local threshold is N^-1/2 times the global one.
   const double thr_local = clip ? (double)c.clip_threshold / std::sqrt((double)c.num_workers) : 0.0;
   if (clip) {
@@ -516,6 +530,17 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   ta.scale_const = scale_const;
   ta.scale_from_state = sa.scale_from_state;
   ta.nesterov = sa.nesterov;
+  // paper: Section 4, warm-up training -- at the densities of the first epochs the masking of u and v
+  // is folded into the streaming pass and the selected values wait in staging arrays, if the
+  // workspace has them.  (The re-threshold pass drops elements after the streaming pass and
+  // expects them untouched in u and v: it keeps the plain pass.)
+  const bool factor_masking = (c.flags & DGC_FLAG_NO_FACTOR_MASKING) == 0;
+  const bool staged = c.density > kStagedMinDensity && c.refine_alpha <= 0.0f && workspace_bytes >= h->lay.total_staged;
+  ta.factor_masking = factor_masking ? 1 : 0;
+  if (staged) {
+    ta.stage_v = at<float>(workspace, h->lay.stage_v);
+    ta.stage_u = (factor_masking && h->layout_may_overflow) ? at<float>(workspace, h->lay.stage_u) : nullptr;
+  }
   if (!hip_ok(launch_stream(ta, stream), "launch stream kernel")) return DGC_ERR_HIP;
   if (ev && !hip_ok(hipEventRecord(ev[3], stream), "record event")) return DGC_ERR_HIP;
 
@@ -553,7 +578,9 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   ea.out_offsets = at<int64_t>(workspace, h->lay.out_offsets);
   ea.out_counts = out_counts;
   ea.state = state;
-  ea.factor_masking = (c.flags & DGC_FLAG_NO_FACTOR_MASKING) ? 0 : 1;
+  ea.factor_masking = factor_masking ? 1 : 0;
+  ea.stage_v = ta.stage_v;
+  ea.stage_u = ta.stage_u;
   if (!hip_ok(launch_emit(ea, (int32_t)h->emit_blocks.size(), sorted, stream), "launch emit kernel"))
     return DGC_ERR_HIP;
   if (ev && !hip_ok(hipEventRecord(ev[4], stream), "record event")) return DGC_ERR_HIP;

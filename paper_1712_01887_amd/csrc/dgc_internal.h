@@ -108,7 +108,8 @@ struct TensorPlan {
 
 struct WorkspaceLayout {
   size_t state, partials, offsets, out_offsets, plans, thr, tile_info, tile_thr, emit_blocks, refine_counters,
-      tile_count, merge_blocks, part_blocks, part_found, wire_first_block, wire_sums, mask, total;
+      tile_count, merge_blocks, part_blocks, part_found, wire_first_block, wire_sums, mask, total,
+      stage_v, stage_u, total_staged;  // staging arrays lie behind `total`: a workspace may end before them
 };
 
 struct SelectArgs {
@@ -150,6 +151,10 @@ struct StreamArgs {
   float scale_const;
   int32_t scale_from_state;
   int32_t nesterov;
+  // staged pass (warm-up densities): selected v' (and u') of every whole tile, masking of u, v in the pass
+  float* stage_v;              // device, n floats, or null: plain pass
+  float* stage_u;              // device, n floats, or null: no region can overflow, or no factor masking
+  int32_t factor_masking;
 };
 
 struct EmitBlock {
@@ -187,6 +192,8 @@ struct EmitArgs {
   DeviceState* state;
   int32_t factor_masking;
   const uint32_t* tile_count;  // mask bits per tile, left by the streaming pass
+  const float* stage_v;        // as in StreamArgs; null: the streaming pass was a plain one
+  const float* stage_u;
 };
 
 struct MergeBlock {

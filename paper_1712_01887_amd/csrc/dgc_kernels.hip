@@ -562,7 +562,17 @@ __device__ __forceinline__ uint32_t mixed_tile_mask(const StreamArgs& a, int64_t
 // the tensor starts and thresholds it needs in one more round of loads.  A tile that took
 // several dependent rounds, as a first version did, held up the end of the whole launch
 // whenever it was dispatched late: 5 us of 88 on the 161-tensor set.
-template <bool NESTEROV, bool SCALED>
+//
+// STAGED (densities of the warm-up epochs, paper: Section 4): with a quarter of the elements
+// selected, an emit pass that comes back for them reads every sector of v and rewrites
+// every sector of u and v a second time.  Here a tile that lies wholly inside one tensor
+// applies the mask to u and v before it stores them, and parks the selected v' (and u',
+// which a full payload region needs to put back) in the tile's 1024 slots of a staging
+// array, in index order: the emit pass then copies from there and touches u and v only
+// where a region overflows.  An element's position among the tile's selected ones is
+// rows before it + bits of its row in lower lanes (from the votes) + lower bits of its
+// nibble.  Tiles shared between tensors are left to the emit pass as before.
+template <bool NESTEROV, bool SCALED, bool STAGED>
 __global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs a) {
   constexpr int U = kStreamUnroll;
   const int lane = threadIdx.x & 63;
@@ -619,6 +629,47 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs a) {
       y[r][c] = u1;
       z[r][c] = v1;
     }
+  }
+  if (STAGED && thr == thr) {  // wholly inside one tensor (and so a whole tile)
+    uint32_t cand = 0;
+#pragma unroll
+    for (int q = 0; q < 4 * U; ++q)
+      if (fabsf(z[q >> 2][q & 3]) > thr) cand |= 1u << q;
+    float* __restrict__ stage_v = a.stage_v + base;
+    float* __restrict__ stage_u = a.stage_u ? a.stage_u + base : nullptr;
+    const bool clear_u = a.factor_masking != 0;
+    int row_base = 0;
+#pragma unroll
+    for (int r = 0; r < U; ++r) {
+      const uint32_t nib = (cand >> (4 * r)) & 0xFu;
+      int lower = 0, row = 0;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const unsigned long long vote = __ballot((nib >> c) & 1u);
+        lower += (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(vote >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)vote, 0u));
+        row += __popcll(vote);
+      }
+      int pos = row_base + lower;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        if ((nib >> c) & 1u) {
+          stage_v[pos] = z[r][c];
+          if (stage_u) stage_u[pos] = y[r][c];
+          z[r][c] = 0.0f;
+          if (clear_u) y[r][c] = 0.0f;
+          ++pos;
+        }
+      }
+      row_base += row;
+    }
+#pragma unroll
+    for (int r = 0; r < U; ++r) {
+      __builtin_nontemporal_store(y[r], u4 + r * 64);
+      __builtin_nontemporal_store(z[r], v4 + r * 64);
+    }
+    a.mask[tile * 64 + lane] = (uint16_t)cand;
+    if (lane == 0) a.tile_count[tile] = (uint32_t)row_base;
+    return;
   }
   // u' and v' go out first: once stored, u' need not be kept while the mask is worked out
   if (full) {
@@ -1105,24 +1156,22 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
   if (overflow) atomicOr(&a.state->flags, (uint32_t)DGC_DIAG_OVERFLOW);
 }
 
-// Sorted variant.  The workgroup's mask words are parked in LDS; everything that
-// follows walks the tiles one at a time from there, which keeps the register count low
-// (the kernel is latency-bound: what matters is how many workgroups a CU holds).
-__global__ __launch_bounds__(kEmitThreads) void emit_sorted_kernel(EmitArgs a) {
+struct EmitTiles {
+  uint16_t words[kEmitTiles * 64];  // the workgroup's mask words, bits outside the tensor removed
+  int tile_tot[kEmitTiles];         // selected elements per tile
+  int tile_base[kEmitTiles];        // ... and in the workgroup's tiles before it
+  int wave_tot[kEmitThreads / 64];
+  int block_base, block_total;      // slots taken before the workgroup's part; elements of the part
+};
+
+// Parks the workgroup's mask words in LDS, counts per tile, finds where the workgroup's part
+// starts in the tensor's region and, in the tensor's last workgroup, writes the tensor's count.
+__device__ __forceinline__ void emit_tiles(const EmitArgs& a, const EmitBlock& blk, EmitTiles& sh) {
   constexpr int kWaves = kEmitThreads / 64;
   constexpr int kPerWave = kEmitTiles / kWaves;
-  constexpr int kRows = kStreamUnroll;  // rounds of 256 elements per tile
   static_assert(kEmitTiles <= 64, "one wavefront scans the tile totals");
-  __shared__ uint16_t words[kEmitTiles * 64];
-  __shared__ int tile_tot[kEmitTiles];
-  __shared__ int tile_base[kEmitTiles];
-  __shared__ int wave_tot[kWaves];
-  __shared__ int block_base, block_total;
-  __shared__ int32_t list[kEmitList];
-
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  const EmitBlock blk = a.blocks[blockIdx.x];
   const int j = blk.tensor;
   const int64_t lo = a.offsets[j];
   const int64_t hi = a.offsets[j + 1];
@@ -1164,7 +1213,7 @@ __global__ __launch_bounds__(kEmitThreads) void emit_sorted_kernel(EmitArgs a) {
     uint32_t pair[kPerWave / 2];
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
-      words[(wave + i * kWaves) * 64 + lane] = (uint16_t)word[i];
+      sh.words[(wave + i * kWaves) * 64 + lane] = (uint16_t)word[i];
       if (i & 1) pair[i / 2] |= (uint32_t)__popc(word[i]) << 16;
       else pair[i / 2] = (uint32_t)__popc(word[i]);
     }
@@ -1174,35 +1223,52 @@ __global__ __launch_bounds__(kEmitThreads) void emit_sorted_kernel(EmitArgs a) {
       before += __shfl_xor(before, d);
     }
     if (lane == 0) {
-      wave_tot[wave] = before;
+      sh.wave_tot[wave] = before;
 #pragma unroll
       for (int i = 0; i < kPerWave; ++i)
-        tile_tot[wave + i * kWaves] = (int)((pair[i / 2] >> (16 * (i & 1))) & 0xFFFFu);
+        sh.tile_tot[wave + i * kWaves] = (int)((pair[i / 2] >> (16 * (i & 1))) & 0xFFFFu);
     }
   }
   __syncthreads();
   if (wave == 0) {
-    const int own = lane < kEmitTiles ? tile_tot[lane] : 0;
+    const int own = lane < kEmitTiles ? sh.tile_tot[lane] : 0;
     int incl = own;
     for (int d = 1; d < 64; d <<= 1) {
       const int t = __shfl_up(incl, d);
       if (lane >= d) incl += t;
     }
-    if (lane < kEmitTiles) tile_base[lane] = incl - own;
+    if (lane < kEmitTiles) sh.tile_base[lane] = incl - own;
     if (lane == 63) {
       int base = 0;
-      for (int w = 0; w < kWaves; ++w) base += wave_tot[w];
-      block_base = base;
-      block_total = incl;
+      for (int w = 0; w < kWaves; ++w) base += sh.wave_tot[w];
+      sh.block_base = base;
+      sh.block_total = incl;
       if (in_tensor == blk.tensor_blocks - 1) a.out_counts[j] = base + incl;
     }
   }
   __syncthreads();
-  const int total = block_total;
+}
+
+// Sorted variant.  The workgroup's mask words are parked in LDS; everything that
+// follows walks the tiles one at a time from there, which keeps the register count low
+// (the kernel is latency-bound: what matters is how many workgroups a CU holds).
+__global__ __launch_bounds__(kEmitThreads) void emit_sorted_kernel(EmitArgs a) {
+  constexpr int kWaves = kEmitThreads / 64;
+  constexpr int kPerWave = kEmitTiles / kWaves;
+  constexpr int kRows = kStreamUnroll;  // rounds of 256 elements per tile
+  __shared__ EmitTiles sh;
+  __shared__ int32_t list[kEmitList];
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const EmitBlock blk = a.blocks[blockIdx.x];
+  const int j = blk.tensor;
+  const int64_t first = blk.first_tile;
+  emit_tiles(a, blk, sh);
+  const int total = sh.block_total;
   if (total == 0) return;
   const int64_t region = a.out_offsets[j];
   const int64_t cap = a.out_offsets[j + 1] - region;
-  const int64_t base_slot = block_base;
+  const int64_t base_slot = sh.block_base;
   bool overflow = false;
   for (int win = 0; win < total; win += kEmitList) {
     // Index order inside a tile is row (round of 256 elements), lane, component: an
@@ -1211,10 +1277,10 @@ __global__ __launch_bounds__(kEmitThreads) void emit_sorted_kernel(EmitArgs a) {
 #pragma unroll 1
     for (int i = 0; i < kPerWave; ++i) {
       const int tl = wave + i * kWaves;
-      if (tile_tot[tl] == 0) continue;
-      const uint32_t w = words[tl * 64 + lane];
+      if (sh.tile_tot[tl] == 0) continue;
+      const uint32_t w = sh.words[tl * 64 + lane];
       const int64_t t = first + tl;
-      int row_base = tile_base[tl];
+      int row_base = sh.tile_base[tl];
 #pragma unroll
       for (int r = 0; r < kRows; ++r) {
         const uint32_t nib = (w >> (4 * r)) & 0xFu;
@@ -1242,6 +1308,134 @@ __global__ __launch_bounds__(kEmitThreads) void emit_sorted_kernel(EmitArgs a) {
     const int in_win = total - win < kEmitList ? total - win : kEmitList;
     overflow |= emit_move(a, list, in_win, base_slot + win, region, cap);
     __syncthreads();
+  }
+  if (overflow) atomicOr(&a.state->flags, (uint32_t)DGC_DIAG_OVERFLOW);
+}
+
+// Emit pass after a STAGED streaming pass: the selected values of a tile that lies wholly
+// inside one tensor wait in the tile's slots of the staging array, in index order, and u
+// and v are masked already.  The part's payload is written in index order (as the sorted
+// variant does, with the same positions), values copied from the staging array; nothing
+// is listed in LDS and u, v are touched only where the region is full (the element is put
+// back: v' and, under factor masking, u') and in tiles shared between tensors, which the
+// streaming pass leaves alone.
+__global__ __launch_bounds__(kEmitThreads) void emit_staged_kernel(EmitArgs a) {
+  constexpr int kWaves = kEmitThreads / 64;
+  constexpr int kPerWave = kEmitTiles / kWaves;
+  constexpr int kRows = kStreamUnroll;
+  __shared__ EmitTiles sh;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const EmitBlock blk = a.blocks[blockIdx.x];
+  const int j = blk.tensor;
+  const int64_t first = blk.first_tile;
+  emit_tiles(a, blk, sh);
+  if (sh.block_total == 0) return;
+  const int64_t lo = a.offsets[j];
+  const int64_t hi = a.offsets[j + 1];
+  const int64_t region = a.out_offsets[j];
+  const int64_t cap = a.out_offsets[j + 1] - region;
+  int32_t* __restrict__ out_idx = a.out_idx + region;
+  float* __restrict__ out_val = a.out_val + region;
+  float* __restrict__ u = a.u;
+  float* __restrict__ v = a.v;
+  bool overflow = false;
+  // What a tile of the wavefront is, as far as the copy of its values goes.
+  auto tile_of = [&](int i, const float*& stage, float*& vals, int& room) {
+    const int tl = wave + i * kWaves;
+    const int64_t t = first + tl;
+    const int tile_total = sh.tile_tot[tl];
+    const bool staged = t * kWaveTile >= lo && (t + 1) * kWaveTile <= hi;
+    const int64_t slot0 = (int64_t)sh.block_base + sh.tile_base[tl];
+    stage = a.stage_v + t * kWaveTile;
+    vals = out_val + slot0;
+    // slots of the tile that exist (the rest of the tile overflows); none to copy for a shared tile
+    room = cap - slot0 >= tile_total ? tile_total : (cap > slot0 ? (int)(cap - slot0) : 0);
+    return staged;
+  };
+  // The values are a straight copy: the staging array holds a tile's in slot order.  The first
+  // 256 of every tile of the wavefront are loaded before any is stored (one wait for all).
+  {
+    float x[kPerWave][4];
+#pragma unroll
+    for (int i = 0; i < kPerWave; ++i) {
+      const float* stage;
+      float* vals;
+      int room;
+      const bool staged = tile_of(i, stage, vals, room);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) x[i][k] = (staged && k * 64 + lane < room) ? stage[k * 64 + lane] : 0.0f;
+    }
+#pragma unroll
+    for (int i = 0; i < kPerWave; ++i) {
+      const float* stage;
+      float* vals;
+      int room;
+      const bool staged = tile_of(i, stage, vals, room);
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        if (staged && k * 64 + lane < room) vals[k * 64 + lane] = x[i][k];
+    }
+  }
+#pragma unroll 1
+  for (int i = 0; i < kPerWave; ++i) {
+    const int tl = wave + i * kWaves;
+    const int tile_total = sh.tile_tot[tl];
+    if (tile_total == 0) continue;
+    const uint32_t w = sh.words[tl * 64 + lane];
+    const int64_t t = first + tl;
+    const float* __restrict__ stage_v;
+    float* __restrict__ tile_val;
+    int room;
+    {
+      const float* stage;
+      float* vals;
+      const bool st = tile_of(i, stage, vals, room);
+      stage_v = stage;
+      tile_val = vals;
+      if (st) {
+        for (int s = 256 + lane; s < room; s += 64) vals[s] = stage[s];  // beyond a quarter of the tile
+      }
+    }
+    const bool staged = t * kWaveTile >= lo && (t + 1) * kWaveTile <= hi;
+    const float* __restrict__ stage_u = a.stage_u ? a.stage_u + t * kWaveTile : nullptr;
+    int32_t* __restrict__ tile_idx = out_idx + ((int64_t)sh.block_base + sh.tile_base[tl]);
+    // the indices: an element's slot is rows before it + bits of its row in lower lanes + lower bits of its nibble
+    int row_base = 0;
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+      const uint32_t nib = (w >> (4 * r)) & 0xFu;
+      int lower = 0, row = 0;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const unsigned long long vote = __ballot((nib >> c) & 1u);
+        lower += (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(vote >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)vote, 0u));
+        row += __popcll(vote);
+      }
+      int pos = row_base + lower;
+      const int32_t e0 = (int32_t)tile_element(t, lane, 4 * r);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        if ((nib >> c) & 1u) {
+          if (pos < room) {
+            tile_idx[pos] = e0 + c;
+            if (!staged) {  // a tile shared between tensors: value taken and u, v masked here
+              tile_val[pos] = v[e0 + c];
+              v[e0 + c] = 0.0f;
+              if (a.factor_masking) u[e0 + c] = 0.0f;
+            }
+          } else {
+            overflow = true;
+            if (staged) {  // region full: the element goes back to where the streaming pass took it from
+              v[e0 + c] = stage_v[pos];
+              if (a.factor_masking && stage_u) u[e0 + c] = stage_u[pos];
+            }
+          }
+        }
+        pos += (int)((nib >> c) & 1u);
+      }
+      row_base += row;
+    }
   }
   if (overflow) atomicOr(&a.state->flags, (uint32_t)DGC_DIAG_OVERFLOW);
 }
@@ -2230,12 +2424,23 @@ hipError_t launch_stream(const StreamArgs& a, hipStream_t stream) {
   // scale is known to be exactly 1 when neither the norm kernel nor an override supplies it
   const bool scaled = a.scale_from_state != 0 || a.scale_const != 1.0f;
   const dim3 grid((unsigned)blocks), block(kStreamThreads);
+  const bool staged = a.stage_v != nullptr;
   if (a.nesterov) {
-    if (scaled) hipLaunchKernelGGL((stream_kernel<true, true>), grid, block, 0, stream, a);
-    else hipLaunchKernelGGL((stream_kernel<true, false>), grid, block, 0, stream, a);
+    if (staged) {
+      if (scaled) hipLaunchKernelGGL((stream_kernel<true, true, true>), grid, block, 0, stream, a);
+      else hipLaunchKernelGGL((stream_kernel<true, false, true>), grid, block, 0, stream, a);
+    } else {
+      if (scaled) hipLaunchKernelGGL((stream_kernel<true, true, false>), grid, block, 0, stream, a);
+      else hipLaunchKernelGGL((stream_kernel<true, false, false>), grid, block, 0, stream, a);
+    }
   } else {
-    if (scaled) hipLaunchKernelGGL((stream_kernel<false, true>), grid, block, 0, stream, a);
-    else hipLaunchKernelGGL((stream_kernel<false, false>), grid, block, 0, stream, a);
+    if (staged) {
+      if (scaled) hipLaunchKernelGGL((stream_kernel<false, true, true>), grid, block, 0, stream, a);
+      else hipLaunchKernelGGL((stream_kernel<false, false, true>), grid, block, 0, stream, a);
+    } else {
+      if (scaled) hipLaunchKernelGGL((stream_kernel<false, true, false>), grid, block, 0, stream, a);
+      else hipLaunchKernelGGL((stream_kernel<false, false, false>), grid, block, 0, stream, a);
+    }
   }
   return hipGetLastError();
 }
@@ -2254,7 +2459,9 @@ hipError_t launch_refine(const RefineArgs& a, int32_t num_blocks, hipStream_t st
 }
 
 hipError_t launch_emit(const EmitArgs& a, int32_t num_blocks, bool sorted, hipStream_t stream) {
-  if (sorted)
+  if (a.stage_v)
+    hipLaunchKernelGGL(emit_staged_kernel, dim3((unsigned)num_blocks), dim3(kEmitThreads), 0, stream, a);
+  else if (sorted)
     hipLaunchKernelGGL(emit_sorted_kernel, dim3((unsigned)num_blocks), dim3(kEmitThreads), 0, stream, a);
   else
     hipLaunchKernelGGL(emit_kernel, dim3((unsigned)num_blocks), dim3(kEmitThreads), 0, stream, a);

@@ -41,7 +41,7 @@ def oracle_config(**kw) -> O.OracleConfig:
 class Pair:
     """One worker on both sides."""
 
-    def __init__(self, offsets, layout_density=None, capacities=None, **cfg_kw):
+    def __init__(self, offsets, layout_density=None, capacities=None, warmup_workspace=False, **cfg_kw):
         import torch
         self.torch = torch
         self.offsets = [int(x) for x in offsets]
@@ -50,7 +50,7 @@ class Pair:
         self.cfg_kw = dict(cfg_kw)
         self.ocfg = oracle_config(**cfg_kw)
         self.sorted = bool(cfg_kw.get("flags", 0) & B.DGC_FLAG_SORTED_OUTPUT)
-        self.dgc = B.Dgc(B.make_config(**cfg_kw), self.offsets)
+        self.dgc = B.Dgc(B.make_config(**cfg_kw), self.offsets, warmup_workspace=warmup_workspace)
         if capacities is not None:
             layout = np.concatenate([[0], np.cumsum(capacities)]).tolist()
         else:
