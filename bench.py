@@ -16,7 +16,9 @@ before the timed region.
 The default workload is the one the headline metric is quoted on: the
 ResNet-50-shaped set (25,557,032 fp32 elements in 161 tensors, density 0.1 %,
 momentum 0.9, no clipping, N = 16).  --workload lstm | speech time the two
-larger sets for the record.
+larger sets for the record; --workload speech_warmup times the speech set's
+first 20 iterations under the warm-up schedule of densities (25 %, 6.25 %,
+1.5625 %, 0.4 %, then 0.1 %), where a step is one iteration at its density.
 
 Prints one JSON line: whole-job throughput in dense gradient elements per
 second, the roofline of the dominant kernel (the streaming pass, 20 bytes per
@@ -59,12 +61,114 @@ WORKLOADS = {
 MEASURED_TRAFFIC_BYTES = {"resnet50": 516175108}
 
 
+WARMUP_DESCRIPTION = ("speech-model-shaped set, 62 fp32 tensors, 122,153,069 elements, m=0.9, no clipping, N=8, "
+                      "iterations 0..19 of the warm-up schedule (densities 0.25, 0.0625, 0.015625, 0.004, then 0.001)")
+
+
+def run_warmup_schedule(args):
+    """The speech set's first 20 iterations: dgc_set_iteration_density, dgc_compress of one
+    worker, accumulate of 8 payloads of that density, sparse clear.  --steps counts iterations
+    (rounded up to whole passes of 20), --warmup passes nothing but the first pass."""
+    import torch
+    from paper_1712_01887_amd import binding as B
+    from paper_1712_01887_amd import synthetic as S
+
+    dev, N, seed, iters = "cuda", 8, 2025, 20
+    gs = S.speech_set()
+    n = gs.numel
+    scales = S.tensor_scales(gs, seed)
+    dgc = B.Dgc(B.make_config(momentum=0.9, density=0.001, seed=1, num_workers=N), gs.offsets, warmup_workspace=True)
+    dgc.set_layout(dgc.dgc_recommended_payload_layout(0.25))
+    shared = S.gradient(gs, seed, 999, 0, scales)
+    g_pool = [torch.from_numpy(S.correlated_gradient(gs, seed, r, 0, shared, scales=scales)).to(dev) for r in range(2)]
+    u = torch.zeros(n, device=dev)
+    v = torch.zeros(n, device=dev)
+    dense = torch.zeros(n, device=dev)
+    fresh = dgc.alloc_payload(dev)
+    stage_of = [min(i, 4) for i in range(iters)]
+    others = []                                   # per stage: N - 1 payloads of that density
+    gw = [torch.from_numpy(S.correlated_gradient(gs, seed, 100 + w, 0, shared, scales=scales)).to(dev)
+          for w in range(N - 1)]
+    for stage in range(5):
+        dgc.dgc_set_iteration_density(stage)
+        pls = []
+        for w in range(N - 1):
+            u.zero_()
+            v.zero_()
+            pl = dgc.alloc_payload(dev)
+            dgc.dgc_compress(gw[w], u, v, pl[0], pl[1], pl[2], pl[3], 0)
+            pls.append(pl)
+        others.append(pls)
+    torch.cuda.synchronize()
+    del gw
+    u.zero_()
+    v.zero_()
+    prepared = {}
+    for stage in range(5):
+        o = others[stage]
+        plist = B.PayloadList([fresh[0]] + [x[0] for x in o], [fresh[1]] + [x[1] for x in o],
+                              [fresh[2]] + [x[2] for x in o])
+        for q in range(2):
+            prepared[(stage, q)] = B.PreparedStep(dgc, g_pool[q], u, v, fresh, plist, dense)
+
+    def one_pass(events=None):
+        for i in range(iters):
+            dgc.dgc_set_iteration_density(i)
+            p = prepared[(stage_of[i], i & 1)]
+            if events is not None:
+                events[i][0].record()
+            p.compress(i)
+            if events is not None:
+                events[i][1].record()
+            p.accumulate_and_clear()
+            if events is not None:
+                events[i][2].record()
+
+    passes = max(1, (args.steps + iters - 1) // iters)
+    one_pass()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(passes):
+        one_pass()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / (passes * iters) * 1e3
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(iters)]
+    one_pass(ev)
+    torch.cuda.synchronize()
+    per_iteration = [{"iteration": i, "density": [0.25, 0.0625, 0.015625, 0.004, 0.001][stage_of[i]],
+                      "compress_us": round(ev[i][0].elapsed_time(ev[i][1]) * 1e3, 1),
+                      "accumulate_and_clear_us": round(ev[i][1].elapsed_time(ev[i][2]) * 1e3, 1)}
+                     for i in range(6)]
+    out = {
+        "metric": "dense gradient elements/s for compress+decompress",
+        "value": n / (ms_per_step * 1e-3),
+        "unit": "elements/s",
+        "n_gpus": 1,
+        "steps": passes * iters,
+        "warmup": iters,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": WARMUP_DESCRIPTION + "; step = one iteration: compress one worker + accumulate 8 "
+                               "payloads + sparse clear; workspace with staging arrays",
+                   "elements": n, "tensors": len(gs.sizes), "workers_accumulated": N},
+        "ms_per_20_iterations": round(ms_per_step * iters, 3),
+        "first_iterations": per_iteration,
+        "roofline": None,
+    }
+    print(json.dumps(out))
+
+
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", choices=sorted(WORKLOADS), default="resnet50")
+    ap.add_argument("--workload", choices=sorted(WORKLOADS) + ["speech_warmup"], default="resnet50")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sample-block", type=int, default=None, help="override dgc_config.sample_block")
     ap.add_argument("--refine-alpha", type=float, default=None,
@@ -135,6 +239,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
+    if args.workload == "speech_warmup":
+        run_warmup_schedule(args)
+        return
     dev = "cuda"
     set_name, cfg_kw, n_workers, description = WORKLOADS[args.workload]
     cfg_kw = dict(cfg_kw)

@@ -761,7 +761,12 @@ static dgc_status scatter_regions(dgc_handle* h, float* dense, int32_t num_paylo
   void* found = at<char>(workspace, h->lay.part_found);
   if (clear) {
     if (few) {
-      if (!hip_ok(launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, widest,
+      // the launch is sized for the pairs the density lets expect (the kernel strides over whatever
+      // there is), not for regions that were laid out for a higher density
+      int64_t expected = 0;
+      for (int32_t j = 0; j < h->num_tensors; ++j) expected += 8 * h->k[j] + 256;
+      const int64_t sized_for = expected < widest ? expected : widest;
+      if (!hip_ok(launch_scatter_regions(dense, h->n, p, 0, num_payloads, oo, h->num_tensors, sized_for,
                                          kScatterClear, 0.0f, nullptr, stream),
                   "launch scatter kernel"))
         return DGC_ERR_HIP;
