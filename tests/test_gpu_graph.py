@@ -15,16 +15,17 @@ from tests.parity import oracle_config, say
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("flags,extra", [
-    (0, dict(clip_threshold=0.05, num_workers=4)),
-    (B.DGC_FLAG_SORTED_OUTPUT, dict(refine_alpha=1.0, sample_min=64, sample_max=64, sample_block=4)),
+@pytest.mark.parametrize("flags,extra,warm", [
+    (0, dict(clip_threshold=0.05, num_workers=4), False),
+    (B.DGC_FLAG_SORTED_OUTPUT, dict(refine_alpha=1.0, sample_min=64, sample_max=64, sample_block=4), False),
+    (0, dict(), True),                  # staged streaming pass, part kernels on the receive side
 ])
-def test_captured_step_replays_match_the_oracle(flags, extra):
+def test_captured_step_replays_match_the_oracle(flags, extra, warm):
     import torch
     gs = S.ragged_set(19, tensors=14, max_numel=150000)
     n = gs.numel
     kw = dict(momentum=0.9, density=0.01, seed=6, flags=flags, **extra)
-    dgc = B.Dgc(B.make_config(**kw), gs.offsets)
+    dgc = B.Dgc(B.make_config(**kw), gs.offsets, warmup_workspace=warm)
     layout = dgc.dgc_recommended_payload_layout(0.05)
     dgc.set_layout(layout)
     caps = [layout[j + 1] - layout[j] for j in range(len(gs.sizes))]

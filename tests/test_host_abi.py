@@ -155,6 +155,9 @@ def test_density_control_and_warmup(dgc_lib):
     with pytest.raises(B.DgcError):
         d.dgc_query_plan(1)
     assert d.dgc_workspace_bytes() > 0 and d.dgc_workspace_bytes() % 256 == 0
+    # the warm-up workspace: the same, and behind it two staging arrays of n floats
+    extra = d.dgc_workspace_bytes_warmup() - d.dgc_workspace_bytes()
+    assert 8 * d.n <= extra <= 8 * d.n + 512 and d.dgc_workspace_bytes_warmup() % 256 == 0
     d.close()
 
 
