@@ -35,15 +35,16 @@ def random_case(seed: int):
     return rng, offsets, sizes, kw, tight
 
 
+@pytest.mark.parametrize("warm", [False, True])      # True: workspace with the staging arrays of the warm-up densities
 @pytest.mark.parametrize("seed", range(48))
-def test_random_configuration(seed):
+def test_random_configuration(seed, warm):
     rng, offsets, sizes, kw, tight = random_case(seed)
     n = int(offsets[-1])
     if tight:
         caps = [max(1, O.topk_count(kw["density"], s) // 2) for s in sizes]
-        p = Pair(offsets, capacities=caps, **kw)
+        p = Pair(offsets, capacities=caps, warmup_workspace=warm, **kw)
     else:
-        p = Pair(offsets, layout_density=1.0, **kw)       # room for anything a small sample lets through
+        p = Pair(offsets, layout_density=1.0, warmup_workspace=warm, **kw)       # room for anything a small sample lets through
     scale = float(rng.choice([1e-3, 1.0, 30.0]))
     for it in range(3):
         g = (scale * rng.standard_t(3, n)).astype(np.float32)
