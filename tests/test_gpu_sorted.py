@@ -188,16 +188,17 @@ def test_sixteen_worker_merge_resnet50_shape(flags):
     assert 0.15 < overlap < 0.5
 
 
-def test_sorted_sparse_sgd_apply_is_merged_in_worker_order():
+@pytest.mark.parametrize("density,flags", [(0.002, SORTED), (0.0625, 0), (0.25, SORTED)])
+def test_sparse_sgd_apply_is_merged_in_worker_order(density, flags):
     import torch
     gs = S.ragged_set(23, tensors=9, max_numel=300000)
     N, lr = 6, 0.05
-    kw = dict(momentum=0.9, density=0.002, seed=12, num_workers=N, flags=SORTED, sample_min=1024, sample_max=8192)
+    kw = dict(momentum=0.9, density=density, seed=12, num_workers=N, flags=flags, sample_min=1024, sample_max=8192)
     shared = S.gradient(gs, 29, 99, 0)
     pairs, payloads = [], []
     for w in range(N):
-        p = Pair(gs.offsets, layout_density=0.02, **kw)
-        res = p.step(S.correlated_gradient(gs, 29, w, 0, shared), 0, label=f"sorted sgd w{w}")
+        p = Pair(gs.offsets, layout_density=max(0.02, density), **kw)
+        res = p.step(S.correlated_gradient(gs, 29, w, 0, shared), 0, label=f"sgd d={density} w{w}")
         payloads.append(O.flatten_payload(res))
         pairs.append(p)
     rng = np.random.default_rng(5)
