@@ -51,6 +51,9 @@ WORKLOADS = {
     "speech": ("speech_set", dict(momentum=0.9, density=0.001, seed=1, num_workers=8), 8,
                "speech-model-shaped set (7 bidirectional GRU-1200 layers), 62 fp32 tensors, 122,153,069 "
                "elements, density 0.001 (steady state of the warm-up schedule), m=0.9, no clipping"),
+    "speech_literal": ("speech_literal_set", dict(momentum=0.9, density=0.001, seed=1, num_workers=8), 8,
+                       "speech set read literally from the benchmark's shapes (5 bidirectional GRU-1024 layers), 46 fp32 "
+                       "tensors, 90,192,061 elements, density 0.001, m=0.9, no clipping"),
 }
 
 # HBM traffic of one streaming-kernel launch on the default workload from rocprofv3 --pmc

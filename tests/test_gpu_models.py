@@ -73,6 +73,20 @@ def test_speech_set_warmup_schedule_six_iterations():
     p.close()
 
 
+def test_literal_speech_set_two_iterations():
+    """The 90 M-element set of five bidirectional GRU-1024 layers: a warm-up step with the
+    staging workspace, then the steady state."""
+    gs = S.speech_literal_set()
+    scales = S.tensor_scales(gs, 53)
+    p = Pair(gs.offsets, warmup_workspace=True, layout_density=0.0625, momentum=0.9, density=0.0625, seed=53,
+             num_workers=8)
+    for it, d in enumerate([0.0625, 0.001]):
+        p.set_density(d)
+        say(f"[speech literal] iteration {it} density {d}")
+        p.step(S.gradient(gs, 53, 0, it, scales), it, check_state=(it == 1), label=f"speech literal it{it}")
+    p.close()
+
+
 def test_sixteen_worker_accumulate_resnet50_shape():
     import torch
     gs = S.resnet50_set()

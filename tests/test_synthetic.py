@@ -36,6 +36,8 @@ def test_lstm_and_speech_manifests():
     assert sp.numel == 122_153_069 and len(sp.tensors) == 62 and max(sp.sizes) == 4_723_200
     assert abs(sp.numel * 4 / 1e6 - _printed()["deepspeech"]) < 1.0      # 488.6 vs 488.08 printed
     assert sp.sizes[-1] == 29                                             # the unaligned tail
+    lit = S.speech_literal_set()                                          # the benchmark's shapes read literally
+    assert lit.numel == 90_192_061 and len(lit.tensors) == 46 and lit.sizes[-1] == 29
 
 
 def test_generators_are_seeded_and_shaped():
