@@ -38,7 +38,6 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0           # MI355X published peak
 BYTES_PER_ELEMENT = 20           # streaming pass: read g, u, v; write u, v (fp32)
-ROTATE = 4
 
 WORKLOADS = {
     # name: (set constructor, config, N payloads accumulated, description)
@@ -178,6 +177,9 @@ def parse_args():
                     help="switch the Section 5 re-threshold on (dgc_config.refine_alpha); off by default")
     ap.add_argument("--sorted", action="store_true",
                     help="emit every tensor's pairs in ascending index order (DGC_FLAG_SORTED_OUTPUT)")
+    ap.add_argument("--rotate", type=int, default=4,
+                    help="independent (g, u, v) sets the steps rotate through; 4 keeps every step's operands out of the "
+                         "last-level cache (the default and the headline), 1 shows the cache-resident case")
     ap.add_argument("--profile-only", action="store_true",
                     help="skip the CPU baseline and the event-instrumented pass (for rocprofv3 runs)")
     return ap.parse_args()
@@ -246,6 +248,7 @@ def main():
         run_warmup_schedule(args)
         return
     dev = "cuda"
+    ROTATE = max(1, args.rotate)
     set_name, cfg_kw, n_workers, description = WORKLOADS[args.workload]
     cfg_kw = dict(cfg_kw)
     gs = getattr(S, set_name)()
@@ -381,7 +384,10 @@ def main():
             "stream_kernel_frac_of_it": round(achieved / ceiling, 4)}
         comp = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
         acc = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+        per_step = sorted(e[0].elapsed_time(e[2]) for e in ev)
         breakdown = {
+            "step_us_median_by_events": round(per_step[len(per_step) // 2] * 1e3, 2),
+            "step_us_best_by_events": round(per_step[0] * 1e3, 2),
             "compress_us": round(comp * 1e3, 2),
             "norm_kernel_us": round(norm_ms / calls * 1e3, 2) if clip else None,
             "select_kernel_us": round(select_ms / calls * 1e3, 2),
