@@ -1880,36 +1880,76 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
 // of one payload have distinct indices and are added without synchronisation; a
 // barrier separates one payload from the next.
 // At these densities a region holds up to millions of pairs and the search for a part's
-// pairs is four rounds of dependent loads: with one workgroup per compute unit (the
+// pairs is several rounds of dependent loads: with one workgroup per compute unit (the
 // accumulator fills LDS) nothing else would run meanwhile.  So the searches of all parts
-// and payloads run first, one wavefront each, spread over the chip, and leave (first
-// pair, number of pairs) in a table.
+// and payloads run first, spread over the chip, and leave (first pair, number of pairs)
+// of every part in every payload's region in a table (a part ends where the next one of
+// its tensor starts, so one bound per part is searched for).  The probes are what this launch costs (each one a 64-byte sector from
+// HBM: 350 MB with 32 probes per round and two bounds per part), so eight lanes share a
+// search: 8 probes per round, about seven rounds for a region of a million pairs.
 __global__ __launch_bounds__(kFlatThreads) void locate_parts_kernel(RegionPayloads p, int32_t num_payloads,
                                                                     const int64_t* __restrict__ out_offsets,
                                                                     const MergeBlock* __restrict__ blocks,
                                                                     int32_t num_blocks, int2* __restrict__ found) {
+  // A wavefront takes seven consecutive parts of one payload; its eighth group finds the
+  // start of the part after them, which is where the seventh ends.
   const int lane = threadIdx.x & 63;
-  const int64_t id = (int64_t)blockIdx.x * (kFlatThreads / 64) + (threadIdx.x >> 6);
-  if (id >= (int64_t)num_blocks * num_payloads) return;
-  const int b = (int)(id / num_payloads);
-  const int w = (int)(id % num_payloads);
-  const MergeBlock blk = blocks[b];
-  const int64_t region = out_offsets[blk.tensor];
-  const int64_t cap = out_offsets[blk.tensor + 1] - region;
-  int64_t cnt = p.counts[w][blk.tensor];
-  if (cnt > cap) cnt = cap;
-  if (cnt < 0) cnt = 0;
-  int lo, hi;
-  wave_equal_range(p.idx[w] + region, (int)cnt, (int32_t)blk.begin, (int32_t)blk.end, lane, lo, hi);
-  if (lane == 0) found[id] = make_int2(lo, hi - lo);
+  const int group = lane >> 3;
+  const int sub = lane & 7;
+  const int waves_per_payload = (num_blocks + 6) / 7;
+  const int64_t wave_id = (int64_t)blockIdx.x * (kFlatThreads / 64) + (threadIdx.x >> 6);
+  const int w = (int)(wave_id / waves_per_payload);
+  const int b = (int)(wave_id % waves_per_payload) * 7 + group;
+  const bool valid = w < num_payloads && b < num_blocks;
+  const int32_t* __restrict__ list = nullptr;
+  int32_t x = 0;
+  int lo = 0, hi = 0;  // the answer lies in [lo, hi]
+  int cnt = 0;
+  bool last = true;    // the tensor's last part: it ends where the region's pairs end
+  if (valid) {
+    const MergeBlock blk = blocks[b];
+    const int64_t region = out_offsets[blk.tensor];
+    const int64_t cap = out_offsets[blk.tensor + 1] - region;
+    int64_t c = p.counts[w][blk.tensor];
+    if (c > cap) c = cap;
+    if (c < 0) c = 0;
+    cnt = (int)c;
+    last = b + 1 >= num_blocks || blocks[b + 1].tensor != blk.tensor;
+    list = p.idx[w] + region;
+    x = (int32_t)blk.begin;
+    hi = cnt;
+  }
+  // first position whose index is not below x ("index < x" is monotone along a region)
+  while (__ballot(hi > lo)) {
+    const int span = hi - lo;
+    const int step = (span + 7) >> 3;
+    const int pos = lo + sub * step;
+    const bool less = span > 0 && pos < hi && list[pos] < x;
+    const unsigned long long votes = __ballot(less);
+    const int c = __popc((uint32_t)(votes >> (8 * group)) & 0xFFu);  // probes below x form a prefix
+    if (span > 0) {
+      if (c == 0) {
+        hi = lo;
+      } else {
+        const int next = lo + c * step;
+        lo = lo + (c - 1) * step + 1;
+        hi = next < hi ? next : hi;
+      }
+    }
+  }
+  const int next_lo = __shfl(lo, (lane + 8) & 63);  // of the part after this one (group 7 does not use it)
+  if (valid && group < 7 && sub == 0) {
+    const int end = last ? cnt : next_lo;
+    found[(int64_t)b * num_payloads + w] = make_int2(lo, end > lo ? end - lo : 0);
+  }
 }
 
 // Fills begin[], idx_at[] and val_at[] from that table; returns the number of pairs.
 template <typename Shared>
 __device__ __forceinline__ int located_pairs(Shared& sh, const RegionPayloads& p, int32_t num_payloads, int64_t region,
-                                             const int2* __restrict__ found, int tid) {
+                                             const int2* __restrict__ found, int part, int tid) {
   if (tid < num_payloads) {
-    const int2 f = found[(int64_t)blockIdx.x * num_payloads + tid];
+    const int2 f = found[(int64_t)part * num_payloads + tid];
     sh.idx_at[tid] = p.idx[tid] + region + f.x;
     sh.val_at[tid] = p.val[tid] ? p.val[tid] + region + f.x : nullptr;
     sh.begin[tid + 1] = f.y;  // length for now
@@ -1939,136 +1979,164 @@ __global__ __launch_bounds__(kPartThreads) void merge_parts_kernel(float* __rest
                                                                    int32_t num_payloads,
                                                                    const int64_t* __restrict__ out_offsets,
                                                                    const MergeBlock* __restrict__ blocks,
+                                                                   int32_t num_blocks,
                                                                    const int2* __restrict__ found, float scale,
                                                                    int32_t scaled) {
   constexpr int kElems = kEmitElements / kPartThreads;
   __shared__ PartShared sh;
   const int tid = threadIdx.x;
-  const MergeBlock blk = blocks[blockIdx.x];
-  const int j = blk.tensor;
-  const int64_t region = out_offsets[j];
-  const int64_t cap = out_offsets[j + 1] - region;
-  const int32_t length = (int32_t)(blk.end - blk.begin);  // <= kEmitElements
-  float* __restrict__ range = dense + blk.begin;
-  // the range of `dense` is on its way while the pairs are located
+  // The accumulator fills LDS, so a workgroup is alone on its compute unit: the grid is one
+  // workgroup per compute unit and every workgroup takes parts b, b + grid, ...; the range of
+  // the next part is requested before the finished one is written back, so that neither
+  // the write-back nor the table look-up leaves the memory pipeline of the unit empty.
+  int b = blockIdx.x;
+  if (b >= num_blocks) return;
+  MergeBlock blk = blocks[b];
   float d[kElems];
+  {
+    const int32_t len = (int32_t)(blk.end - blk.begin);
+    const float* __restrict__ src = dense + blk.begin;
 #pragma unroll
-  for (int k = 0; k < kElems; ++k) {
-    const int e = tid + k * kPartThreads;
-    d[k] = e < length ? __builtin_nontemporal_load(range + e) : 0.0f;
+    for (int i = 0; i < kElems; ++i) {
+      const int e = tid + i * kPartThreads;
+      d[i] = e < len ? __builtin_nontemporal_load(src + e) : 0.0f;
+    }
   }
-  const int total = located_pairs(sh, p, num_payloads, region, found, tid);
-  if (total == 0) return;
-#pragma unroll
-  for (int k = 0; k < kElems; ++k) sh.acc[tid + k * kPartThreads] = d[k];
-
-  if (total <= kPartRound) {
-    // Few pairs (many payloads of a low density): all of them at once, whatever payload they
-    // belong to, so that their loads are one wait; then payload after payload from registers.
-    int32_t at[kPartPer];  // payload << 16 | index relative to the range; -1: none
-    float x[kPartPer];
-#pragma unroll
-    for (int k = 0; k < kPartPer; ++k) {
-      const int q = tid + k * kPartThreads;
-      at[k] = -1;
-      x[k] = 0.0f;
-      if (q < total) {
-        const int w = payload_of(sh.begin, num_payloads, q);
-        const int src = q - sh.begin[w];
-        const int64_t r = (int64_t)__builtin_nontemporal_load(sh.idx_at[w] + src) - blk.begin;
-        const float value = __builtin_nontemporal_load(sh.val_at[w] + src);
-        x[k] = scaled ? scale * value : value;
-        if (r >= 0 && r < length) at[k] = (int32_t)r | (w << 16);  // anything else: a foreign region
-      }
-    }
-    __syncthreads();  // the accumulator is filled
-    for (int w = 0; w < num_payloads; ++w) {  // payloads in the order given
-      if (sh.begin[w + 1] == sh.begin[w]) continue;
-      float sum[kPartPer];
-#pragma unroll
-      for (int k = 0; k < kPartPer; ++k)
-        sum[k] = (at[k] >= 0 && (at[k] >> 16) == w) ? sh.acc[at[k] & 0xFFFF] + x[k] : 0.0f;
-#pragma unroll
-      for (int k = 0; k < kPartPer; ++k)
-        if (at[k] >= 0 && (at[k] >> 16) == w) sh.acc[at[k] & 0xFFFF] = sum[k];
-      __syncthreads();
-    }
-  } else {
-  // A round: up to kPartRound consecutive pairs of one payload.  Two rounds are on their way
-  // while a third is added, and nothing in fetch() depends on the loaded words.
-  struct Loaded {
-    int32_t idx[kPartPer];
-    float x[kPartPer];
-    int w;  // payload
-    int n;  // pairs of the round; 0: there is no further round
-  };
-  int cursor_w = 0, cursor_at = 0;  // next pair to fetch: payload, position among its pairs inside the range
-  auto fetch = [&](Loaded& L) {
-    L.n = 0;
-    L.w = 0;
-    while (cursor_w < num_payloads) {
-      const int len = sh.begin[cursor_w + 1] - sh.begin[cursor_w];
-      if (cursor_at < len) break;
-      ++cursor_w;
-      cursor_at = 0;
-    }
-    if (cursor_w >= num_payloads) return;
-    const int left = sh.begin[cursor_w + 1] - sh.begin[cursor_w] - cursor_at;
-    L.w = cursor_w;
-    L.n = left < kPartRound ? left : kPartRound;
-    const int32_t* __restrict__ ip = sh.idx_at[cursor_w] + cursor_at;
-    const float* __restrict__ vp = sh.val_at[cursor_w] + cursor_at;
-    cursor_at += L.n;
-#pragma unroll
-    for (int k = 0; k < kPartPer; ++k) {
-      const int q = tid + k * kPartThreads;
-      L.idx[k] = 0;
-      L.x[k] = 0.0f;
-      if (q < L.n) {
-        L.idx[k] = __builtin_nontemporal_load(ip + q);
-        L.x[k] = __builtin_nontemporal_load(vp + q);
-      }
-    }
-  };
-  int last_w = -1;
-  // Adds the round in L and refills L with the next round to fetch.
-  auto add = [&](Loaded& L) {
-    int32_t at[kPartPer];  // index relative to the range; -1: none
-    float x[kPartPer];
-#pragma unroll
-    for (int k = 0; k < kPartPer; ++k) {
-      const int64_t r = (int64_t)L.idx[k] - blk.begin;
-      // an index outside the range can only come from a foreign region
-      at[k] = (tid + k * kPartThreads < L.n && r >= 0 && r < length) ? (int32_t)r : -1;
-      x[k] = scaled ? scale * L.x[k] : L.x[k];
-    }
-    const int w = L.w;
-    fetch(L);
-    if (w != last_w) __syncthreads();  // the payload before is added (the first time: the accumulator is filled)
-    last_w = w;
-    // the indices of one payload are distinct: all reads, then all writes, no barrier between its rounds
-    float sum[kPartPer];
-#pragma unroll
-    for (int k = 0; k < kPartPer; ++k) sum[k] = at[k] >= 0 ? sh.acc[at[k]] + x[k] : 0.0f;
-#pragma unroll
-    for (int k = 0; k < kPartPer; ++k)
-      if (at[k] >= 0) sh.acc[at[k]] = sum[k];
-  };
-  Loaded A, B;
-  fetch(A);
-  fetch(B);
   for (;;) {
-    if (A.n == 0) break;
-    add(A);
-    if (B.n == 0) break;
-    add(B);
-  }
-  __syncthreads();
-  }
+    const int next_b = b + (int)gridDim.x;
+    const bool more = next_b < num_blocks;
+    const MergeBlock next = blocks[more ? next_b : b];
+    const int32_t length = (int32_t)(blk.end - blk.begin);  // <= kEmitElements
+    float* __restrict__ range = dense + blk.begin;
+    const int total = located_pairs(sh, p, num_payloads, out_offsets[blk.tensor], found, b, tid);
+    if (total > 0) {
 #pragma unroll
-  for (int k = 0; k < kElems; ++k) {
-    const int e = tid + k * kPartThreads;
-    if (e < length) __builtin_nontemporal_store(sh.acc[e], range + e);
+      for (int k = 0; k < kElems; ++k) sh.acc[tid + k * kPartThreads] = d[k];
+
+      if (total <= kPartRound) {
+        // Few pairs (many payloads of a low density): all of them at once, whatever payload they
+        // belong to, so that their loads are one wait; then payload after payload from registers.
+        int32_t at[kPartPer];  // payload << 16 | index relative to the range; -1: none
+        float x[kPartPer];
+#pragma unroll
+        for (int k = 0; k < kPartPer; ++k) {
+          const int q = tid + k * kPartThreads;
+          at[k] = -1;
+          x[k] = 0.0f;
+          if (q < total) {
+            const int w = payload_of(sh.begin, num_payloads, q);
+            const int src = q - sh.begin[w];
+            const int64_t r = (int64_t)__builtin_nontemporal_load(sh.idx_at[w] + src) - blk.begin;
+            const float value = __builtin_nontemporal_load(sh.val_at[w] + src);
+            x[k] = scaled ? scale * value : value;
+            if (r >= 0 && r < length) at[k] = (int32_t)r | (w << 16);  // anything else: a foreign region
+          }
+        }
+        __syncthreads();  // the accumulator is filled
+        for (int w = 0; w < num_payloads; ++w) {  // payloads in the order given
+          if (sh.begin[w + 1] == sh.begin[w]) continue;
+          float sum[kPartPer];
+#pragma unroll
+          for (int k = 0; k < kPartPer; ++k)
+            sum[k] = (at[k] >= 0 && (at[k] >> 16) == w) ? sh.acc[at[k] & 0xFFFF] + x[k] : 0.0f;
+#pragma unroll
+          for (int k = 0; k < kPartPer; ++k)
+            if (at[k] >= 0 && (at[k] >> 16) == w) sh.acc[at[k] & 0xFFFF] = sum[k];
+          __syncthreads();
+        }
+      } else {
+      // A round: up to kPartRound consecutive pairs of one payload.  Two rounds are on their way
+      // while a third is added, and nothing in fetch() depends on the loaded words.
+      struct Loaded {
+        int32_t idx[kPartPer];
+        float x[kPartPer];
+        int w;  // payload
+        int n;  // pairs of the round; 0: there is no further round
+      };
+      int cursor_w = 0, cursor_at = 0;  // next pair to fetch: payload, position among its pairs inside the range
+      auto fetch = [&](Loaded& L) {
+        L.n = 0;
+        L.w = 0;
+        while (cursor_w < num_payloads) {
+          const int len = sh.begin[cursor_w + 1] - sh.begin[cursor_w];
+          if (cursor_at < len) break;
+          ++cursor_w;
+          cursor_at = 0;
+        }
+        if (cursor_w >= num_payloads) return;
+        const int left = sh.begin[cursor_w + 1] - sh.begin[cursor_w] - cursor_at;
+        L.w = cursor_w;
+        L.n = left < kPartRound ? left : kPartRound;
+        const int32_t* __restrict__ ip = sh.idx_at[cursor_w] + cursor_at;
+        const float* __restrict__ vp = sh.val_at[cursor_w] + cursor_at;
+        cursor_at += L.n;
+#pragma unroll
+        for (int k = 0; k < kPartPer; ++k) {
+          const int q = tid + k * kPartThreads;
+          L.idx[k] = 0;
+          L.x[k] = 0.0f;
+          if (q < L.n) {
+            L.idx[k] = __builtin_nontemporal_load(ip + q);
+            L.x[k] = __builtin_nontemporal_load(vp + q);
+          }
+        }
+      };
+      int last_w = -1;
+      // Adds the round in L and refills L with the next round to fetch.
+      auto add = [&](Loaded& L) {
+        int32_t at[kPartPer];  // index relative to the range; -1: none
+        float x[kPartPer];
+#pragma unroll
+        for (int k = 0; k < kPartPer; ++k) {
+          const int64_t r = (int64_t)L.idx[k] - blk.begin;
+          // an index outside the range can only come from a foreign region
+          at[k] = (tid + k * kPartThreads < L.n && r >= 0 && r < length) ? (int32_t)r : -1;
+          x[k] = scaled ? scale * L.x[k] : L.x[k];
+        }
+        const int w = L.w;
+        fetch(L);
+        if (w != last_w) __syncthreads();  // the payload before is added (the first time: the accumulator is filled)
+        last_w = w;
+        // the indices of one payload are distinct: all reads, then all writes, no barrier between its rounds
+        float sum[kPartPer];
+#pragma unroll
+        for (int k = 0; k < kPartPer; ++k) sum[k] = at[k] >= 0 ? sh.acc[at[k]] + x[k] : 0.0f;
+#pragma unroll
+        for (int k = 0; k < kPartPer; ++k)
+          if (at[k] >= 0) sh.acc[at[k]] = sum[k];
+      };
+      Loaded A, B;
+      fetch(A);
+      fetch(B);
+      for (;;) {
+        if (A.n == 0) break;
+        add(A);
+        if (B.n == 0) break;
+        add(B);
+      }
+      __syncthreads();
+      }
+    }
+    {  // (every d[i] is assigned anew: the old values must not stay alive through the rounds above)
+      const int32_t len = more ? (int32_t)(next.end - next.begin) : 0;
+      const float* __restrict__ src = dense + next.begin;
+#pragma unroll
+      for (int i = 0; i < kElems; ++i) {
+        const int e = tid + i * kPartThreads;
+        d[i] = e < len ? __builtin_nontemporal_load(src + e) : 0.0f;
+      }
+    }
+    if (total > 0) {
+#pragma unroll
+      for (int k = 0; k < kElems; ++k) {
+        const int e = tid + k * kPartThreads;
+        if (e < length) __builtin_nontemporal_store(sh.acc[e], range + e);
+      }
+    }
+    if (!more) break;
+    b = next_b;
+    blk = next;
+    __syncthreads();  // the accumulator and the tables are free again
   }
 }
 
@@ -2096,7 +2164,7 @@ __global__ __launch_bounds__(kPartClearThreads) void clear_parts_kernel(float* _
   const int32_t length = (int32_t)(blk.end - blk.begin);
 #pragma unroll
   for (int k = 0; k < kWords; ++k) sh.bitmap[tid + k * kPartClearThreads] = 0;
-  const int total = located_pairs(sh, p, num_payloads, region, found, tid);
+  const int total = located_pairs(sh, p, num_payloads, region, found, (int)blockIdx.x, tid);
   if (total == 0) return;
   for (int w = 0; w < num_payloads; ++w) {
     const int n = sh.begin[w + 1] - sh.begin[w];
@@ -2504,7 +2572,7 @@ hipError_t launch_merge_regions(float* dense, const RegionPayloads& p, int32_t n
 
 static void launch_locate_parts(const RegionPayloads& p, int32_t num, const int64_t* out_offsets_dev,
                                 const MergeBlock* parts, int32_t num_parts, int2* found, hipStream_t stream) {
-  const int64_t waves = (int64_t)num_parts * num;
+  const int64_t waves = ceil_div(num_parts, 7) * num;  // seven parts of one payload per wavefront
   hipLaunchKernelGGL(locate_parts_kernel, dim3((unsigned)ceil_div(waves, kFlatThreads / 64)), dim3(kFlatThreads), 0,
                      stream, p, num, out_offsets_dev, parts, num_parts, found);
 }
@@ -2514,8 +2582,16 @@ hipError_t launch_merge_parts(float* dense, const RegionPayloads& p, int32_t num
                               hipStream_t stream) {
   if (num <= 0 || num_parts <= 0) return hipSuccess;
   launch_locate_parts(p, num, out_offsets_dev, parts, num_parts, static_cast<int2*>(found), stream);
-  hipLaunchKernelGGL(merge_parts_kernel, dim3((unsigned)num_parts), dim3(kPartThreads), 0, stream, dense, p, num,
-                     out_offsets_dev, parts, static_cast<const int2*>(found), scale, scaled ? 1 : 0);
+  static int compute_units = 0;  // one workgroup of this kernel fits a compute unit
+  if (compute_units <= 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&compute_units, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || compute_units <= 0)
+      compute_units = 256;
+  }
+  const int grid = num_parts < compute_units ? num_parts : compute_units;
+  hipLaunchKernelGGL(merge_parts_kernel, dim3((unsigned)grid), dim3(kPartThreads), 0, stream, dense, p, num,
+                     out_offsets_dev, parts, num_parts, static_cast<const int2*>(found), scale, scaled ? 1 : 0);
   return hipGetLastError();
 }
 
