@@ -4,11 +4,13 @@
 A step is one pass of the whole path for one worker of an N-worker job on a
 paper-shaped gradient set: dgc_compress of the worker's gradient (clipping norm
 when the configuration clips, sampled thresholds, streaming update + mask,
-emit = extraction + residual + factor masking), then
-dgc_decompress_accumulate_regions of N payloads (the fresh one and N - 1 from
-other seeded, correlated streams) into the dense aggregate (merged by element
-range on chip, workers in order, no float atomics), then
-dgc_dense_clear_regions to return the aggregate to zero.  Four workers' states
+emit = extraction + residual + factor masking), then the dense aggregate of N
+payloads (the fresh one and N - 1 from other seeded, correlated streams),
+merged by element range on chip, workers in order, no float atomics:
+dgc_decompress_replace_regions writes it in place of the previous step's
+aggregate in one launch (--receive accumulate_clear: the same result from
+dgc_decompress_accumulate_regions into a zero buffer followed by
+dgc_dense_clear_regions).  Four workers' states
 (g, u, v) rotate so that no step finds its operands in the 256 MB last-level
 cache.  Inputs are generated on the host once, seeded, and are resident in HBM
 before the timed region.
@@ -86,7 +88,7 @@ def run_warmup_schedule(args):
     u = torch.zeros(n, device=dev)
     v = torch.zeros(n, device=dev)
     dense = torch.zeros(n, device=dev)
-    fresh = dgc.alloc_payload(dev)
+    fresh = [dgc.alloc_payload(dev) for _ in range(2)]
     stage_of = [min(i, 4) for i in range(iters)]
     others = []                                   # per stage: N - 1 payloads of that density
     gw = [torch.from_numpy(S.correlated_gradient(gs, seed, 100 + w, 0, shared, scales=scales)).to(dev)
@@ -105,24 +107,32 @@ def run_warmup_schedule(args):
     del gw
     u.zero_()
     v.zero_()
-    prepared = {}
+    replace = args.receive == "replace"
+    plists = {}
     for stage in range(5):
         o = others[stage]
-        plist = B.PayloadList([fresh[0]] + [x[0] for x in o], [fresh[1]] + [x[1] for x in o],
-                              [fresh[2]] + [x[2] for x in o])
         for q in range(2):
-            prepared[(stage, q)] = B.PreparedStep(dgc, g_pool[q], u, v, fresh, plist, dense)
+            f = fresh[q]
+            plists[(stage, q)] = B.PayloadList([f[0]] + [x[0] for x in o], [f[1]] + [x[1] for x in o],
+                                               [f[2]] + [x[2] for x in o])
+    prepared = []                                  # iteration i: gradient and payload buffer i & 1
+    for i in range(iters):
+        before = (i - 1) % iters
+        prepared.append(B.PreparedStep(dgc, g_pool[i & 1], u, v, fresh[i & 1], plists[(stage_of[i], i & 1)], dense,
+                                       previous=plists[(stage_of[before], before & 1)]))
+    for p in prepared:
+        p.receive = p.replace if replace else p.accumulate_and_clear
 
     def one_pass(events=None):
         for i in range(iters):
             dgc.dgc_set_iteration_density(i)
-            p = prepared[(stage_of[i], i & 1)]
+            p = prepared[i]
             if events is not None:
                 events[i][0].record()
             p.compress(i)
             if events is not None:
                 events[i][1].record()
-            p.accumulate_and_clear()
+            p.receive()
             if events is not None:
                 events[i][2].record()
 
@@ -140,7 +150,8 @@ def run_warmup_schedule(args):
     torch.cuda.synchronize()
     per_iteration = [{"iteration": i, "density": [0.25, 0.0625, 0.015625, 0.004, 0.001][stage_of[i]],
                       "compress_us": round(ev[i][0].elapsed_time(ev[i][1]) * 1e3, 1),
-                      "accumulate_and_clear_us": round(ev[i][1].elapsed_time(ev[i][2]) * 1e3, 1)}
+                      "replace_us" if replace else "accumulate_and_clear_us":
+                          round(ev[i][1].elapsed_time(ev[i][2]) * 1e3, 1)}
                      for i in range(6)]
     out = {
         "metric": "dense gradient elements/s for compress+decompress",
@@ -155,8 +166,9 @@ def run_warmup_schedule(args):
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": WARMUP_DESCRIPTION + "; step = one iteration: compress one worker + accumulate 8 "
-                               "payloads + sparse clear; workspace with staging arrays",
+        "config": {"workload": WARMUP_DESCRIPTION + "; step = one iteration: compress one worker + " +
+                               ("aggregate of 8 payloads written in place of the previous one" if replace else
+                                "accumulate 8 payloads + sparse clear") + "; workspace with staging arrays",
                    "elements": n, "tensors": len(gs.sizes), "workers_accumulated": N},
         "ms_per_20_iterations": round(ms_per_step * iters, 3),
         "first_iterations": per_iteration,
@@ -177,6 +189,9 @@ def parse_args():
                     help="switch the Section 5 re-threshold on (dgc_config.refine_alpha); off by default")
     ap.add_argument("--sorted", action="store_true",
                     help="emit every tensor's pairs in ascending index order (DGC_FLAG_SORTED_OUTPUT)")
+    ap.add_argument("--receive", choices=["replace", "accumulate_clear"], default="replace",
+                    help="receive side of a step: dgc_decompress_accumulate_regions + dgc_dense_clear_regions, or "
+                         "dgc_decompress_replace_regions (the aggregate written in place of the previous one)")
     ap.add_argument("--rotate", type=int, default=4,
                     help="independent (g, u, v) sets the steps rotate through; 4 keeps every step's operands out of the "
                          "last-level cache (the default and the headline), 1 shows the cache-resident case")
@@ -292,20 +307,26 @@ def main():
     dense = torch.zeros(n, device=dev)
 
     # every argument marshalled once: worker r with gradient slot q
+    replace = args.receive == "replace"
+    if replace and ROTATE < 2:
+        print("--receive replace needs --rotate >= 2: the previous step's payload must stay intact", file=sys.stderr)
+        sys.exit(2)
     prepared = {}
+    plists = [B.PayloadList([f[0]] + [o[0] for o in others], [f[1]] + [o[1] for o in others],
+                            [f[2]] + [o[2] for o in others]) for f in fresh]
     for r in range(ROTATE):
-        f = fresh[r]
-        plist = B.PayloadList([f[0]] + [o[0] for o in others], [f[1]] + [o[1] for o in others],
-                              [f[2]] + [o[2] for o in others])
         for q in range(ROTATE):
-            prepared[(r, q)] = B.PreparedStep(dgc, g_pool[q], u[r], v[r], f, plist, dense)
+            prepared[(r, q)] = B.PreparedStep(dgc, g_pool[q], u[r], v[r], fresh[r], plists[r], dense,
+                                              previous=plists[(r - 1) % ROTATE])
+    for p in prepared.values():
+        p.receive = p.replace if replace else p.accumulate_and_clear
 
     def step(i):
         r = i % ROTATE
         it = i // ROTATE
         p = prepared[(r, (r + it) % ROTATE)]
         p.compress(it)
-        p.accumulate_and_clear()
+        p.receive()
 
     # ---- warm-up, then the timed region -------------------------------------------
     for i in range(args.warmup):
@@ -346,7 +367,7 @@ def main():
             ev[k][0].record()
             p.compress(it)
             ev[k][1].record()
-            p.accumulate_and_clear()
+            p.receive()
             ev[k][2].record()
         torch.cuda.synchronize()
         profiled_ms = (time.perf_counter() - t1) / args.steps * 1e3
@@ -393,7 +414,7 @@ def main():
             "select_kernel_us": round(select_ms / calls * 1e3, 2),
             "stream_kernel_us": round(stream_avg_ms * 1e3, 2),
             "emit_kernel_us": round(emit_ms / calls * 1e3, 2),
-            "accumulate_and_clear_us": round(acc * 1e3, 2),
+            "replace_us" if replace else "accumulate_and_clear_us": round(acc * 1e3, 2),
             "ms_per_step_with_events": round(profiled_ms, 5),
         }
         if clip:
@@ -416,8 +437,9 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": description + f"; step = compress one worker + accumulate {n_workers} payloads + "
-                                      "sparse clear",
+            "workload": description + (f"; step = compress one worker + aggregate of {n_workers} payloads written in "
+                                       "place of the previous one" if replace else
+                                       f"; step = compress one worker + accumulate {n_workers} payloads + sparse clear"),
             "elements": n,
             "tensors": len(gs.sizes),
             "workers_accumulated": n_workers,

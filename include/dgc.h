@@ -248,6 +248,31 @@ dgc_status dgc_decompress_accumulate_regions(dgc_handle* h, float* dense, int32_
                                              size_t workspace_bytes, void* stream);
 
 /*
+ * The aggregate of an iteration written in place of the one before (Algorithm 3, the
+ * all-reduce line: G_t is a fresh sum of the N sparse gradients every iteration):
+ *       dense <- sum over the given payloads, zero wherever none of them has an index,
+ * provided that `dense` is zero outside the indices of the `previous` payloads (typically
+ * those of the previous call, whose index and count arrays must still be intact;
+ * num_previous = 0: `dense` is zero everywhere, as before the first iteration).  One launch
+ * does what dgc_dense_clear_regions followed by dgc_decompress_accumulate_regions does: up
+ * to a density of 0.5 % the sums start from zero instead of the scattered contents of
+ * `dense`, and indices of the previous payloads that do not recur are set to zero; above
+ * (and in the call that follows one above it, whose previous payloads are long), the whole
+ * of `dense` is written once and read never, and `previous` is ignored.
+ * Workers are added in the order given; the result is bit for bit that of clearing and
+ * accumulating.  Arguments and the regions' layout as for dgc_decompress_accumulate_regions;
+ * the previous payloads have the same layout.
+ */
+dgc_status dgc_decompress_replace_regions(dgc_handle* h, float* dense, int32_t num_payloads,
+                                          const int32_t* const* idx_ptrs_host,
+                                          const float* const* val_ptrs_host,
+                                          const int32_t* const* count_ptrs_host, int32_t num_previous,
+                                          const int32_t* const* previous_idx_ptrs_host,
+                                          const int32_t* const* previous_count_ptrs_host,
+                                          const int64_t* out_offsets_host, void* workspace,
+                                          size_t workspace_bytes, void* stream);
+
+/*
  * dense[idx] = 0 for every pair of the given region-layout payloads: returns a
  * dense aggregate to all-zero after it has been consumed at the cost of the
  * payload size instead of a full fill.  Arguments as above.  Above a density of 0.5 %

@@ -41,7 +41,8 @@ EXPORTS = [
     "dgc_config_default", "dgc_status_string", "dgc_create", "dgc_destroy", "dgc_set_density",
     "dgc_set_warmup_schedule", "dgc_set_warmup_stage_length", "dgc_set_iteration_density", "dgc_query_plan", "dgc_workspace_bytes", "dgc_workspace_bytes_warmup",
     "dgc_recommended_payload_layout", "dgc_compress", "dgc_get_diagnostics",
-    "dgc_decompress_accumulate", "dgc_decompress_accumulate_regions", "dgc_dense_clear_regions",
+    "dgc_decompress_accumulate", "dgc_decompress_accumulate_regions", "dgc_decompress_replace_regions",
+    "dgc_dense_clear_regions",
     "dgc_version", "dgc_last_error_string", "dgc_profile_enable", "dgc_profile_collect",
     "dgc_profile_disable", "dgc_sparse_sgd_apply", "dgc_sparse_sgd_apply_regions",
     "dgc_encode_max_entries", "dgc_encode", "dgc_decode_accumulate", "dgc_profile_stream_ceiling",
@@ -129,6 +130,9 @@ def load() -> C.CDLL:
     lib.dgc_decompress_accumulate_regions.restype = i32
     lib.dgc_decompress_accumulate_regions.argtypes = [vp, vp, i32, P(vp), P(vp), P(vp), P(i64), vp,
                                                       C.c_size_t, vp]
+    lib.dgc_decompress_replace_regions.restype = i32
+    lib.dgc_decompress_replace_regions.argtypes = [vp, vp, i32, P(vp), P(vp), P(vp), i32, P(vp), P(vp), P(i64), vp,
+                                                   C.c_size_t, vp]
     lib.dgc_dense_clear_regions.restype = i32
     lib.dgc_dense_clear_regions.argtypes = [vp, vp, i32, P(vp), P(vp), P(i64), vp, C.c_size_t, vp]
     lib.dgc_sparse_sgd_apply.restype = i32
@@ -330,6 +334,15 @@ class Dgc:
             _ptr_array(count_list), self._layout_c, self._ws_ptr, self._ws_bytes, _stream()),
             "dgc_decompress_accumulate_regions")
 
+    def dgc_decompress_replace_regions(self, dense, idx_list, val_list, count_list, previous_idx_list=(),
+                                       previous_count_list=()) -> None:
+        self.ensure_workspace(dense.device)
+        m = len(previous_idx_list)
+        _check(self.lib.dgc_decompress_replace_regions(
+            self._h, _ptr(dense), len(idx_list), _ptr_array(idx_list), _ptr_array(val_list), _ptr_array(count_list),
+            m, _ptr_array(previous_idx_list) if m else None, _ptr_array(previous_count_list) if m else None,
+            self._layout_c, self._ws_ptr, self._ws_bytes, _stream()), "dgc_decompress_replace_regions")
+
     def dgc_sparse_sgd_apply(self, theta, learning_rate: float, idx_list, val_list, counts: Sequence[int],
                              diag_flags=None) -> None:
         _check(self.lib.dgc_sparse_sgd_apply(self._h, _ptr(theta), int(theta.numel()), float(learning_rate),
@@ -387,9 +400,9 @@ class PreparedStep:
     """One worker's compress call and the accumulate / clear calls that follow it, with every
     argument marshalled ahead of time (pointers, layout, workspace, stream)."""
 
-    def __init__(self, dgc: "Dgc", g, u, v, payload, accumulate: PayloadList, dense):
+    def __init__(self, dgc: "Dgc", g, u, v, payload, accumulate: PayloadList, dense, previous: PayloadList = None):
         dgc.ensure_workspace(g.device)
-        self.keep = (g, u, v, payload, accumulate, dense)
+        self.keep = (g, u, v, payload, accumulate, dense, previous)
         lib, h = dgc.lib, dgc._h
         stream = C.c_void_p(_stream())
         out_idx, out_val, out_counts, out_thr = payload
@@ -415,8 +428,17 @@ class PreparedStep:
             if st != DGC_OK:
                 _check(st, "dgc_dense_clear_regions")
 
+        def replace() -> None:
+            st = lib.dgc_decompress_replace_regions(*rargs)
+            if st != DGC_OK:
+                _check(st, "dgc_decompress_replace_regions")
+
+        prev = previous if previous is not None else accumulate
+        rargs = (h, C.c_void_p(_ptr(dense)), C.c_int32(accumulate.n), accumulate.idx, accumulate.val,
+                 accumulate.counts, C.c_int32(prev.n), prev.idx, prev.counts, dgc._layout_c, ws, wsb, stream)
         self.compress = compress
         self.accumulate_and_clear = accumulate_and_clear
+        self.replace = replace
 
 
 def gather_payload(layout: Sequence[int], out_idx, out_val, out_counts, sort: bool = True):

@@ -29,6 +29,7 @@ struct dgc_handle {
   std::vector<MergeBlock> merge_blocks;  // work list of the receive side: ranges of several emit parts
   std::vector<MergeBlock> part_blocks;   // the same with one emit part per range (warm-up densities)
   bool layout_may_overflow = true;       // some region of the registered layout is smaller than its tensor
+  double last_replace_density = 0.0;     // density at the last dgc_decompress_replace_regions call
   WorkspaceLayout lay{};
   // what the bound workspace currently holds
   void* ws = nullptr;
@@ -665,7 +666,7 @@ dgc_status dgc_get_diagnostics(dgc_handle* h, const void* workspace, dgc_diagnos
 }
 
 namespace {
-enum class ScatterOp { kAccumulate, kClear, kSgd };
+enum class ScatterOp { kAccumulate, kClear, kSgd, kReplace };
 }
 
 static dgc_status scatter_pairs(dgc_handle* h, float* dense, int64_t n, int32_t num_payloads,
@@ -729,9 +730,20 @@ static dgc_status scatter_regions(dgc_handle* h, float* dense, int32_t num_paylo
                                   const float* const* val_ptrs_host,
                                   const int32_t* const* count_ptrs_host,
                                   const int64_t* out_offsets_host, void* workspace,
-                                  size_t workspace_bytes, void* stream_, ScatterOp op, float scale) {
+                                  size_t workspace_bytes, void* stream_, ScatterOp op, float scale,
+                                  int32_t num_old = 0, const int32_t* const* old_idx_host = nullptr,
+                                  const int32_t* const* old_count_host = nullptr) {
   const bool clear = op == ScatterOp::kClear;
   const bool sgd = op == ScatterOp::kSgd;
+  const bool replace = op == ScatterOp::kReplace;
+  if (num_old < 0 || (num_old > 0 && (!old_idx_host || !old_count_host))) return DGC_ERR_INVALID_ARG;
+  if (num_old > kMaxPayloads) return DGC_ERR_CAPACITY;
+  RegionPayloads was{};
+  for (int32_t w = 0; w < num_old; ++w) {
+    if (!old_idx_host[w] || !old_count_host[w]) return DGC_ERR_INVALID_ARG;
+    was.idx[w] = old_idx_host[w];
+    was.counts[w] = old_count_host[w];
+  }
   if (!h || !dense || !idx_ptrs_host || !count_ptrs_host) return DGC_ERR_INVALID_ARG;
   if (!clear && !val_ptrs_host) return DGC_ERR_INVALID_ARG;
   if (num_payloads < 1) return DGC_ERR_INVALID_ARG;
@@ -755,7 +767,11 @@ static dgc_status scatter_regions(dgc_handle* h, float* dense, int32_t num_paylo
   // workgroup merges the pairs of a range of up to 128 Ki elements in LDS and touches only
   // the elements that occur; at warm-up densities a workgroup keeps one emit part's whole
   // range of `dense` in LDS.
-  const bool few = h->cfg.density <= kMergeMaxDensity;
+  // (Replacing an aggregate that was built at a warm-up density: its index lists are long, and
+  // writing the whole of `dense` once, which needs none of them, is the cheaper way.)
+  const bool few = h->cfg.density <= kMergeMaxDensity &&
+                   !(replace && num_old > 0 && h->last_replace_density > kMergeMaxDensity);
+  if (replace) h->last_replace_density = h->cfg.density;
   const MergeBlock* parts = at<MergeBlock>(workspace, h->lay.part_blocks);
   const int32_t num_parts = (int32_t)h->part_blocks.size();
   void* found = at<char>(workspace, h->lay.part_found);
@@ -775,11 +791,13 @@ static dgc_status scatter_regions(dgc_handle* h, float* dense, int32_t num_paylo
       return DGC_ERR_HIP;
     }
   } else if (few) {
-    if (!hip_ok(launch_merge_regions(dense, p, num_payloads, oo, at<MergeBlock>(workspace, h->lay.merge_blocks),
-                                     (int32_t)h->merge_blocks.size(), sgd, scale, stream),
+    if (!hip_ok(launch_merge_regions(dense, p, num_payloads, replace ? &was : nullptr, num_old, oo,
+                                     at<MergeBlock>(workspace, h->lay.merge_blocks), (int32_t)h->merge_blocks.size(),
+                                     sgd, scale, stream),
                 "launch merge kernel"))
       return DGC_ERR_HIP;
-  } else if (!hip_ok(launch_merge_parts(dense, p, num_payloads, oo, parts, num_parts, found, sgd, scale, stream),
+  } else if (!hip_ok(launch_merge_parts(dense, p, num_payloads, oo, parts, num_parts, found, replace, sgd, scale,
+                                        stream),
                      "launch merge kernel")) {
     return DGC_ERR_HIP;
   }
@@ -794,6 +812,19 @@ dgc_status dgc_decompress_accumulate_regions(dgc_handle* h, float* dense, int32_
                                              size_t workspace_bytes, void* stream) {
   return scatter_regions(h, dense, num_payloads, idx_ptrs_host, val_ptrs_host, count_ptrs_host,
                          out_offsets_host, workspace, workspace_bytes, stream, ScatterOp::kAccumulate, 0.0f);
+}
+
+dgc_status dgc_decompress_replace_regions(dgc_handle* h, float* dense, int32_t num_payloads,
+                                          const int32_t* const* idx_ptrs_host,
+                                          const float* const* val_ptrs_host,
+                                          const int32_t* const* count_ptrs_host, int32_t num_previous,
+                                          const int32_t* const* previous_idx_ptrs_host,
+                                          const int32_t* const* previous_count_ptrs_host,
+                                          const int64_t* out_offsets_host, void* workspace,
+                                          size_t workspace_bytes, void* stream) {
+  return scatter_regions(h, dense, num_payloads, idx_ptrs_host, val_ptrs_host, count_ptrs_host,
+                         out_offsets_host, workspace, workspace_bytes, stream, ScatterOp::kReplace, 0.0f,
+                         num_previous, previous_idx_ptrs_host, previous_count_ptrs_host);
 }
 
 dgc_status dgc_sparse_sgd_apply_regions(dgc_handle* h, float* theta, float learning_rate,

@@ -272,12 +272,12 @@ hipError_t launch_scatter_regions(float* dense, int64_t n, const RegionPayloads&
                                   int64_t total_capacity, ScatterMode mode, float scale,
                                   uint32_t* diag_flags, hipStream_t stream);
 
-hipError_t launch_merge_regions(float* dense, const RegionPayloads& p, int32_t num, const int64_t* out_offsets_dev,
-                                const MergeBlock* blocks, int32_t num_blocks, bool scaled, float scale,
-                                hipStream_t stream);
+hipError_t launch_merge_regions(float* dense, const RegionPayloads& p, int32_t num, const RegionPayloads* old,
+                                int32_t num_old, const int64_t* out_offsets_dev, const MergeBlock* blocks,
+                                int32_t num_blocks, bool scaled, float scale, hipStream_t stream);
 hipError_t launch_merge_parts(float* dense, const RegionPayloads& p, int32_t num, const int64_t* out_offsets_dev,
-                              const MergeBlock* parts, int32_t num_parts, void* found, bool scaled, float scale,
-                              hipStream_t stream);
+                              const MergeBlock* parts, int32_t num_parts, void* found, bool replace, bool scaled,
+                              float scale, hipStream_t stream);
 hipError_t launch_clear_parts(float* dense, const RegionPayloads& p, int32_t num, const int64_t* out_offsets_dev,
                               const MergeBlock* parts, int32_t num_parts, void* found, hipStream_t stream);
 hipError_t launch_encode(const EncodeArgs& a, int64_t widest_region, int32_t total_blocks, hipStream_t stream);

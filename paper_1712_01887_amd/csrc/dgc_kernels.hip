@@ -1678,14 +1678,29 @@ struct MergeShared {
 
 // `scale` multiplies every value first (1 for the plain sum; -learning rate for the SGD
 // apply, where `dense` is the parameter vector).
+//
+// REPLACE: `dense` becomes the sum of the payloads instead of growing by it.  It holds
+// the sum of an earlier set of payloads (`old`: their index lists are all that is needed),
+// i.e. zero wherever none of those has an index.  The accumulator then starts from zero,
+// which saves the scattered reads of `dense`, and an index of the earlier set that is in
+// none of the new payloads gets a zero: one launch instead of a clear and an accumulate.
+struct OldLists {
+  int32_t begin[kMaxPayloads + 1];
+  const int32_t* idx_at[kMaxPayloads];
+  const float* val_at[kMaxPayloads];  // unused
+};
+
+template <bool REPLACE>
 __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __restrict__ dense, RegionPayloads p,
-                                                                      int32_t num_payloads,
+                                                                      int32_t num_payloads, RegionPayloads old,
+                                                                      int32_t num_old,
                                                                       const int64_t* __restrict__ out_offsets,
                                                                       const MergeBlock* __restrict__ blocks,
                                                                       float scale, int32_t scaled) {
   constexpr int kPerThread = kMergeCap / kMergeThreads;
   constexpr int kWordsPerThread = kMergeMaxRange / 32 / kMergeThreads;
   __shared__ MergeShared sh;
+  __shared__ OldLists was;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
@@ -1697,7 +1712,21 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
 #pragma unroll
   for (int k = 0; k < kWordsPerThread; ++k) sh.bitmap[tid * kWordsPerThread + k] = 0;
   const int total = locate_pairs(sh, p, num_payloads, region, cap, blk, tid, kMergeWaves);
-  if (total == 0) return;
+  const int old_total = (REPLACE && num_old > 0) ? locate_pairs(was, old, num_old, region, cap, blk, tid, kMergeWaves) : 0;
+  if (total == 0 && old_total == 0) return;
+  // Whether the accumulator may start from zero: the earlier set's indices of this range fit
+  // the registers too.  Otherwise they are cleared in `dense` first and the sum is added
+  // to what `dense` holds then, as without REPLACE.
+  const bool from_zero = REPLACE && total <= kMergeCap && old_total <= kMergeCap;
+  if (REPLACE && !from_zero) {
+    for (int q = tid; q < old_total; q += kMergeThreads) {
+      const int w = payload_of(was.begin, num_old, q);
+      const int64_t r = (int64_t)was.idx_at[w][q - was.begin[w]] - blk.begin;
+      if (r >= 0 && r < length) dense[blk.begin + r] = 0.0f;
+    }
+    __syncthreads();  // the zeros are in place before any thread of the workgroup reads `dense`
+  }
+  if (total == 0 && !from_zero) return;
 
   if (total <= kMergeCap) {
     // this thread's pairs: payload, index relative to the range (-1: none), value
@@ -1728,7 +1757,28 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
         }
       }
     }
+    // the earlier set's indices of this range (loads in flight with the pairs above)
+    int32_t was_rel[kPerThread];
+    if (from_zero) {
+#pragma unroll
+      for (int k = 0; k < kPerThread; ++k) {
+        const int q = tid + k * kMergeThreads;
+        was_rel[k] = -1;
+        if (q < old_total) {
+          const int w = payload_of(was.begin, num_old, q);
+          const int64_t r = (int64_t)was.idx_at[w][q - was.begin[w]] - blk.begin;
+          if (r >= 0 && r < length) was_rel[k] = (int32_t)r;
+        }
+      }
+    }
     __syncthreads();
+    if (from_zero) {  // an index of the earlier set that no new payload has becomes zero
+#pragma unroll
+      for (int k = 0; k < kPerThread; ++k)
+        if (was_rel[k] >= 0 && !((sh.bitmap[was_rel[k] >> 5] >> (was_rel[k] & 31)) & 1u))
+          dense[blk.begin + was_rel[k]] = 0.0f;
+      if (total == 0) return;
+    }
     {
       uint32_t mine = 0, c[kWordsPerThread];
 #pragma unroll
@@ -1759,7 +1809,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
       if (rel[k] >= 0) {
         const uint32_t word = sh.bitmap[rel[k] >> 5];
         id[k] = (int)(sh.prefix[rel[k] >> 5] + (uint32_t)__popc(word & ((1u << (rel[k] & 31)) - 1u)));
-        sh.acc[id[k]] = dense[blk.begin + rel[k]];  // pairs of several payloads with one index write the same
+        // pairs of several payloads with one index write the same
+        sh.acc[id[k]] = from_zero ? 0.0f : dense[blk.begin + rel[k]];
       }
     }
     __syncthreads();
@@ -1975,6 +2026,9 @@ struct PartShared {
   const float* val_at[kMaxPayloads];
 };
 
+// REPLACE: `dense` becomes the sum of the payloads: the accumulator starts from zero instead of
+// the range of `dense`, and every range is written, also one that no pair falls into.
+template <bool REPLACE>
 __global__ __launch_bounds__(kPartThreads) void merge_parts_kernel(float* __restrict__ dense, RegionPayloads p,
                                                                    int32_t num_payloads,
                                                                    const int64_t* __restrict__ out_offsets,
@@ -1994,7 +2048,7 @@ __global__ __launch_bounds__(kPartThreads) void merge_parts_kernel(float* __rest
   MergeBlock blk = blocks[b];
   float d[kElems];
   {
-    const int32_t len = (int32_t)(blk.end - blk.begin);
+    const int32_t len = REPLACE ? 0 : (int32_t)(blk.end - blk.begin);
     const float* __restrict__ src = dense + blk.begin;
 #pragma unroll
     for (int i = 0; i < kElems; ++i) {
@@ -2118,7 +2172,7 @@ __global__ __launch_bounds__(kPartThreads) void merge_parts_kernel(float* __rest
       }
     }
     {  // (every d[i] is assigned anew: the old values must not stay alive through the rounds above)
-      const int32_t len = more ? (int32_t)(next.end - next.begin) : 0;
+      const int32_t len = (more && !REPLACE) ? (int32_t)(next.end - next.begin) : 0;
       const float* __restrict__ src = dense + next.begin;
 #pragma unroll
       for (int i = 0; i < kElems; ++i) {
@@ -2131,6 +2185,12 @@ __global__ __launch_bounds__(kPartThreads) void merge_parts_kernel(float* __rest
       for (int k = 0; k < kElems; ++k) {
         const int e = tid + k * kPartThreads;
         if (e < length) __builtin_nontemporal_store(sh.acc[e], range + e);
+      }
+    } else if (REPLACE) {
+#pragma unroll
+      for (int k = 0; k < kElems; ++k) {
+        const int e = tid + k * kPartThreads;
+        if (e < length) __builtin_nontemporal_store(0.0f, range + e);
       }
     }
     if (!more) break;
@@ -2561,12 +2621,16 @@ hipError_t launch_scatter_regions(float* dense, int64_t n, const RegionPayloads&
   return hipGetLastError();
 }
 
-hipError_t launch_merge_regions(float* dense, const RegionPayloads& p, int32_t num, const int64_t* out_offsets_dev,
-                                const MergeBlock* blocks, int32_t num_blocks, bool scaled, float scale,
-                                hipStream_t stream) {
+hipError_t launch_merge_regions(float* dense, const RegionPayloads& p, int32_t num, const RegionPayloads* old,
+                                int32_t num_old, const int64_t* out_offsets_dev, const MergeBlock* blocks,
+                                int32_t num_blocks, bool scaled, float scale, hipStream_t stream) {
   if (num <= 0 || num_blocks <= 0) return hipSuccess;
-  hipLaunchKernelGGL(merge_regions_kernel, dim3((unsigned)num_blocks), dim3(kMergeThreads), 0, stream, dense, p, num,
-                     out_offsets_dev, blocks, scale, scaled ? 1 : 0);
+  if (old)  // dense becomes the sum (it holds the sum of `old` now)
+    hipLaunchKernelGGL(merge_regions_kernel<true>, dim3((unsigned)num_blocks), dim3(kMergeThreads), 0, stream, dense, p,
+                       num, *old, num_old, out_offsets_dev, blocks, scale, scaled ? 1 : 0);
+  else
+    hipLaunchKernelGGL(merge_regions_kernel<false>, dim3((unsigned)num_blocks), dim3(kMergeThreads), 0, stream, dense, p,
+                       num, p, 0, out_offsets_dev, blocks, scale, scaled ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -2578,8 +2642,8 @@ static void launch_locate_parts(const RegionPayloads& p, int32_t num, const int6
 }
 
 hipError_t launch_merge_parts(float* dense, const RegionPayloads& p, int32_t num, const int64_t* out_offsets_dev,
-                              const MergeBlock* parts, int32_t num_parts, void* found, bool scaled, float scale,
-                              hipStream_t stream) {
+                              const MergeBlock* parts, int32_t num_parts, void* found, bool replace, bool scaled,
+                              float scale, hipStream_t stream) {
   if (num <= 0 || num_parts <= 0) return hipSuccess;
   launch_locate_parts(p, num, out_offsets_dev, parts, num_parts, static_cast<int2*>(found), stream);
   static int compute_units = 0;  // one workgroup of this kernel fits a compute unit
@@ -2590,8 +2654,12 @@ hipError_t launch_merge_parts(float* dense, const RegionPayloads& p, int32_t num
       compute_units = 256;
   }
   const int grid = num_parts < compute_units ? num_parts : compute_units;
-  hipLaunchKernelGGL(merge_parts_kernel, dim3((unsigned)grid), dim3(kPartThreads), 0, stream, dense, p, num,
-                     out_offsets_dev, parts, num_parts, static_cast<const int2*>(found), scale, scaled ? 1 : 0);
+  if (replace)
+    hipLaunchKernelGGL(merge_parts_kernel<true>, dim3((unsigned)grid), dim3(kPartThreads), 0, stream, dense, p, num,
+                       out_offsets_dev, parts, num_parts, static_cast<const int2*>(found), scale, scaled ? 1 : 0);
+  else
+    hipLaunchKernelGGL(merge_parts_kernel<false>, dim3((unsigned)grid), dim3(kPartThreads), 0, stream, dense, p, num,
+                       out_offsets_dev, parts, num_parts, static_cast<const int2*>(found), scale, scaled ? 1 : 0);
   return hipGetLastError();
 }
 
