@@ -1621,6 +1621,53 @@ __device__ __forceinline__ void wave_equal_range(const int32_t* __restrict__ L, 
   out_hi = __shfl(lo, 32);
 }
 
+// The same for two lists at once, with the probes of both in flight together (`safe` is any
+// readable word: it is read in place of a probe that has nothing left to ask).
+__device__ __forceinline__ void wave_equal_range2(const int32_t* __restrict__ L0, int m0, const int32_t* __restrict__ L1,
+                                                  int m1, const int32_t* __restrict__ safe, int32_t xa, int32_t xb,
+                                                  int lane, int& lo_0, int& hi_0, int& lo_1, int& hi_1) {
+  const int half = lane >> 5;
+  const int sub = lane & 31;
+  const int32_t x = half ? xb : xa;
+  const int32_t* __restrict__ A = m0 > 0 ? L0 : safe;
+  const int32_t* __restrict__ B = m1 > 0 ? L1 : safe;
+  int lo0 = 0, hi0 = m0, lo1 = 0, hi1 = m1;
+  while (__ballot(hi0 > lo0 || hi1 > lo1)) {
+    const int span0 = hi0 - lo0, span1 = hi1 - lo1;
+    const int step0 = (span0 + 31) >> 5, step1 = (span1 + 31) >> 5;
+    const int pos0 = lo0 + sub * step0, pos1 = lo1 + sub * step1;
+    const bool ask0 = span0 > 0 && pos0 < hi0, ask1 = span1 > 0 && pos1 < hi1;
+    const int32_t v0 = A[ask0 ? pos0 : 0];
+    const int32_t v1 = B[ask1 ? pos1 : 0];
+    const unsigned long long votes0 = __ballot(ask0 && v0 < x);
+    const unsigned long long votes1 = __ballot(ask1 && v1 < x);
+    const int c0 = __popc((uint32_t)(votes0 >> (32 * half)));
+    const int c1 = __popc((uint32_t)(votes1 >> (32 * half)));
+    if (span0 > 0) {
+      if (c0 == 0) {
+        hi0 = lo0;
+      } else {
+        const int next = lo0 + c0 * step0;
+        lo0 = lo0 + (c0 - 1) * step0 + 1;
+        hi0 = next < hi0 ? next : hi0;
+      }
+    }
+    if (span1 > 0) {
+      if (c1 == 0) {
+        hi1 = lo1;
+      } else {
+        const int next = lo1 + c1 * step1;
+        lo1 = lo1 + (c1 - 1) * step1 + 1;
+        hi1 = next < hi1 ? next : hi1;
+      }
+    }
+  }
+  lo_0 = __shfl(lo0, 0);
+  hi_0 = __shfl(lo0, 32);
+  lo_1 = __shfl(lo1, 0);
+  hi_1 = __shfl(lo1, 32);
+}
+
 // Finds every payload's pairs inside [blk.begin, blk.end) and fills begin[], idx_at[] and
 // val_at[] (in LDS: a payload's pointers looked up per pair in the kernel's argument block
 // would put a load from memory in front of every pair load).
@@ -1652,6 +1699,66 @@ __device__ __forceinline__ int locate_pairs(Shared& sh, const RegionPayloads& p,
     }
   }
   __syncthreads();
+  return sh.begin[num_payloads];
+}
+
+// Two sets of payloads at once (the new ones and the previous ones of a replacing merge):
+// wavefront w searches payload w of both sets with the probes of the two searches in flight
+// together.  `total2` gets the second set's number of pairs, the first set's is returned.
+template <typename Shared, typename Shared2>
+__device__ __forceinline__ int locate_pairs2(Shared& sh, const RegionPayloads& p, int32_t num_payloads, Shared2& sh2,
+                                             const RegionPayloads& p2, int32_t num_payloads2, int64_t region,
+                                             int64_t cap, const MergeBlock& blk, const int32_t* __restrict__ safe,
+                                             int tid, int waves, int& total2) {
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int most = num_payloads > num_payloads2 ? num_payloads : num_payloads2;
+  for (int w = wave; w < most; w += waves) {
+    int64_t cnt = w < num_payloads ? (int64_t)p.counts[w][blk.tensor] : 0;
+    int64_t cnt2 = w < num_payloads2 ? (int64_t)p2.counts[w][blk.tensor] : 0;
+    if (cnt > cap) cnt = cap;
+    if (cnt < 0) cnt = 0;
+    if (cnt2 > cap) cnt2 = cap;
+    if (cnt2 < 0) cnt2 = 0;
+    const int32_t* __restrict__ list = w < num_payloads ? p.idx[w] + region : safe;
+    const int32_t* __restrict__ list2 = w < num_payloads2 ? p2.idx[w] + region : safe;
+    int lo, hi, lo2, hi2;
+    wave_equal_range2(list, (int)cnt, list2, (int)cnt2, safe, (int32_t)blk.begin, (int32_t)blk.end, lane, lo, hi, lo2,
+                      hi2);
+    if (lane == 0) {
+      if (w < num_payloads) {
+        sh.idx_at[w] = list + lo;
+        sh.val_at[w] = p.val[w] ? p.val[w] + region + lo : nullptr;
+        sh.begin[w + 1] = hi - lo;  // length for now
+      }
+      if (w < num_payloads2) {
+        sh2.idx_at[w] = list2 + lo2;
+        sh2.val_at[w] = nullptr;
+        sh2.begin[w + 1] = hi2 - lo2;
+      }
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int run = 0;
+    sh.begin[0] = 0;
+    for (int w = 0; w < num_payloads; ++w) {
+      const int len = sh.begin[w + 1];
+      sh.begin[w + 1] = run + len;
+      run += len;
+    }
+  }
+  if (tid == 64) {
+    int run = 0;
+    sh2.begin[0] = 0;
+    for (int w = 0; w < num_payloads2; ++w) {
+      const int len = sh2.begin[w + 1];
+      sh2.begin[w + 1] = run + len;
+      run += len;
+    }
+  }
+  __syncthreads();
+  total2 = sh2.begin[num_payloads2];
   return sh.begin[num_payloads];
 }
 
@@ -1711,8 +1818,11 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
   const int32_t length = (int32_t)(blk.end - blk.begin);  // <= kMergeMaxRange
 #pragma unroll
   for (int k = 0; k < kWordsPerThread; ++k) sh.bitmap[tid * kWordsPerThread + k] = 0;
-  const int total = locate_pairs(sh, p, num_payloads, region, cap, blk, tid, kMergeWaves);
-  const int old_total = (REPLACE && num_old > 0) ? locate_pairs(was, old, num_old, region, cap, blk, tid, kMergeWaves) : 0;
+  int old_total = 0;
+  const int total = (REPLACE && num_old > 0)
+                        ? locate_pairs2(sh, p, num_payloads, was, old, num_old, region, cap, blk,
+                                        reinterpret_cast<const int32_t*>(blocks), tid, kMergeWaves, old_total)
+                        : locate_pairs(sh, p, num_payloads, region, cap, blk, tid, kMergeWaves);
   if (total == 0 && old_total == 0) return;
   // Whether the accumulator may start from zero: the earlier set's indices of this range fit
   // the registers too.  Otherwise they are cleared in `dense` first and the sum is added
@@ -1729,6 +1839,18 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
   if (total == 0 && !from_zero) return;
 
   if (total <= kMergeCap) {
+    // the earlier set's indices of this range, asked for first and not looked at before the
+    // new pairs are in: their loads are in flight together with those of the pairs
+    int32_t was_idx[kPerThread];
+#pragma unroll
+    for (int k = 0; k < kPerThread; ++k) {
+      const int q = tid + k * kMergeThreads;
+      was_idx[k] = 0;
+      if (from_zero && q < old_total) {
+        const int w = payload_of(was.begin, num_old, q);
+        was_idx[k] = was.idx_at[w][q - was.begin[w]];
+      }
+    }
     // this thread's pairs: payload, index relative to the range (-1: none), value
     int pw[kPerThread];
     int32_t rel[kPerThread];
@@ -1757,26 +1879,14 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
         }
       }
     }
-    // the earlier set's indices of this range (loads in flight with the pairs above)
-    int32_t was_rel[kPerThread];
-    if (from_zero) {
-#pragma unroll
-      for (int k = 0; k < kPerThread; ++k) {
-        const int q = tid + k * kMergeThreads;
-        was_rel[k] = -1;
-        if (q < old_total) {
-          const int w = payload_of(was.begin, num_old, q);
-          const int64_t r = (int64_t)was.idx_at[w][q - was.begin[w]] - blk.begin;
-          if (r >= 0 && r < length) was_rel[k] = (int32_t)r;
-        }
-      }
-    }
     __syncthreads();
     if (from_zero) {  // an index of the earlier set that no new payload has becomes zero
 #pragma unroll
-      for (int k = 0; k < kPerThread; ++k)
-        if (was_rel[k] >= 0 && !((sh.bitmap[was_rel[k] >> 5] >> (was_rel[k] & 31)) & 1u))
-          dense[blk.begin + was_rel[k]] = 0.0f;
+      for (int k = 0; k < kPerThread; ++k) {
+        const int64_t r = (int64_t)was_idx[k] - blk.begin;
+        if (tid + k * kMergeThreads < old_total && r >= 0 && r < length && !((sh.bitmap[r >> 5] >> (r & 31)) & 1u))
+          dense[blk.begin + r] = 0.0f;
+      }
       if (total == 0) return;
     }
     {
