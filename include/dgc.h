@@ -149,7 +149,7 @@ dgc_status dgc_workspace_bytes(const dgc_handle* h, size_t* bytes);
  * and v inside its streaming pass and parks the selected values in the staging arrays, so
  * that the emit pass does not come back to u and v (1017 -> about 600 us at 25 % on a
  * 122 M-element set); every region of the payload is then in ascending index order.  With
- * the smaller workspace, or with re_threshold on, the same results are computed the slower
+ * the smaller workspace, or with refine_alpha > 0, the same results are computed the slower
  * way.  Results do not depend on which workspace is given.
  */
 dgc_status dgc_workspace_bytes_warmup(const dgc_handle* h, size_t* bytes);
@@ -183,14 +183,15 @@ dgc_status dgc_recommended_payload_layout(const dgc_handle* h, double density,
  *              mask.  Pairs [out_offsets[j], out_offsets[j] + min(count_j, capacity_j))
  *              are valid: the same pairs in the same order on every run, the parts of
  *              consecutive blocks of 32768 elements in index order, ascending throughout
- *              with DGC_FLAG_SORTED_OUTPUT.  An element that passed but found the
- *              region full is neither emitted nor cleared (it stays in u, v) and
- *              DGC_DIAG_OVERFLOW is raised; with DGC_FLAG_SORTED_OUTPUT those are the
- *              highest indices.
+ *              with DGC_FLAG_SORTED_OUTPUT (and whenever the staging arrays of
+ *              dgc_workspace_bytes_warmup are in use).  An element that passed but found
+ *              the region full is neither emitted nor cleared (it stays in u, v) and
+ *              DGC_DIAG_OVERFLOW is raised; in an ascending region those are the highest
+ *              indices.
  *   out_thr    device, float[num_tensors], or NULL
  *   iteration  t: with the seed and the tensor index it fixes the sample positions
- *   workspace  device, >= dgc_workspace_bytes, 256-byte aligned; it must not be
- *              shared by calls that may overlap in time
+ *   workspace  device, >= dgc_workspace_bytes (or dgc_workspace_bytes_warmup), 256-byte
+ *              aligned; it must not be shared by calls that may overlap in time
  * Errors: INVALID_ARG (null, bad layout), ALIGNMENT, CAPACITY (workspace), HIP.
  */
 dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32_t* out_idx,
