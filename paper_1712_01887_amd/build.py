@@ -17,7 +17,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB_PATH = os.path.join(HERE, "libdgc.so")
-SOURCES = [os.path.join(HERE, "csrc", "dgc_api.hip"), os.path.join(HERE, "csrc", "dgc_kernels.hip")]
+SOURCES = [os.path.join(HERE, "csrc", name) for name in
+           ("dgc_api.hip", "dgc_compress.hip", "dgc_receive.hip", "dgc_wire.hip")]
 HEADERS = [os.path.join(HERE, "csrc", "dgc_internal.h"), os.path.join(ROOT, "include", "dgc.h")]
 
 

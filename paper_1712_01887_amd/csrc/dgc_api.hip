@@ -1,6 +1,7 @@
 // Host side of libdgc: argument checks, the host arithmetic of the method
 // (k_j, sample plan, warm-up table), workspace management and launch order.
-// Every step of the path itself runs in the kernels of dgc_kernels.hip.
+// Every step of the path itself runs in the kernels of dgc_compress.hip, dgc_receive.hip and
+// dgc_wire.hip.
 
 #include <cmath>
 #include <cstdio>

@@ -11,6 +11,8 @@
 
 namespace dgc {
 
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
 // ---- launch geometry -------------------------------------------------------
 // Streaming pass: one wavefront owns a contiguous run of kWaveTile elements and
 // reads it as kStreamUnroll rounds of one float4 per lane (64 lanes x 16 B =
@@ -256,7 +258,7 @@ enum ScatterMode : int32_t {
   kScatterPlainSgd = 4
 };
 
-// ---- launchers (dgc_kernels.hip) ---------------------------------------------
+// ---- launchers (dgc_compress.hip, dgc_receive.hip, dgc_wire.hip) --------------
 int32_t norm_blocks(int64_t n);  // partial sums launch_norm leaves
 hipError_t launch_norm(const float* g, int64_t n, double* partials, hipStream_t stream);
 hipError_t launch_select(const SelectArgs& a, int32_t num_tensors, hipStream_t stream);
