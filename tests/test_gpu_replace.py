@@ -17,7 +17,7 @@ SORTED = B.DGC_FLAG_SORTED_OUTPUT
 
 
 def _run(gs, N, densities, seed, flags=0, scales=None, layout_density=None, warm=False, workers_per_iteration=None,
-         **extra):
+         reverse_previous=False, **extra):
     """One Pair per worker and per parity of the iteration (so that the previous payloads stay
     intact); every iteration replaces the aggregate and is compared with the oracle."""
     import torch
@@ -46,9 +46,10 @@ def _run(gs, N, densities, seed, flags=0, scales=None, layout_density=None, warm
             payloads.append(O.flatten_payload(res))
             current.append(p)
         acc.dgc_set_density(d)
+        before = previous[::-1] if reverse_previous else previous       # the order of the previous payloads is free
         acc.dgc_decompress_replace_regions(dense, [p.out_idx for p in current], [p.out_val for p in current],
-                                           [p.out_counts for p in current], [p.out_idx for p in previous],
-                                           [p.out_counts for p in previous])
+                                           [p.out_counts for p in current], [p.out_idx for p in before],
+                                           [p.out_counts for p in before])
         expect = np.zeros(gs.numel, np.float32)
         O.decompress_accumulate(expect, payloads)
         got = dense.cpu().numpy()
@@ -77,6 +78,12 @@ def test_replace_with_more_pairs_than_a_workgroup_holds():
     accumulator take the general path (previous indices cleared first)."""
     gs = S.ragged_set(42, tensors=10, max_numel=400000)
     _run(gs, 48, [0.005, 0.005], 77, layout_density=0.04, sample_min=1024, sample_max=8192)
+
+
+def test_replace_with_the_previous_payloads_in_another_order():
+    gs = S.ragged_set(44, tensors=12, max_numel=300000)
+    _run(gs, 5, [0.002, 0.002, 0.002], 93, reverse_previous=True, layout_density=0.02, sample_min=1024,
+         sample_max=8192)
 
 
 def test_replace_with_a_changing_number_of_workers():
