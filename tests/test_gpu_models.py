@@ -87,6 +87,47 @@ def test_literal_speech_set_two_iterations():
     p.close()
 
 
+def test_speech_set_receive_side_at_warmup_densities():
+    """The receive side above 0.5 % at the speech set's full size (3764 emit parts: every
+    workgroup of the part kernels takes several), two workers: accumulate, sparse clear and
+    the replacing merge against the oracle's ordered sum, bit for bit."""
+    import torch
+    gs = S.speech_set()
+    scales = S.tensor_scales(gs, 57)
+    N = 2
+    kw = dict(momentum=0.9, density=0.25, seed=57, num_workers=N)
+    shared = S.gradient(gs, 57, 999, 0, scales)
+    pairs = [Pair(gs.offsets, warmup_workspace=True, layout_density=0.0625, **kw) for _ in range(N)]
+    acc = B.Dgc(B.make_config(**kw), gs.offsets)
+    acc.set_layout(pairs[0].layout)
+    dense = torch.zeros(gs.numel, device="cuda")
+    for it, d in enumerate([0.25, 0.0625]):
+        payloads = []
+        for w, p in enumerate(pairs):
+            p.set_density(d)
+            say(f"[speech receive] iteration {it} density {d} worker {w}")
+            res = p.step(S.correlated_gradient(gs, 57, w, it, shared, scales=scales), it, check_state=False,
+                         label=f"speech receive it{it} w{w}")
+            assert not res.overflow
+            payloads.append(O.flatten_payload(res))
+        expect = np.zeros(gs.numel, np.float32)
+        O.decompress_accumulate(expect, payloads)
+        lists = ([p.out_idx for p in pairs], [p.out_val for p in pairs], [p.out_counts for p in pairs])
+        acc.dgc_set_density(d)
+        if it == 0:
+            acc.dgc_decompress_accumulate_regions(dense, *lists)
+            assert np.array_equal(dense.cpu().numpy().view(np.uint32), expect.view(np.uint32)), "accumulate"
+            acc.dgc_dense_clear_regions(dense, lists[0], lists[2])
+            assert not dense.any().item(), "sparse clear"
+            acc.dgc_decompress_replace_regions(dense, *lists)
+        else:                                            # over the aggregate of iteration 0, whose lists are gone
+            acc.dgc_decompress_replace_regions(dense, *lists)
+        assert np.array_equal(dense.cpu().numpy().view(np.uint32), expect.view(np.uint32)), f"replace it{it}"
+    acc.close()
+    for p in pairs:
+        p.close()
+
+
 def test_sixteen_worker_accumulate_resnet50_shape():
     import torch
     gs = S.resnet50_set()
