@@ -341,7 +341,7 @@ dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tenso
       const int64_t t0 = h->offsets[t] / kWaveTile;
       const int64_t t1 = (h->offsets[t + 1] - 1) / kWaveTile;
       const int32_t nb = (int32_t)((t1 - t0) / kEmitTiles + 1);
-      for (int64_t f = t0; f <= t1; f += kEmitTiles) h->emit_blocks.push_back(EmitBlock{t, (int32_t)f, nb, 0});
+      for (int64_t f = t0; f <= t1; f += kEmitTiles) h->emit_blocks.push_back(EmitBlock{t, (int32_t)f, nb, 0, h->offsets[t], h->offsets[t + 1]});
     }
     // element ranges of the receive side: kMergeEmitBlocks consecutive emit workgroups' parts of one tensor
     for (size_t b = 0; b < h->emit_blocks.size();) {

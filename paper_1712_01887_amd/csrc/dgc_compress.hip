@@ -785,8 +785,10 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
   const int wave = tid >> 6;
   const EmitBlock blk = a.blocks[blockIdx.x];
   const int j = blk.tensor;
-  const int64_t lo = a.offsets[j];
-  const int64_t hi = a.offsets[j + 1];
+  const int64_t region = a.out_offsets[j];  // asked for early: needed late
+  const int64_t cap = a.out_offsets[j + 1] - region;
+  const int64_t lo = blk.lo;
+  const int64_t hi = blk.hi;
   const int64_t t0 = lo / kWaveTile;
   const int64_t t1 = (hi - 1) / kWaveTile;
   const int64_t first = blk.first_tile;
@@ -823,8 +825,6 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
 
   // ---- exact threshold among the selected elements of tensor j (rare) ---------------
   const int64_t words = (t1 - t0 + 1) * 64;
-  const int64_t region = a.out_offsets[j];
-  const int64_t cap = a.out_offsets[j + 1] - region;
   const int64_t passed = sh.passed;
   uint32_t prefix = 0;
   uint32_t rank = (uint32_t)a.plans[j].k;
@@ -1068,8 +1068,10 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
   const int wave = threadIdx.x >> 6;
   const EmitBlock blk = a.blocks[blockIdx.x];
   const int j = blk.tensor;
-  const int64_t lo = a.offsets[j];
-  const int64_t hi = a.offsets[j + 1];
+  const int64_t region = a.out_offsets[j];  // asked for early: needed late
+  const int64_t cap = a.out_offsets[j + 1] - region;
+  const int64_t lo = blk.lo;
+  const int64_t hi = blk.hi;
   const int64_t t1 = (hi - 1) / kWaveTile;
   const int64_t first = blk.first_tile;
 
@@ -1127,8 +1129,6 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
   }
   if (total == 0) return;
   __syncthreads();
-  const int64_t region = a.out_offsets[j];
-  const int64_t cap = a.out_offsets[j + 1] - region;
   const int64_t base_slot = block_base;
   const int my_first = before + (incl - cnt);  // position of this lane's first element in the workgroup
   bool overflow = false;
@@ -1173,8 +1173,8 @@ __device__ __forceinline__ void emit_tiles(const EmitArgs& a, const EmitBlock& b
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   const int j = blk.tensor;
-  const int64_t lo = a.offsets[j];
-  const int64_t hi = a.offsets[j + 1];
+  const int64_t lo = blk.lo;
+  const int64_t hi = blk.hi;
   const int64_t t1 = (hi - 1) / kWaveTile;
   const int64_t first = blk.first_tile;
 
@@ -1262,12 +1262,12 @@ __global__ __launch_bounds__(kEmitThreads) void emit_sorted_kernel(EmitArgs a) {
   const int wave = threadIdx.x >> 6;
   const EmitBlock blk = a.blocks[blockIdx.x];
   const int j = blk.tensor;
+  const int64_t region = a.out_offsets[j];  // asked for early: needed late
+  const int64_t cap = a.out_offsets[j + 1] - region;
   const int64_t first = blk.first_tile;
   emit_tiles(a, blk, sh);
   const int total = sh.block_total;
   if (total == 0) return;
-  const int64_t region = a.out_offsets[j];
-  const int64_t cap = a.out_offsets[j + 1] - region;
   const int64_t base_slot = sh.block_base;
   bool overflow = false;
   for (int win = 0; win < total; win += kEmitList) {
@@ -1331,8 +1331,8 @@ __global__ __launch_bounds__(kEmitThreads) void emit_staged_kernel(EmitArgs a) {
   const int64_t first = blk.first_tile;
   emit_tiles(a, blk, sh);
   if (sh.block_total == 0) return;
-  const int64_t lo = a.offsets[j];
-  const int64_t hi = a.offsets[j + 1];
+  const int64_t lo = blk.lo;
+  const int64_t hi = blk.hi;
   const int64_t region = a.out_offsets[j];
   const int64_t cap = a.out_offsets[j + 1] - region;
   int32_t* __restrict__ out_idx = a.out_idx + region;

@@ -164,6 +164,7 @@ struct EmitBlock {
   int32_t first_tile;     // first wave tile of the workgroup's run inside that tensor
   int32_t tensor_blocks;  // workgroups that share this tensor
   int32_t pad;
+  int64_t lo, hi;         // the tensor's elements [lo, hi): here, so that no workgroup waits for a second table
 };
 
 struct RefineArgs {
