@@ -88,6 +88,19 @@ def test_compress_and_accumulate_validate_before_touching_the_device(dgc_lib):
     assert acc(d._h, a, 10, 65, ptrs, ptrs, cnt, None, None) == B.DGC_ERR_CAPACITY
     neg = (C.c_int64 * 1)(-1)
     assert acc(d._h, a, 10, 1, ptrs, ptrs, neg, None, None) == B.DGC_ERR_INVALID_ARG
+    # the region-layout receive calls: payload lists, previous lists, layout and workspace are checked first
+    rep = dgc_lib.dgc_decompress_replace_regions
+    big = (C.c_void_p * 65)(*([a] * 65))
+    assert rep(d._h, None, 1, ptrs, ptrs, ptrs, 0, None, None, lay, a, 1 << 24, None) == B.DGC_ERR_INVALID_ARG
+    assert rep(d._h, a, 0, ptrs, ptrs, ptrs, 0, None, None, lay, a, 1 << 24, None) == B.DGC_ERR_INVALID_ARG
+    assert rep(d._h, a, 65, big, big, big, 0, None, None, lay, a, 1 << 24, None) == B.DGC_ERR_CAPACITY
+    assert rep(d._h, a, 1, ptrs, None, ptrs, 0, None, None, lay, a, 1 << 24, None) == B.DGC_ERR_INVALID_ARG
+    assert rep(d._h, a, 1, ptrs, ptrs, ptrs, -1, None, None, lay, a, 1 << 24, None) == B.DGC_ERR_INVALID_ARG
+    assert rep(d._h, a, 1, ptrs, ptrs, ptrs, 1, None, None, lay, a, 1 << 24, None) == B.DGC_ERR_INVALID_ARG
+    assert rep(d._h, a, 1, ptrs, ptrs, ptrs, 65, big, big, lay, a, 1 << 24, None) == B.DGC_ERR_CAPACITY
+    assert rep(d._h, a, 1, ptrs, ptrs, ptrs, 1, ptrs, ptrs, bad, a, 1 << 24, None) == B.DGC_ERR_INVALID_ARG
+    assert rep(d._h, a, 1, ptrs, ptrs, ptrs, 1, ptrs, ptrs, lay, None, 1 << 24, None) == B.DGC_ERR_INVALID_ARG
+    assert rep(d._h, a, 1, ptrs, ptrs, ptrs, 1, ptrs, ptrs, lay, a, 16, None) == B.DGC_ERR_CAPACITY
     d.close()
 
 
