@@ -46,7 +46,10 @@ def test_random_configuration(seed, warm):
     else:
         p = Pair(offsets, layout_density=1.0, warmup_workspace=warm, **kw)       # room for anything a small sample lets through
     scale = float(rng.choice([1e-3, 1.0, 30.0]))
+    wander = (not tight) and rng.random() < 0.5            # another density every iteration, one state
     for it in range(3):
+        if wander and it:
+            p.set_density(float(rng.choice([0.001, 0.004, 0.006, 0.01, 0.1, 0.5, 1.0])))
         g = (scale * rng.standard_t(3, n)).astype(np.float32)
         if rng.random() < 0.3:
             g[rng.random(n) < 0.7] = 0.0                  # mostly zero: thresholds of 0, empty regions
