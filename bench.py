@@ -189,9 +189,10 @@ def parse_args():
                     help="switch the Section 5 re-threshold on (dgc_config.refine_alpha); off by default")
     ap.add_argument("--sorted", action="store_true",
                     help="emit every tensor's pairs in ascending index order (DGC_FLAG_SORTED_OUTPUT)")
-    ap.add_argument("--receive", choices=["replace", "accumulate_clear"], default="replace",
+    ap.add_argument("--receive", choices=["replace", "accumulate_clear", "sgd_apply"], default="replace",
                     help="receive side of a step: dgc_decompress_accumulate_regions + dgc_dense_clear_regions, or "
-                         "dgc_decompress_replace_regions (the aggregate written in place of the previous one)")
+                         "dgc_decompress_replace_regions (the aggregate written in place of the previous one), or "
+                         "dgc_sparse_sgd_apply_regions (no aggregate: the dense buffer plays the parameters, lr 1e-3)")
     ap.add_argument("--rotate", type=int, default=4,
                     help="independent (g, u, v) sets the steps rotate through; 4 keeps every step's operands out of the "
                          "last-level cache (the default and the headline), 1 shows the cache-resident case")
@@ -319,7 +320,8 @@ def main():
             prepared[(r, q)] = B.PreparedStep(dgc, g_pool[q], u[r], v[r], fresh[r], plists[r], dense,
                                               previous=plists[(r - 1) % ROTATE])
     for p in prepared.values():
-        p.receive = p.replace if replace else p.accumulate_and_clear
+        p.receive = {"replace": p.replace, "accumulate_clear": p.accumulate_and_clear,
+                     "sgd_apply": p.sgd_apply}[args.receive]
 
     def step(i):
         r = i % ROTATE
@@ -414,7 +416,8 @@ def main():
             "select_kernel_us": round(select_ms / calls * 1e3, 2),
             "stream_kernel_us": round(stream_avg_ms * 1e3, 2),
             "emit_kernel_us": round(emit_ms / calls * 1e3, 2),
-            "replace_us" if replace else "accumulate_and_clear_us": round(acc * 1e3, 2),
+            {"replace": "replace_us", "accumulate_clear": "accumulate_and_clear_us",
+             "sgd_apply": "sgd_apply_us"}[args.receive]: round(acc * 1e3, 2),
             "ms_per_step_with_events": round(profiled_ms, 5),
         }
         if clip:
@@ -439,6 +442,8 @@ def main():
         "config": {
             "workload": description + (f"; step = compress one worker + aggregate of {n_workers} payloads written in "
                                        "place of the previous one" if replace else
+                                       f"; step = compress one worker + sparse SGD apply of {n_workers} payloads"
+                                       if args.receive == "sgd_apply" else
                                        f"; step = compress one worker + accumulate {n_workers} payloads + sparse clear"),
             "elements": n,
             "tensors": len(gs.sizes),

@@ -433,6 +433,14 @@ class PreparedStep:
             if st != DGC_OK:
                 _check(st, "dgc_decompress_replace_regions")
 
+        def sgd_apply() -> None:
+            st = lib.dgc_sparse_sgd_apply_regions(*sargs)
+            if st != DGC_OK:
+                _check(st, "dgc_sparse_sgd_apply_regions")
+
+        sargs = (h, C.c_void_p(_ptr(dense)), C.c_float(1e-3), C.c_int32(accumulate.n), accumulate.idx, accumulate.val,
+                 accumulate.counts, dgc._layout_c, ws, wsb, stream)
+        self.sgd_apply = sgd_apply
         prev = previous if previous is not None else accumulate
         rargs = (h, C.c_void_p(_ptr(dense)), C.c_int32(accumulate.n), accumulate.idx, accumulate.val,
                  accumulate.counts, C.c_int32(prev.n), prev.idx, prev.counts, dgc._layout_c, ws, wsb, stream)
