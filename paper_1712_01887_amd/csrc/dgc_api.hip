@@ -60,8 +60,8 @@ bool hip_ok(hipError_t e, const char* what) {
 }
 
 constexpr size_t kAlign = 256;
-constexpr double kMergeMaxDensity = 0.005;
-constexpr double kStagedMinDensity = 0.005;  // compress: staged streaming pass above this density  // receive side: merge by element range in LDS up to here
+constexpr double kMergeMaxDensity = 0.005;   // receive side: merge by element range in LDS up to here
+constexpr double kStagedMinDensity = 0.005;  // compress: staged streaming pass above this density
 constexpr int kProfEvents = 5;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -341,7 +341,8 @@ dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tenso
       const int64_t t0 = h->offsets[t] / kWaveTile;
       const int64_t t1 = (h->offsets[t + 1] - 1) / kWaveTile;
       const int32_t nb = (int32_t)((t1 - t0) / kEmitTiles + 1);
-      for (int64_t f = t0; f <= t1; f += kEmitTiles) h->emit_blocks.push_back(EmitBlock{t, (int32_t)f, nb, 0, h->offsets[t], h->offsets[t + 1]});
+      for (int64_t f = t0; f <= t1; f += kEmitTiles)
+        h->emit_blocks.push_back(EmitBlock{t, (int32_t)f, nb, 0, h->offsets[t], h->offsets[t + 1]});
     }
     // element ranges of the receive side: kMergeEmitBlocks consecutive emit workgroups' parts of one tensor
     for (size_t b = 0; b < h->emit_blocks.size();) {

@@ -64,7 +64,9 @@ constexpr int kPartThreads = 1024;
 constexpr int kPartPer = 8;  // pairs a thread holds per round
 constexpr int kPartRound = kPartThreads * kPartPer;
 constexpr int kPartClearThreads = 256;
-static_assert(kEmitElements <= 65536 && kEmitElements % kPartThreads == 0 && (kEmitElements / 32) % kPartClearThreads == 0, "dealt evenly");
+static_assert(kEmitElements <= 65536 && kEmitElements % kPartThreads == 0 &&
+                  (kEmitElements / 32) % kPartClearThreads == 0,
+              "dealt evenly");
 
 // Wire format (32-bit values + 16-bit zero-run lengths): pairs or entries handled by one
 // workgroup, kWirePerThread consecutive ones per thread.

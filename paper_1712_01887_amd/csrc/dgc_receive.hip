@@ -607,14 +607,16 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
 // payload, kPartPer per thread, with the loads of the next two rounds in flight.  Pairs
 // of one payload have distinct indices and are added without synchronisation; a
 // barrier separates one payload from the next.
+//
 // At these densities a region holds up to millions of pairs and the search for a part's
 // pairs is several rounds of dependent loads: with one workgroup per compute unit (the
 // accumulator fills LDS) nothing else would run meanwhile.  So the searches of all parts
 // and payloads run first, spread over the chip, and leave (first pair, number of pairs)
 // of every part in every payload's region in a table (a part ends where the next one of
-// its tensor starts, so one bound per part is searched for).  The probes are what this launch costs (each one a 64-byte sector from
-// HBM: 350 MB with 32 probes per round and two bounds per part), so eight lanes share a
-// search: 8 probes per round, about seven rounds for a region of a million pairs.
+// its tensor starts, so one bound per part is searched for).  The probes are what this
+// launch costs (each one a 64-byte sector from HBM: 350 MB with 32 probes per round and
+// two bounds per part), so eight lanes share a search: 8 probes per round, about seven
+// rounds for a region of a million pairs.
 __global__ __launch_bounds__(kFlatThreads) void locate_parts_kernel(RegionPayloads p, int32_t num_payloads,
                                                                     const int64_t* __restrict__ out_offsets,
                                                                     const MergeBlock* __restrict__ blocks,
