@@ -60,3 +60,52 @@ def test_random_configuration(seed, warm):
             check_overflow_invariants(p, g, u0, v0)
             break                                         # the two sides' states differ from here on (order-dependent)
     p.close()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_large_configuration(seed):
+    """Millions of elements in a few dozen tensors of very different sizes: thousands of wave
+    tiles per tensor, hundreds of emit parts, regions of 10^5 pairs; compress over three
+    iterations with the density changing, then the receive side of three workers."""
+    import torch
+    rng = np.random.default_rng([seed, 90210])
+    T = int(rng.integers(2, 40))
+    sizes = [int(np.exp(rng.uniform(np.log(10.0), np.log(3.0e6)))) for _ in range(T)]
+    offsets = np.concatenate([[0], np.cumsum(sizes)])
+    n = int(offsets[-1])
+    flags = 0
+    for f in (B.DGC_FLAG_NESTEROV, B.DGC_FLAG_NO_FACTOR_MASKING, B.DGC_FLAG_SORTED_OUTPUT):
+        if rng.random() < 0.3:
+            flags |= f
+    warm = bool(rng.random() < 0.6)
+    kw = dict(momentum=0.9, density=0.001, seed=int(rng.integers(0, 2 ** 40)), flags=flags, num_workers=3)
+    if rng.random() < 0.4:
+        kw.update(clip_threshold=float(rng.choice([0.5, 50.0])))
+    workers = [Pair(offsets, layout_density=0.25, warmup_workspace=warm, **kw) for _ in range(3)]
+    shared = rng.standard_t(3, n).astype(np.float32)
+    densities = [float(rng.choice([0.001, 0.004, 0.02, 0.1])) for _ in range(3)]
+    payloads = []
+    for it, d in enumerate(densities):
+        payloads = []
+        for w, p in enumerate(workers):
+            p.set_density(d)
+            g = (0.01 * (0.5 * shared + rng.standard_t(3, n))).astype(np.float32)
+            res = p.step(g, it, check_state=(w == 0), label=f"large seed={seed} it{it} w{w} d={d} n={n} T={T}")
+            assert not res.overflow
+            payloads.append(O.flatten_payload(res))
+    acc = B.Dgc(B.make_config(**kw), offsets)
+    acc.set_layout(workers[0].layout)
+    acc.dgc_set_density(densities[-1])
+    dense = torch.zeros(n, device="cuda")
+    lists = ([p.out_idx for p in workers], [p.out_val for p in workers], [p.out_counts for p in workers])
+    expect = np.zeros(n, np.float32)
+    O.decompress_accumulate(expect, payloads)
+    acc.dgc_decompress_replace_regions(dense, *lists)
+    assert np.array_equal(dense.cpu().numpy().view(np.uint32), expect.view(np.uint32)), "replace"
+    acc.dgc_dense_clear_regions(dense, lists[0], lists[2])
+    assert not dense.any().item(), "clear"
+    acc.dgc_decompress_accumulate_regions(dense, *lists)
+    assert np.array_equal(dense.cpu().numpy().view(np.uint32), expect.view(np.uint32)), "accumulate"
+    acc.close()
+    for p in workers:
+        p.close()
