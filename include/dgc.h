@@ -113,6 +113,28 @@ dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tenso
 dgc_status dgc_destroy(dgc_handle* h);
 
 /*
+ * Workspaces.  The device workspace passed to dgc_compress and to the region calls of the
+ * receive side holds tables that the library uploads (tile and work lists, the selection plan
+ * of the current density, the payload layout) the first time a handle meets it, and again
+ * when the density or the layout changes.  The handle remembers on the host what it has
+ * uploaded where, so:
+ *   - give every handle a workspace of its own on the hot path.  A workspace may pass from one
+ *     handle to another between calls (never between calls that overlap in time): the library
+ *     notices and uploads the new owner's tables again, which costs several host-to-device
+ *     copies per change of owner;
+ *   - a workspace that was freed, overwritten by the caller, or allocated again at the same
+ *     address must be announced with dgc_invalidate_workspace before its next use: the
+ *     library cannot see that its tables are gone;
+ *   - uploads cannot be captured into a HIP graph.  A call that would have to upload while
+ *     its stream is being captured returns DGC_ERR_STATE and enqueues nothing: make the first
+ *     call on a workspace, and the first one after dgc_set_density or a change of payload
+ *     layout, outside the capture.
+ * dgc_invalidate_workspace forgets everything the handle believes about its workspace; the
+ * next call uploads all tables again.  Host only.
+ */
+dgc_status dgc_invalidate_workspace(dgc_handle* h);
+
+/*
  * Density control (Section 3.3 "warm-up training"; Section 4.1 lists the
  * sparsities 75 %, 93.75 %, 98.4375 %, 99.6 %, 99.9 %).  Host only: recomputes
  * k_j and the sample plan; the next dgc_compress uploads the new plan.
@@ -127,6 +149,14 @@ dgc_status dgc_set_warmup_schedule(dgc_handle* h, const double* densities_host, 
 dgc_status dgc_set_warmup_stage_length(dgc_handle* h, int64_t iterations_per_stage);
 /* density <- table[min(iteration / stage length, len - 1)]. */
 dgc_status dgc_set_iteration_density(dgc_handle* h, int64_t iteration);
+
+/*
+ * Test hook for the clipping scale of Appendix C (equation 12): a finite value replaces the
+ * factor min(1, thr_local / ||g||) in the following dgc_compress calls (the norm is still
+ * computed and reported when clipping is on), NaN returns to the computed one.  Same meaning
+ * as dgc_config.scale_override.  Host only.  Errors: INVALID_ARG (null handle, infinity).
+ */
+dgc_status dgc_set_scale_override(dgc_handle* h, float scale);
 
 /*
  * Host arithmetic of tensor j under the current density (any pointer may be NULL):
@@ -191,8 +221,10 @@ dgc_status dgc_recommended_payload_layout(const dgc_handle* h, double density,
  *   out_thr    device, float[num_tensors], or NULL
  *   iteration  t: with the seed and the tensor index it fixes the sample positions
  *   workspace  device, >= dgc_workspace_bytes (or dgc_workspace_bytes_warmup), 256-byte
- *              aligned; it must not be shared by calls that may overlap in time
- * Errors: INVALID_ARG (null, bad layout), ALIGNMENT, CAPACITY (workspace), HIP.
+ *              aligned; it must not be shared by calls that may overlap in time (see
+ *              "Workspaces" above)
+ * Errors: INVALID_ARG (null, bad layout), ALIGNMENT, CAPACITY (workspace), HIP, STATE (tables
+ * would have to be uploaded while the stream is being captured).
  */
 dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32_t* out_idx,
                         float* out_val, const int64_t* out_offsets_host, int32_t* out_counts,

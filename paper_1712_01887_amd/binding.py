@@ -9,11 +9,8 @@ raises.
 from __future__ import annotations
 
 import ctypes as C
-import math
 import os
-from typing import List, Optional, Sequence
-
-import numpy as np
+from typing import List, Sequence
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 # DGC_LIBRARY selects another build of the library (e.g. one compiled with different tile constants).
@@ -38,7 +35,8 @@ DGC_DIAG_BAD_INDEX = 1 << 2
 DGC_DIAG_UNSORTED = 1 << 3
 
 EXPORTS = [
-    "dgc_config_default", "dgc_status_string", "dgc_create", "dgc_destroy", "dgc_set_density",
+    "dgc_config_default", "dgc_status_string", "dgc_create", "dgc_destroy", "dgc_invalidate_workspace",
+    "dgc_set_scale_override", "dgc_set_density",
     "dgc_set_warmup_schedule", "dgc_set_warmup_stage_length", "dgc_set_iteration_density", "dgc_query_plan", "dgc_workspace_bytes", "dgc_workspace_bytes_warmup",
     "dgc_recommended_payload_layout", "dgc_compress", "dgc_get_diagnostics",
     "dgc_decompress_accumulate", "dgc_decompress_accumulate_regions", "dgc_decompress_replace_regions",
@@ -105,6 +103,10 @@ def load() -> C.CDLL:
     lib.dgc_create.argtypes = [P(vp), P(DgcConfig), i32, P(i64)]
     lib.dgc_destroy.restype = i32
     lib.dgc_destroy.argtypes = [vp]
+    lib.dgc_invalidate_workspace.restype = i32
+    lib.dgc_invalidate_workspace.argtypes = [vp]
+    lib.dgc_set_scale_override.restype = i32
+    lib.dgc_set_scale_override.argtypes = [vp, C.c_float]
     lib.dgc_set_density.restype = i32
     lib.dgc_set_density.argtypes = [vp, dbl]
     lib.dgc_set_warmup_schedule.restype = i32
@@ -233,6 +235,12 @@ class Dgc:
             pass
 
     # -- host-only calls ---------------------------------------------------
+    def dgc_invalidate_workspace(self) -> None:
+        _check(self.lib.dgc_invalidate_workspace(self._h), "dgc_invalidate_workspace")
+
+    def dgc_set_scale_override(self, scale: float) -> None:
+        _check(self.lib.dgc_set_scale_override(self._h, float(scale)), "dgc_set_scale_override")
+
     def dgc_set_density(self, density: float) -> None:
         _check(self.lib.dgc_set_density(self._h, float(density)), "dgc_set_density")
 
@@ -382,86 +390,3 @@ class Dgc:
         _check(self.lib.dgc_dense_clear_regions(
             self._h, _ptr(dense), len(idx_list), _ptr_array(idx_list), _ptr_array(count_list),
             self._layout_c, self._ws_ptr, self._ws_bytes, _stream()), "dgc_dense_clear_regions")
-
-
-class PayloadList:
-    """Device pointers of several region-layout payloads, marshalled once so that a
-    measurement loop does not rebuild ctypes arrays every call.  Keeps the tensors alive."""
-
-    def __init__(self, idx_list, val_list, count_list):
-        self.tensors = (list(idx_list), list(val_list) if val_list is not None else None, list(count_list))
-        self.n = len(idx_list)
-        self.idx = _ptr_array(idx_list)
-        self.val = _ptr_array(val_list) if val_list is not None else None
-        self.counts = _ptr_array(count_list)
-
-
-class PreparedStep:
-    """One worker's compress call and the accumulate / clear calls that follow it, with every
-    argument marshalled ahead of time (pointers, layout, workspace, stream)."""
-
-    def __init__(self, dgc: "Dgc", g, u, v, payload, accumulate: PayloadList, dense, previous: PayloadList = None):
-        dgc.ensure_workspace(g.device)
-        self.keep = (g, u, v, payload, accumulate, dense, previous)
-        lib, h = dgc.lib, dgc._h
-        stream = C.c_void_p(_stream())
-        out_idx, out_val, out_counts, out_thr = payload
-        ws, wsb = C.c_void_p(dgc._ws_ptr), C.c_size_t(dgc._ws_bytes)
-        cargs = (h, C.c_void_p(_ptr(g)), C.c_void_p(_ptr(u)), C.c_void_p(_ptr(v)), C.c_void_p(_ptr(out_idx)),
-                 C.c_void_p(_ptr(out_val)), dgc._layout_c, C.c_void_p(_ptr(out_counts)),
-                 C.c_void_p(_ptr(out_thr)))
-        aargs = (h, C.c_void_p(_ptr(dense)), C.c_int32(accumulate.n), accumulate.idx, accumulate.val,
-                 accumulate.counts, dgc._layout_c, ws, wsb, stream)
-        kargs = (h, C.c_void_p(_ptr(dense)), C.c_int32(accumulate.n), accumulate.idx, accumulate.counts,
-                 dgc._layout_c, ws, wsb, stream)
-
-        def compress(iteration: int) -> None:
-            st = lib.dgc_compress(*cargs, C.c_uint64(iteration), ws, wsb, stream)
-            if st != DGC_OK:
-                _check(st, "dgc_compress")
-
-        def accumulate_and_clear() -> None:
-            st = lib.dgc_decompress_accumulate_regions(*aargs)
-            if st != DGC_OK:
-                _check(st, "dgc_decompress_accumulate_regions")
-            st = lib.dgc_dense_clear_regions(*kargs)
-            if st != DGC_OK:
-                _check(st, "dgc_dense_clear_regions")
-
-        def replace() -> None:
-            st = lib.dgc_decompress_replace_regions(*rargs)
-            if st != DGC_OK:
-                _check(st, "dgc_decompress_replace_regions")
-
-        def sgd_apply() -> None:
-            st = lib.dgc_sparse_sgd_apply_regions(*sargs)
-            if st != DGC_OK:
-                _check(st, "dgc_sparse_sgd_apply_regions")
-
-        sargs = (h, C.c_void_p(_ptr(dense)), C.c_float(1e-3), C.c_int32(accumulate.n), accumulate.idx, accumulate.val,
-                 accumulate.counts, dgc._layout_c, ws, wsb, stream)
-        self.sgd_apply = sgd_apply
-        prev = previous if previous is not None else accumulate
-        rargs = (h, C.c_void_p(_ptr(dense)), C.c_int32(accumulate.n), accumulate.idx, accumulate.val,
-                 accumulate.counts, C.c_int32(prev.n), prev.idx, prev.counts, dgc._layout_c, ws, wsb, stream)
-        self.compress = compress
-        self.accumulate_and_clear = accumulate_and_clear
-        self.replace = replace
-
-
-def gather_payload(layout: Sequence[int], out_idx, out_val, out_counts, sort: bool = True):
-    """Host copy of a region-layout payload as per-tensor (indices, values), sorted by index
-    unless `sort` is false (then in the order the library left them).
-    Test/report helper: it waits for the device."""
-    idx = out_idx.cpu().numpy()
-    val = out_val.cpu().numpy()
-    cnt = out_counts.cpu().numpy()
-    per_idx, per_val = [], []
-    for j in range(len(layout) - 1):
-        lo = layout[j]
-        c = min(int(cnt[j]), layout[j + 1] - lo)
-        i = idx[lo:lo + c]
-        order = np.argsort(i, kind="stable") if sort else np.arange(c)
-        per_idx.append(i[order].copy())
-        per_val.append(val[lo:lo + c][order].copy())
-    return per_idx, per_val, cnt

@@ -3,10 +3,13 @@
 // Every step of the path itself runs in the kernels of dgc_compress.hip, dgc_receive.hip and
 // dgc_wire.hip.
 
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
+#include <unordered_map>
 #include <vector>
 
 #include "dgc_internal.h"
@@ -15,6 +18,7 @@ using namespace dgc;
 
 struct dgc_handle {
   dgc_config cfg;
+  uint64_t id = 0;                   // unique in the process: what the workspace registry records
   int32_t num_tensors = 0;
   int64_t n = 0;
   std::vector<int64_t> offsets;      // T + 1
@@ -57,6 +61,31 @@ bool hip_ok(hipError_t e, const char* what) {
   std::snprintf(g_last_error, sizeof(g_last_error), "%s: %s (%d)", what, hipGetErrorString(e), (int)e);
   (void)hipGetLastError();  // clear the sticky launch error so later calls start clean
   return false;
+}
+
+// Which handle's tables a workspace holds.  A handle keeps host-side flags for what it has
+// uploaded into the workspace it used last; they mean something only while no other handle has
+// written its own tables there in between, which this map records (workspace address -> id of
+// the handle that uploaded last).
+std::mutex g_registry_mutex;
+std::unordered_map<const void*, uint64_t> g_workspace_owner;
+std::atomic<uint64_t> g_next_handle_id{1};
+
+bool workspace_owned_by(const void* ws, uint64_t id) {
+  std::lock_guard<std::mutex> lock(g_registry_mutex);
+  auto it = g_workspace_owner.find(ws);
+  return it != g_workspace_owner.end() && it->second == id;
+}
+
+void workspace_claim(const void* ws, uint64_t id) {
+  std::lock_guard<std::mutex> lock(g_registry_mutex);
+  g_workspace_owner[ws] = id;
+}
+
+void workspace_release_all(uint64_t id) {
+  std::lock_guard<std::mutex> lock(g_registry_mutex);
+  for (auto it = g_workspace_owner.begin(); it != g_workspace_owner.end();)
+    it = it->second == id ? g_workspace_owner.erase(it) : std::next(it);
 }
 
 constexpr size_t kAlign = 256;
@@ -178,22 +207,38 @@ dgc_status check_layout(const dgc_handle* h, const int64_t* oo) {
 // Make the workspace hold the static tables, the current plan and the payload
 // layout.  Copies are stream-ordered; the sources are host vectors that stay
 // alive in the handle (the runtime stages pageable memory before returning).
+// The host-side flags say what has been ENQUEUED, so nothing may be uploaded while the stream
+// is being captured into a graph (a capture runs nothing, and may be thrown away): such a call
+// is refused with DGC_ERR_STATE, and the caller makes its first call on a workspace, and the
+// first one after a change of density or payload layout, eagerly.
 dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_t* out_offsets,
                           bool need_plan, hipStream_t stream) {
   if (!ws) return DGC_ERR_INVALID_ARG;
   if (!aligned(ws, kAlign)) return DGC_ERR_ALIGNMENT;
   if (ws_bytes < h->lay.total) return DGC_ERR_CAPACITY;
   const size_t T = (size_t)h->num_tensors;
-  if (ws != h->ws) {
+  if (ws != h->ws || !workspace_owned_by(ws, h->id)) {
     h->ws = ws;
     h->ws_static_valid = h->ws_plan_valid = h->ws_layout_valid = false;
   }
+  const bool layout_same = !out_offsets ||
+                           (h->ws_layout_valid &&
+                            std::memcmp(h->ws_out_offsets.data(), out_offsets, sizeof(int64_t) * (T + 1)) == 0);
+  if (!h->ws_static_valid || (need_plan && !h->ws_plan_valid) || !layout_same) {
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (!hip_ok(hipStreamIsCapturing(stream, &capturing), "query stream capture")) return DGC_ERR_HIP;
+    if (capturing != hipStreamCaptureStatusNone) {
+      std::snprintf(g_last_error, sizeof(g_last_error),
+                    "the workspace tables must be uploaded, which cannot be captured: make this call once outside the capture");
+      return DGC_ERR_STATE;
+    }
+  }
   if (!h->ws_static_valid) {
-    if (!hip_ok(hipMemsetAsync(at<char>(ws, h->lay.state), 0, sizeof(DeviceState), stream),
+    workspace_claim(ws, h->id);
+    if (!hip_ok(launch_clear_words(at<uint32_t>(ws, h->lay.state), sizeof(DeviceState) / sizeof(uint32_t), stream),
                 "clear workspace state"))
       return DGC_ERR_HIP;
-    if (!hip_ok(hipMemsetAsync(at<char>(ws, h->lay.refine_counters), 0, align_up(sizeof(uint32_t) * kCounterStride * T),
-                               stream),
+    if (!hip_ok(launch_clear_words(at<uint32_t>(ws, h->lay.refine_counters), (size_t)kCounterStride * T, stream),
                 "clear re-threshold counters"))
       return DGC_ERR_HIP;
     if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.offsets), h->offsets.data(),
@@ -230,9 +275,7 @@ dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_
     h->ws_plan_valid = true;
   }
   if (out_offsets) {
-    const bool same = h->ws_layout_valid &&
-                      std::memcmp(h->ws_out_offsets.data(), out_offsets, sizeof(int64_t) * (T + 1)) == 0;
-    if (!same) {
+    if (!layout_same) {
       h->ws_out_offsets.assign(out_offsets, out_offsets + T + 1);
       if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.out_offsets), h->ws_out_offsets.data(),
                                  sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, stream),
@@ -318,6 +361,7 @@ dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tenso
   if (!h) return DGC_ERR_CAPACITY;
   try {
     h->cfg = *cfg;
+    h->id = g_next_handle_id.fetch_add(1);
     h->num_tensors = num_tensors;
     h->offsets.assign(offsets_host, offsets_host + num_tensors + 1);
     h->n = offsets_host[num_tensors];
@@ -378,8 +422,26 @@ dgc_status dgc_create(dgc_handle** out, const dgc_config* cfg, int32_t num_tenso
 static void profile_release(dgc_handle* h);
 
 dgc_status dgc_destroy(dgc_handle* h) {
-  if (h) profile_release(h);
+  if (h) {
+    profile_release(h);
+    workspace_release_all(h->id);
+  }
   delete h;
+  return DGC_OK;
+}
+
+dgc_status dgc_invalidate_workspace(dgc_handle* h) {
+  if (!h) return DGC_ERR_INVALID_ARG;
+  workspace_release_all(h->id);
+  h->ws = nullptr;
+  h->ws_static_valid = h->ws_plan_valid = h->ws_layout_valid = false;
+  return DGC_OK;
+}
+
+dgc_status dgc_set_scale_override(dgc_handle* h, float scale) {
+  if (!h) return DGC_ERR_INVALID_ARG;
+  if (scale - scale != 0.0f && scale == scale) return DGC_ERR_INVALID_ARG;  // an infinity
+  h->cfg.scale_override = scale;
   return DGC_OK;
 }
 
@@ -547,8 +609,8 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   if (!hip_ok(launch_stream(ta, stream), "launch stream kernel")) return DGC_ERR_HIP;
   if (ev && !hip_ok(hipEventRecord(ev[3], stream), "record event")) return DGC_ERR_HIP;
 
-  // paper: Section 5 -- "if the number of gradients exceeding the threshold is far more than
-  // expected, a precise threshold is calculated from the already-selected gradients"
+  // paper: Section 5 -- a tensor that lets through far more elements than wanted gets an exact
+  // threshold, computed among the elements that passed
   if (c.refine_alpha > 0.0f) {
     RefineArgs ra{};
     ra.blocks = at<EmitBlock>(workspace, h->lay.emit_blocks);

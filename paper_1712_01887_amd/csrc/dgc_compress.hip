@@ -36,6 +36,12 @@ __device__ __forceinline__ void momentum_update(float g, float u, float v, float
   }
 }
 
+// Zero fill of small pieces of the workspace (a kernel rather than a memset: the calls of
+// the library may be captured into a HIP graph).
+__global__ __launch_bounds__(256) void clear_words_kernel(uint32_t* __restrict__ p, size_t words) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words; i += (size_t)gridDim.x * 256) p[i] = 0u;
+}
+
 // ---------------------------------------------------------------------------
 // Clipping norm (paper: Section 3.2 "Local Gradient Clipping"; Appendix C eq. 12)
 // ---------------------------------------------------------------------------
@@ -1445,6 +1451,14 @@ __global__ __launch_bounds__(kEmitThreads) void emit_staged_kernel(EmitArgs a) {
 // ---------------------------------------------------------------------------
 // Launchers
 // ---------------------------------------------------------------------------
+hipError_t launch_clear_words(uint32_t* p, size_t words, hipStream_t stream) {
+  if (words == 0) return hipSuccess;
+  size_t blocks = (words + 255) / 256;
+  if (blocks > 1024) blocks = 1024;
+  hipLaunchKernelGGL(clear_words_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, p, words);
+  return hipGetLastError();
+}
+
 int32_t norm_blocks(int64_t n) {
   int64_t blocks = ceil_div(n >> 2, (int64_t)kNormThreads * 8);
   if (blocks < 1) blocks = 1;

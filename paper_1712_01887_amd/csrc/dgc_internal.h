@@ -262,6 +262,7 @@ enum ScatterMode : int32_t {
 };
 
 // ---- launchers (dgc_compress.hip, dgc_receive.hip, dgc_wire.hip) --------------
+hipError_t launch_clear_words(uint32_t* p, size_t words, hipStream_t stream);  // p[0 .. words) <- 0
 int32_t norm_blocks(int64_t n);  // partial sums launch_norm leaves
 hipError_t launch_norm(const float* g, int64_t n, double* partials, hipStream_t stream);
 hipError_t launch_select(const SelectArgs& a, int32_t num_tensors, hipStream_t stream);

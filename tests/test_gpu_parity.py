@@ -9,7 +9,7 @@ import pytest
 from oracle import dgc_oracle as O
 from paper_1712_01887_amd import binding as B
 from paper_1712_01887_amd import synthetic as S
-from tests.parity import Pair, check_overflow_invariants, say
+from tests.parity import Pair, check_overflow_invariants, compare_under_scale_tolerance, say
 
 pytestmark = pytest.mark.gpu
 
@@ -73,6 +73,51 @@ def test_toy_four_workers_compress_then_accumulate():
         assert np.array_equal(dense.cpu().numpy().view(np.uint32), expect.view(np.uint32))
     for p in pairs:
         p.close()
+
+
+# ---------------------------------------------------------------------------
+# A clipping scale that is NOT the oracle's, on purpose: the library is handed the binary32
+# neighbour of the oracle's scale (what a reduction in another order can produce at worst)
+# and is held to the bar stated for that case: thresholds and sent values within 1e-6
+# relative, index sets differing only next to the threshold.  The states are then put back
+# and the iteration is repeated with the oracle's scale, bit for bit, so that the next
+# iteration starts from equal states.
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("flags,density,up", [(0, 0.001, True), (0, 0.05, False), (B.DGC_FLAG_NESTEROV, 0.01, True),
+                                              (B.DGC_FLAG_NO_FACTOR_MASKING, 0.25, False)])
+def test_scale_off_by_one_ulp_moves_the_index_set_only_at_the_threshold(flags, density, up):
+    import torch
+    sizes = [700001, 29, 300000, 4097, 1, 150016, 33333]
+    gs = S.GradientSet("ulp", tuple(S.TensorSpec(f"t{i}", (s,)) for i, s in enumerate(sizes)))
+    p = Pair(gs.offsets, layout_density=max(density, 0.02), momentum=0.9, density=density, flags=flags, seed=17,
+             clip_threshold=0.02, num_workers=4)
+    total_flips = 0
+    for it in range(3):
+        g = S.gradient(gs, 23, 0, it)
+        g_dev = torch.from_numpy(g).cuda()
+        u0, v0 = p.ou.copy(), p.ov.copy()
+        res = O.compress(g, p.ou, p.ov, p.offsets, p.ocfg, it, p.capacities)
+        assert res.scale < 1.0 and not res.overflow
+        off = np.nextafter(res.scale, np.float32(2.0 if up else 0.0), dtype=np.float32)
+        assert off != res.scale and abs(float(off) / float(res.scale) - 1.0) < 1.3e-7
+        u_keep, v_keep = p.u.clone(), p.v.clone()
+        p.dgc.dgc_set_scale_override(float(off))
+        diag, per_idx, per_val, counts, thr = p.run_library(g_dev, it)
+        assert np.float32(diag.scale) == off
+        total_flips += compare_under_scale_tolerance(p, g, u0, v0, res, per_idx, per_val, thr, p.u.cpu().numpy(),
+                                                     p.v.cpu().numpy(), f"ulp-off flags={flags} d={density} it{it}")
+        p.u.copy_(u_keep)
+        p.v.copy_(v_keep)
+        p.dgc.dgc_set_scale_override(float(res.scale))
+        diag, per_idx, per_val, counts, thr = p.run_library(g_dev, it)
+        p.dgc.dgc_set_scale_override(float("nan"))
+        assert np.array_equal(thr.view(np.uint32), res.thresholds.view(np.uint32))
+        for j in range(p.T):
+            assert np.array_equal(per_idx[j], res.indices[j]), (it, j)
+        assert np.array_equal(p.v.cpu().numpy().view(np.uint32), p.ov.view(np.uint32)), it
+        assert np.array_equal(p.u.cpu().numpy().view(np.uint32), p.ou.view(np.uint32)), it
+    say(f"[ulp-off] flags={flags} density={density}: {total_flips} index flips in 3 iterations")
+    p.close()
 
 
 # ---------------------------------------------------------------------------
