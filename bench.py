@@ -5,32 +5,44 @@ A step is one pass of the whole path for one worker of an N-worker job on a
 paper-shaped gradient set: dgc_compress of the worker's gradient (clipping norm
 when the configuration clips, sampled thresholds, streaming update + mask,
 emit = extraction + residual + factor masking), then the dense aggregate of N
-payloads (the fresh one and N - 1 from other seeded, correlated streams),
-merged by element range on chip, workers in order, no float atomics:
+payloads (the fresh one and N - 1 of other seeded, correlated streams), merged
+by element range on chip, workers in order, no float atomics:
 dgc_decompress_replace_regions writes it in place of the previous step's
 aggregate in one launch (--receive accumulate_clear: the same result from
 dgc_decompress_accumulate_regions into a zero buffer followed by
-dgc_dense_clear_regions).  Four workers' states
-(g, u, v) rotate so that no step finds its operands in the 256 MB last-level
-cache.  Inputs are generated on the host once, seeded, and are resident in HBM
-before the timed region.
+dgc_dense_clear_regions).  Four workers' states (g, u, v) rotate so that no
+step finds its operands in the 256 MB last-level cache, and with them four sets
+of the other workers' payloads, taken from four consecutive iterations of those
+workers: the previous step's payloads and the current ones share no buffer, and
+next to none of the previous indices recurs (a coordinate is sent once in many
+iterations), which is what the receive side sees in training.  Inputs are
+generated on the host once, seeded, and are resident in HBM before the timed
+region.
 
-The default workload is the one the headline metric is quoted on: the
-ResNet-50-shaped set (25,557,032 fp32 elements in 161 tensors, density 0.1 %,
-momentum 0.9, no clipping, N = 16).  --workload lstm | speech time the two
-larger sets for the record; --workload speech_warmup times the speech set's
-first 20 iterations under the warm-up schedule of densities (25 %, 6.25 %,
-1.5625 %, 0.4 %, then 0.1 %), where a step is one iteration at its density.
+The default run measures the largest configuration: the speech-model-shaped
+set (122,153,069 fp32 elements in 62 tensors, momentum 0.9, no clipping, N = 8)
+in the steady state of its warm-up schedule (density 0.1 %), which is what
+`value` is quoted on; the first iterations of the schedule (25 %, 6.25 %,
+1.5625 %, 0.4 %) are timed per density under "warmup_schedule", the same step
+with the Section 5 re-threshold switched on under "rethreshold", and the
+ResNet-50-shaped set (25,557,032 elements, 161 tensors, N = 16) under
+"resnet50".  --workload resnet50 | lstm | speech_literal make another set the
+headline; --only-headline skips the extra blocks.
 
 Prints one JSON line: whole-job throughput in dense gradient elements per
 second, the roofline of the dominant kernel (the streaming pass, 20 bytes per
-element) from HIP events recorded on the launch stream, and the CPU oracle timed
-on a bounded sample of the same workload.
+element) from HIP events recorded on the launch stream, the fraction of the HBM
+peak the whole dgc_compress call reaches, and the CPU oracle timed on a bounded
+sample of the same workload (one core, and one oracle worker per host core).
 """
 
 import argparse
+import ctypes as C
+import hashlib
 import json
+import math
 import os
+import re
 import sys
 import time
 
@@ -40,88 +52,473 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0           # MI355X published peak
 BYTES_PER_ELEMENT = 20           # streaming pass: read g, u, v; write u, v (fp32)
+MIN_TIMED_SECONDS = 0.2          # the timed region is repeated until it has run this long
+SEED = 2025
+WARMUP_DENSITIES = (0.25, 0.0625, 0.015625, 0.004, 0.001)
 
 WORKLOADS = {
     # name: (set constructor, config, N payloads accumulated, description)
+    "speech": ("speech_set", dict(momentum=0.9, density=0.001, seed=1, num_workers=8), 8,
+               "speech-model-shaped set (2 convolutions, 7 bidirectional GRU-1200 layers, output layer), 62 fp32 "
+               "tensors, 122,153,069 elements = 488 MB, N=8, m=0.9, no clipping, steady state of the warm-up "
+               "schedule (density 0.001; the iterations at 0.25 .. 0.004 are under warmup_schedule)"),
     "resnet50": ("resnet50_set", dict(momentum=0.9, density=0.001, seed=1, num_workers=16), 16,
                  "ResNet-50-shaped gradient set, 161 fp32 tensors, 25,557,032 elements, density 0.001, "
-                 "m=0.9, no clipping"),
+                 "m=0.9, no clipping, N=16"),
     "lstm": ("lstm_lm_set", dict(momentum=0.9, density=0.001, seed=1, num_workers=4, clip_threshold=0.25), 4,
              "2-layer LSTM-1500 language-model-shaped set, 11 fp32 tensors, 66,034,000 elements, density 0.001, "
              "m=0.9, clipping 0.25 with N=4"),
-    "speech": ("speech_set", dict(momentum=0.9, density=0.001, seed=1, num_workers=8), 8,
-               "speech-model-shaped set (7 bidirectional GRU-1200 layers), 62 fp32 tensors, 122,153,069 "
-               "elements, density 0.001 (steady state of the warm-up schedule), m=0.9, no clipping"),
     "speech_literal": ("speech_literal_set", dict(momentum=0.9, density=0.001, seed=1, num_workers=8), 8,
                        "speech set read literally from the benchmark's shapes (5 bidirectional GRU-1024 layers), 46 fp32 "
-                       "tensors, 90,192,061 elements, density 0.001, m=0.9, no clipping"),
+                       "tensors, 90,192,061 elements, density 0.001, m=0.9, no clipping, N=8"),
 }
 
-# HBM traffic of one streaming-kernel launch on the default workload from rocprofv3 --pmc
-# (FETCH_SIZE and WRITE_SIZE runs, each scaled by what the same counter reads for a
-# device copy of n floats): 308.3 MB read + 207.9 MB written.  The counters cannot be
-# read from inside this process; profiles/stream_kernel_resnet50_hbm_traffic.txt holds
-# the run this number comes from.
-MEASURED_TRAFFIC_BYTES = {"resnet50": 516176898}
+
+# ---------------------------------------------------------------------------
+# Calls with every argument marshalled ahead of time (ctypes objects are built once, so that
+# the measurement loop is the C calls and nothing else)
+# ---------------------------------------------------------------------------
+class PayloadList:
+    """Device pointers of several region-layout payloads.  Keeps the tensors alive."""
+
+    def __init__(self, B, idx_list, val_list, count_list):
+        self.tensors = (list(idx_list), list(val_list), list(count_list))
+        self.n = len(idx_list)
+        self.idx = B._ptr_array(idx_list)
+        self.val = B._ptr_array(val_list)
+        self.counts = B._ptr_array(count_list)
 
 
-WARMUP_DESCRIPTION = ("speech-model-shaped set, 62 fp32 tensors, 122,153,069 elements, m=0.9, no clipping, N=8, "
-                      "iterations 0..19 of the warm-up schedule (densities 0.25, 0.0625, 0.015625, 0.004, then 0.001)")
+class PreparedStep:
+    """One worker's compress call and the receive-side calls that follow it."""
+
+    def __init__(self, B, dgc, g, u, v, payload, current: PayloadList, dense, previous: PayloadList, stream):
+        dgc.ensure_workspace(g.device)
+        self.keep = (g, u, v, payload, current, dense, previous)
+        lib, h = dgc.lib, dgc._h
+        vp = C.c_void_p
+        stream = vp(stream)
+        out_idx, out_val, out_counts, out_thr = payload
+        ws, wsb = vp(dgc._ws_ptr), C.c_size_t(dgc._ws_bytes)
+        cargs = (h, vp(g.data_ptr()), vp(u.data_ptr()), vp(v.data_ptr()), vp(out_idx.data_ptr()),
+                 vp(out_val.data_ptr()), dgc._layout_c, vp(out_counts.data_ptr()), vp(out_thr.data_ptr()))
+        d = vp(dense.data_ptr())
+        aargs = (h, d, C.c_int32(current.n), current.idx, current.val, current.counts, dgc._layout_c, ws, wsb, stream)
+        kargs = (h, d, C.c_int32(current.n), current.idx, current.counts, dgc._layout_c, ws, wsb, stream)
+        rargs = (h, d, C.c_int32(current.n), current.idx, current.val, current.counts, C.c_int32(previous.n),
+                 previous.idx, previous.counts, dgc._layout_c, ws, wsb, stream)
+        sargs = (h, d, C.c_float(1e-3), C.c_int32(current.n), current.idx, current.val, current.counts,
+                 dgc._layout_c, ws, wsb, stream)
+
+        def compress(iteration: int) -> None:
+            B._check(lib.dgc_compress(*cargs, C.c_uint64(iteration), ws, wsb, stream), "dgc_compress")
+
+        def accumulate_clear() -> None:
+            B._check(lib.dgc_decompress_accumulate_regions(*aargs), "dgc_decompress_accumulate_regions")
+            B._check(lib.dgc_dense_clear_regions(*kargs), "dgc_dense_clear_regions")
+
+        def replace() -> None:
+            B._check(lib.dgc_decompress_replace_regions(*rargs), "dgc_decompress_replace_regions")
+
+        def sgd_apply() -> None:
+            B._check(lib.dgc_sparse_sgd_apply_regions(*sargs), "dgc_sparse_sgd_apply_regions")
+
+        self.compress = compress
+        self.receivers = {"replace": replace, "accumulate_clear": accumulate_clear, "sgd_apply": sgd_apply}
 
 
-def run_warmup_schedule(args):
-    """The speech set's first 20 iterations: dgc_set_iteration_density, dgc_compress of one
-    worker, accumulate of 8 payloads of that density, sparse clear.  --steps counts iterations
-    (rounded up to whole passes of 20), --warmup passes nothing but the first pass."""
+# ---------------------------------------------------------------------------
+# CPU baseline: the oracle as it stands.  Runs before anything touches the GPU (the
+# all-core leg forks).
+# ---------------------------------------------------------------------------
+def host_cores() -> int:
+    try:
+        return len(os.sched_getaffinity(0))
+    except AttributeError:
+        return os.cpu_count() or 1
+
+
+def _oracle_worker(job):
+    """One simulated worker in a process of its own: its gradient, then `iters` timed iterations."""
+    name, cfg_kw, worker, iters = job
+    import numpy as np
+    from oracle import dgc_oracle as O
+    from paper_1712_01887_amd import synthetic as S
+    set_name = WORKLOADS[name][0]
+    gs = getattr(S, set_name)()
+    scales = S.tensor_scales(gs, SEED)
+    g = S.gradient(gs, SEED, 2000 + worker, 0, scales)
+    if name == "lstm":
+        S.zero_inactive_embedding_rows(g, SEED, worker, 0)
+    cfg = O.OracleConfig(**{k: v for k, v in cfg_kw.items() if k != "flags"})
+    u = np.zeros(gs.numel, np.float32)
+    v = np.zeros(gs.numel, np.float32)
+    O.compress(g, u, v, gs.offsets, cfg, 0)                 # untimed: first touch of the buffers
+    t0 = time.perf_counter()
+    for it in range(iters):
+        O.compress(g, u, v, gs.offsets, cfg, it + 1)
+    return t0, time.perf_counter()
+
+
+def cpu_baseline(name, cfg_kw, n_workers, budget_s=12.0):
+    """The oracle, as it stands, on a bounded sample of the workload: (i) one process, numpy on
+    one thread; (ii) one oracle worker per host core at the same time, which is how the
+    workers of a data-parallel job would share a host (the oracle itself is not changed or
+    threaded for this)."""
+    import numpy as np
+    from oracle import dgc_oracle as O
+    from paper_1712_01887_amd import synthetic as S
+
+    gs = getattr(S, WORKLOADS[name][0])()
+    scales = S.tensor_scales(gs, SEED)
+    cfg = O.OracleConfig(**{k: v for k, v in cfg_kw.items() if k != "flags"})   # its payload is always ascending
+    u = np.zeros(gs.numel, np.float32)
+    v = np.zeros(gs.numel, np.float32)
+    grads = [S.gradient(gs, SEED, 0, it, scales) for it in range(2)]
+    if name == "lstm":
+        for it in range(2):
+            S.zero_inactive_embedding_rows(grads[it], SEED, 0, it)
+    O.compress(grads[0], u, v, gs.offsets, cfg, 0)                     # untimed: first touch of the buffers
+    t_comp, iters, res = 0.0, 0, None
+    while iters < 3 or (t_comp < budget_s and iters < 400):
+        t0 = time.perf_counter()
+        res = O.compress(grads[(iters + 1) % 2], u, v, gs.offsets, cfg, iters + 1)
+        t_comp += time.perf_counter() - t0
+        iters += 1
+    payload = O.flatten_payload(res)
+    dense = np.zeros(gs.numel, np.float32)
+    reps = 3
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        O.decompress_accumulate(dense, [payload] * n_workers)
+        dense[payload[0]] = 0.0                                        # sparse clear, as the GPU step does
+    t_acc = (time.perf_counter() - t0) / reps
+    per_step = t_comp / iters + t_acc
+    del grads, u, v, dense
+    out = {
+        "value": gs.numel / per_step,
+        "unit": "elements/s",
+        "cores": 1,
+        "host_cores": host_cores(),
+        "kind": "oracle",
+        "sample": f"{iters} compress iterations of the full {name} set "
+                  f"({t_comp / iters * 1e3:.0f} ms each) + accumulate/clear of {n_workers} payloads "
+                  f"({t_acc * 1e3:.1f} ms), numpy, single thread",
+    }
+    # (ii) all cores: one oracle worker per core, each compressing its own gradient
+    cores = max(1, min(16, host_cores()))
+    if cores > 1:
+        import multiprocessing as mp
+        each = max(2, min(6, int(math.ceil(budget_s / max(1e-3, 2.0 * t_comp / iters)))))
+        with mp.get_context("fork").Pool(cores) as pool:
+            spans = pool.map(_oracle_worker, [(name, cfg_kw, w, each) for w in range(cores)])
+        # wall clock from the first worker's start to the last one's end (perf_counter is system-wide on Linux)
+        wall = max(s[1] for s in spans) - min(s[0] for s in spans)
+        out["all_cores"] = {
+            "value": cores * each * gs.numel / wall,
+            "unit": "elements/s (compress only, summed over the workers)",
+            "cores": cores,
+            "sample": f"{cores} processes at once, one simulated worker each, {each} compress iterations of the full "
+                      f"{name} set per worker, {wall:.1f} s wall clock",
+        }
+    return out
+
+
+# ---------------------------------------------------------------------------
+# HBM traffic of the streaming kernel: read from the rocprofv3 summary under profiles/, and
+# only if that summary was made from the kernel sources as they are now
+# ---------------------------------------------------------------------------
+def source_hash() -> str:
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_1712_01887_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload: str):
+    """Bytes one stream_kernel launch moved through HBM according to
+    profiles/stream_kernel_<workload>_hbm_traffic.txt, or None when there is no such summary or
+    it was made from other kernel sources (its `source_hash` line)."""
+    path = os.path.join(ROOT, "profiles", f"stream_kernel_{workload}_hbm_traffic.txt")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    m_hash = re.search(r"^source_hash:\s*([0-9a-f]+)", text, re.M)
+    m_bytes = re.search(r"^stream_kernel traffic per launch = ([0-9,]+) bytes", text, re.M)
+    if not m_hash or not m_bytes or m_hash.group(1) != source_hash():
+        return None
+    return int(m_bytes.group(1).replace(",", ""))
+
+
+# ---------------------------------------------------------------------------
+# One workload on the GPU
+# ---------------------------------------------------------------------------
+def make_gradient(S, name, gs, worker, shared, scales):
+    g = S.correlated_gradient(gs, SEED, worker, 0, shared, scales=scales)
+    if name == "lstm":      # the embedding gradient touches 700 seeded rows only
+        S.zero_inactive_embedding_rows(g, SEED, worker, 0)
+    return g
+
+
+def percentile_stats(xs):
+    xs = sorted(xs)
+    return {"median": xs[len(xs) // 2], "best": xs[0], "worst": xs[-1]}
+
+
+class Workload:
+    """A gradient set resident in HBM: ROTATE worker states, ROTATE sets of the other workers'
+    payloads, the aggregate, and the prepared calls."""
+
+    def __init__(self, name, args, cfg_extra=None, shared_inputs=None):
+        import torch
+        from paper_1712_01887_amd import binding as B
+        from paper_1712_01887_amd import synthetic as S
+        self.torch, self.B = torch, B
+        self.name = name
+        set_name, cfg_kw, self.n_workers, self.description = WORKLOADS[name]
+        self.cfg_kw = dict(cfg_kw)
+        if args.sample_block:
+            self.cfg_kw["sample_block"] = args.sample_block
+        if args.sorted:
+            self.cfg_kw["flags"] = self.cfg_kw.get("flags", 0) | B.DGC_FLAG_SORTED_OUTPUT
+            self.description += ", sorted payload"
+        if cfg_extra:
+            self.cfg_kw.update(cfg_extra)
+        self.clip = self.cfg_kw.get("clip_threshold", 0.0) > 0.0
+        self.gs = gs = getattr(S, set_name)()
+        self.n = n = gs.numel
+        self.rotate = R = max(2, args.rotate)
+        self.receive = args.receive
+        dev = "cuda"
+        self.stream = int(torch.cuda.current_stream().cuda_stream)
+        self.dgc = dgc = B.Dgc(B.make_config(**self.cfg_kw), gs.offsets)
+        dgc.set_layout(dgc.dgc_recommended_payload_layout(self.cfg_kw["density"]))
+        if shared_inputs is not None:                     # same inputs as another Workload on the same set
+            self.g_pool, self.g_others = shared_inputs
+        else:
+            scales = S.tensor_scales(gs, SEED)
+            shared = S.gradient(gs, SEED, 999, 0, scales)
+            self.g_pool = [torch.from_numpy(make_gradient(S, name, gs, r, shared, scales)).to(dev) for r in range(R)]
+            self.g_others = [torch.from_numpy(make_gradient(S, name, gs, 100 + w, shared, scales)).to(dev)
+                             for w in range(self.n_workers - 1)]
+            del shared
+        self.u = [torch.zeros(n, device=dev) for _ in range(R)]
+        self.v = [torch.zeros(n, device=dev) for _ in range(R)]
+        self.fresh = [dgc.alloc_payload(dev) for _ in range(R)]
+        # the other N - 1 workers: R consecutive iterations of each (its state evolves, so the sets of sent
+        # indices of consecutive iterations are next to disjoint); set r holds iteration r of every worker
+        self.others = [[None] * (self.n_workers - 1) for _ in range(R)]
+        tu = torch.zeros(n, device=dev)
+        tv = torch.zeros(n, device=dev)
+        for w, gw in enumerate(self.g_others):
+            tu.zero_()
+            tv.zero_()
+            for r in range(R):
+                pl = dgc.alloc_payload(dev)
+                dgc.dgc_compress(gw, tu, tv, pl[0], pl[1], pl[2], pl[3], r)
+                self.others[r][w] = pl
+        torch.cuda.synchronize()
+        del tu, tv
+        self.dense = torch.zeros(n, device=dev)
+        self.plists = [PayloadList(B, [self.fresh[r][0]] + [o[0] for o in self.others[r]],
+                                   [self.fresh[r][1]] + [o[1] for o in self.others[r]],
+                                   [self.fresh[r][2]] + [o[2] for o in self.others[r]]) for r in range(R)]
+        for r in range(R):                                 # no buffer in both a step's list and its predecessor's
+            a = {t.data_ptr() for t in self.plists[r].tensors[0]}
+            b = {t.data_ptr() for t in self.plists[(r - 1) % R].tensors[0]}
+            assert not (a & b)
+        self.prepared = {}
+        for r in range(R):
+            for q in range(R):
+                self.prepared[(r, q)] = PreparedStep(B, dgc, self.g_pool[q], self.u[r], self.v[r], self.fresh[r],
+                                                     self.plists[r], self.dense, self.plists[(r - 1) % R], self.stream)
+        self.next_step = 0
+
+    def inputs(self):
+        return self.g_pool, self.g_others
+
+    def step(self, i, events=None):
+        R = self.rotate
+        r, it = i % R, i // R
+        p = self.prepared[(r, (r + it) % R)]
+        if events is not None:
+            events[0].record()
+        p.compress(it)
+        if events is not None:
+            events[1].record()
+        p.receivers[self.receive]()
+        if events is not None:
+            events[2].record()
+
+    def run_steps(self, count, events=None):
+        for k in range(count):
+            self.step(self.next_step, None if events is None else events[k])
+            self.next_step += 1
+
+    def measure(self, steps, warmup, kernel_breakdown=True):
+        """Timed passes of `steps` steps each until MIN_TIMED_SECONDS have run, then the same steps with events."""
+        torch, dgc, n = self.torch, self.dgc, self.n
+        self.run_steps(warmup)
+        torch.cuda.synchronize()
+        pass_ms, total, passes = [], 0.0, 0
+        while passes == 0 or (total < MIN_TIMED_SECONDS and passes < 1000):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            self.run_steps(steps)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            pass_ms.append(dt / steps * 1e3)
+            total += dt
+            passes += 1
+        ms_per_step = total / (passes * steps) * 1e3
+        spread = percentile_stats(pass_ms)
+        out = {
+            "value": n / (ms_per_step * 1e-3),
+            "ms_per_step": round(ms_per_step, 5),
+            "passes": passes,
+            "timed_seconds": round(total, 4),
+            "ms_per_step_over_passes": {k: round(x, 5) for k, x in spread.items()},
+        }
+        # -- events around the two calls of a step (no events between the kernels of a call) --------
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        self.run_steps(steps, ev)
+        torch.cuda.synchronize()
+        comp = sorted(e[0].elapsed_time(e[1]) for e in ev)
+        recv = sorted(e[1].elapsed_time(e[2]) for e in ev)
+        comp_ms = sum(comp) / steps
+        call_bytes = (BYTES_PER_ELEMENT + (4 if self.clip else 0)) * n
+        breakdown = {
+            "compress_call_us": round(comp_ms * 1e3, 2),
+            "compress_call_us_median": round(comp[steps // 2] * 1e3, 2),
+            "compress_call_us_best": round(comp[0] * 1e3, 2),
+            self.receive + "_us": round(sum(recv) / steps * 1e3, 2),
+        }
+        out["compress_frac"] = round(call_bytes / (comp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
+        out["compress_call"] = {
+            "algorithmic_bytes": call_bytes, "bytes_per_element": call_bytes // n,
+            "GBps": round(call_bytes / (comp_ms * 1e-3) / 1e9, 1),
+            "what": "whole dgc_compress call (norm when clipping, select, stream, emit and the gaps between them), HIP "
+                    "events before and after the call, mean over the steps, against the 8 TB/s peak",
+        }
+        roofline = None
+        if kernel_breakdown:
+            # -- events between the kernels of dgc_compress (they add a few us of gaps each) --------------
+            dgc.dgc_profile_enable(steps)
+            self.run_steps(steps)
+            torch.cuda.synchronize()
+            calls, norm_ms, select_ms, stream_ms, emit_ms = dgc.dgc_profile_collect()
+            dgc.dgc_profile_disable()
+            stream_avg_ms = stream_ms / calls
+            achieved = BYTES_PER_ELEMENT * n / (stream_avg_ms * 1e-3) / 1e9
+            roofline = {
+                "bound": "hbm",
+                "kernel": "stream_kernel",
+                "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                "traffic": measured_traffic(self.name),
+                "algorithmic_bytes": BYTES_PER_ELEMENT * n,
+                "avg_kernel_us": round(stream_avg_ms * 1e3, 2),
+            }
+            breakdown.update({
+                "norm_kernel_us": round(norm_ms / calls * 1e3, 2) if self.clip else None,
+                "select_kernel_us": round(select_ms / calls * 1e3, 2),
+                "stream_kernel_us": round(stream_avg_ms * 1e3, 2),
+                "emit_kernel_us": round(emit_ms / calls * 1e3, 2),
+            })
+            if self.clip:
+                breakdown["norm_kernel_GBps"] = round(4 * n / (norm_ms / calls * 1e-3) / 1e9, 1)
+            # the box's own ceiling for this traffic: the bare three-read / two-write kernel on the same
+            # rotating buffers, timed the same way (it overwrites u and v: last use of this workload's state)
+            R = self.rotate
+            cev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+            for k in range(warmup + steps):
+                r = k % R
+                if k >= warmup:
+                    cev[k - warmup][0].record()
+                self.B.dgc_profile_stream_ceiling(self.g_pool[(r + k // R) % R], self.u[r], self.v[r])
+                if k >= warmup:
+                    cev[k - warmup][1].record()
+            torch.cuda.synchronize()
+            ceil_ms = sum(e[0].elapsed_time(e[1]) for e in cev) / steps
+            ceiling = BYTES_PER_ELEMENT * (n // 1024 * 1024) / (ceil_ms * 1e-3) / 1e9
+            roofline["practical_ceiling"] = {
+                "kernel": "ceiling_kernel (3 arrays read, 2 written, non-temporal, same tiling, no table, no mask)",
+                "achieved": round(ceiling, 1), "unit": "GB/s", "avg_kernel_us": round(ceil_ms * 1e3, 2),
+                "stream_kernel_frac_of_it": round(achieved / ceiling, 4)}
+        counts = max(1, int(self.fresh[0][2].sum().item()))
+        out["pairs_per_payload"] = counts
+        out["compression_ratio"] = {"ours_8B_pairs": round(4.0 * n / (8 * counts), 1),
+                                    "ours_6B_entries": round(4.0 * n / (6 * counts), 1)}
+        out["breakdown"] = breakdown
+        out["roofline"] = roofline
+        return out
+
+    def profile_only_tail(self, steps):
+        """For rocprofv3 runs: a plain device copy of known size (n floats in, n floats out) for scaling the
+        FETCH_SIZE / WRITE_SIZE counters, and the bare streaming kernel for its duration in the same trace."""
+        torch, R = self.torch, self.rotate
+        for _ in range(3):
+            self.dense.copy_(self.g_pool[0])
+        self.dense.zero_()
+        for k in range(steps):
+            r = k % R
+            self.B.dgc_profile_stream_ceiling(self.g_pool[(r + k // R) % R], self.u[r], self.v[r])
+        torch.cuda.synchronize()
+
+    def close(self):
+        self.dgc.close()
+
+
+def warmup_schedule_block(args, g_pool, g_others):
+    """The speech set's first iterations (Section 4.1's sparsities as densities 25 %, 6.25 %, 1.5625 %, 0.4 %,
+    then 0.1 %): per density, dgc_compress of one worker (workspace with staging arrays) and the aggregate of
+    8 payloads of that density written in place of the previous iteration's."""
     import torch
     from paper_1712_01887_amd import binding as B
     from paper_1712_01887_amd import synthetic as S
 
-    dev, N, seed, iters = "cuda", 8, 2025, 20
+    dev, N, iters = "cuda", 8, 20
     gs = S.speech_set()
     n = gs.numel
-    scales = S.tensor_scales(gs, seed)
+    stream = int(torch.cuda.current_stream().cuda_stream)
     dgc = B.Dgc(B.make_config(momentum=0.9, density=0.001, seed=1, num_workers=N), gs.offsets, warmup_workspace=True)
     dgc.set_layout(dgc.dgc_recommended_payload_layout(0.25))
-    shared = S.gradient(gs, seed, 999, 0, scales)
-    g_pool = [torch.from_numpy(S.correlated_gradient(gs, seed, r, 0, shared, scales=scales)).to(dev) for r in range(2)]
     u = torch.zeros(n, device=dev)
     v = torch.zeros(n, device=dev)
     dense = torch.zeros(n, device=dev)
     fresh = [dgc.alloc_payload(dev) for _ in range(2)]
-    stage_of = [min(i, 4) for i in range(iters)]
-    others = []                                   # per stage: N - 1 payloads of that density
-    gw = [torch.from_numpy(S.correlated_gradient(gs, seed, 100 + w, 0, shared, scales=scales)).to(dev)
-          for w in range(N - 1)]
-    for stage in range(5):
-        dgc.dgc_set_iteration_density(stage)
-        pls = []
-        for w in range(N - 1):
-            u.zero_()
-            v.zero_()
+    # the other 7 workers run the schedule too: iteration i of every worker, i = 0 .. 5 (two sets at 0.1 %,
+    # so that consecutive steady-state iterations do not share them)
+    others = [[None] * (N - 1) for _ in range(6)]
+    for w, gw in enumerate(g_others):
+        u.zero_()
+        v.zero_()
+        for i in range(6):
+            dgc.dgc_set_iteration_density(i)
             pl = dgc.alloc_payload(dev)
-            dgc.dgc_compress(gw[w], u, v, pl[0], pl[1], pl[2], pl[3], 0)
-            pls.append(pl)
-        others.append(pls)
+            dgc.dgc_compress(gw, u, v, pl[0], pl[1], pl[2], pl[3], i)
+            others[i][w] = pl
     torch.cuda.synchronize()
-    del gw
     u.zero_()
     v.zero_()
-    replace = args.receive == "replace"
+    set_of = [i if i < 4 else 4 + (i & 1) for i in range(iters)]
     plists = {}
-    for stage in range(5):
-        o = others[stage]
-        for q in range(2):
-            f = fresh[q]
-            plists[(stage, q)] = B.PayloadList([f[0]] + [x[0] for x in o], [f[1]] + [x[1] for x in o],
-                                               [f[2]] + [x[2] for x in o])
-    prepared = []                                  # iteration i: gradient and payload buffer i & 1
+    for i in range(iters):
+        key = (set_of[i], i & 1)
+        if key not in plists:
+            f, o = fresh[i & 1], others[set_of[i]]
+            plists[key] = PayloadList(B, [f[0]] + [x[0] for x in o], [f[1]] + [x[1] for x in o],
+                                      [f[2]] + [x[2] for x in o])
+    prepared = []
     for i in range(iters):
         before = (i - 1) % iters
-        prepared.append(B.PreparedStep(dgc, g_pool[i & 1], u, v, fresh[i & 1], plists[(stage_of[i], i & 1)], dense,
-                                       previous=plists[(stage_of[before], before & 1)]))
-    for p in prepared:
-        p.receive = p.replace if replace else p.accumulate_and_clear
+        prepared.append(PreparedStep(B, dgc, g_pool[i & 1], u, v, fresh[i & 1], plists[(set_of[i], i & 1)], dense,
+                                     plists[(set_of[before], before & 1)], stream))
 
     def one_pass(events=None):
         for i in range(iters):
@@ -132,119 +529,76 @@ def run_warmup_schedule(args):
             p.compress(i)
             if events is not None:
                 events[i][1].record()
-            p.receive()
+            p.receivers[args.receive]()
             if events is not None:
                 events[i][2].record()
 
-    passes = max(1, (args.steps + iters - 1) // iters)
     one_pass()
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(passes):
+    times = []
+    total = 0.0
+    while not times or (total < MIN_TIMED_SECONDS and len(times) < 100):
+        t0 = time.perf_counter()
         one_pass()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / (passes * iters) * 1e3
+        torch.cuda.synchronize()
+        times.append(time.perf_counter() - t0)
+        total += times[-1]
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(iters)]
     one_pass(ev)
     torch.cuda.synchronize()
-    per_iteration = [{"iteration": i, "density": [0.25, 0.0625, 0.015625, 0.004, 0.001][stage_of[i]],
-                      "compress_us": round(ev[i][0].elapsed_time(ev[i][1]) * 1e3, 1),
-                      "replace_us" if replace else "accumulate_and_clear_us":
-                          round(ev[i][1].elapsed_time(ev[i][2]) * 1e3, 1)}
-                     for i in range(6)]
-    out = {
-        "metric": "dense gradient elements/s for compress+decompress",
-        "value": n / (ms_per_step * 1e-3),
-        "unit": "elements/s",
-        "n_gpus": 1,
-        "steps": passes * iters,
-        "warmup": iters,
-        "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "f32",
-        "data": "synthetic",
-        "config": {"workload": WARMUP_DESCRIPTION + "; step = one iteration: compress one worker + " +
-                               ("aggregate of 8 payloads written in place of the previous one" if replace else
-                                "accumulate 8 payloads + sparse clear") + "; workspace with staging arrays",
-                   "elements": n, "tensors": len(gs.sizes), "workers_accumulated": N},
-        "ms_per_20_iterations": round(ms_per_step * iters, 3),
-        "first_iterations": per_iteration,
-        "roofline": None,
+    per_density = []
+    for i in range(5):
+        d = WARMUP_DENSITIES[i]
+        c_us = ev[i][0].elapsed_time(ev[i][1]) * 1e3
+        r_us = ev[i][1].elapsed_time(ev[i][2]) * 1e3
+        per_density.append({"iteration": i, "density": d, "compress_us": round(c_us, 1), args.receive + "_us": round(r_us, 1),
+                            "step_us": round(c_us + r_us, 1),
+                            "compress_frac": round(BYTES_PER_ELEMENT * n / (c_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4)})
+    ms20 = total / len(times) * 1e3
+    dgc.close()
+    return {
+        "what": "iterations 0..19 of the warm-up schedule on the speech set, N=8: density 0.25, 0.0625, 0.015625, 0.004, "
+                "then 0.001; a step = compress one worker (workspace with staging arrays) + aggregate of 8 payloads",
+        "ms_per_20_iterations": round(ms20, 3),
+        "ms_per_20_iterations_best": round(min(times) * 1e3, 3),
+        "passes": len(times),
+        "elements_per_s_over_the_schedule": 20 * n / (ms20 * 1e-3),
+        "per_density": per_density,
     }
-    print(json.dumps(out))
 
 
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", choices=sorted(WORKLOADS) + ["speech_warmup"], default="resnet50")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", choices=sorted(WORKLOADS), default="speech")
+    ap.add_argument("--only-headline", action="store_true",
+                    help="skip the extra blocks of the default run (warm-up schedule, re-threshold, ResNet-50 set)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sample-block", type=int, default=None, help="override dgc_config.sample_block")
     ap.add_argument("--refine-alpha", type=float, default=None,
-                    help="switch the Section 5 re-threshold on (dgc_config.refine_alpha); off by default")
+                    help="switch the Section 5 re-threshold on in the headline (dgc_config.refine_alpha)")
     ap.add_argument("--sorted", action="store_true",
                     help="emit every tensor's pairs in ascending index order (DGC_FLAG_SORTED_OUTPUT)")
     ap.add_argument("--receive", choices=["replace", "accumulate_clear", "sgd_apply"], default="replace",
-                    help="receive side of a step: dgc_decompress_accumulate_regions + dgc_dense_clear_regions, or "
-                         "dgc_decompress_replace_regions (the aggregate written in place of the previous one), or "
+                    help="receive side of a step: dgc_decompress_replace_regions (the aggregate written in place of "
+                         "the previous one), or dgc_decompress_accumulate_regions + dgc_dense_clear_regions, or "
                          "dgc_sparse_sgd_apply_regions (no aggregate: the dense buffer plays the parameters, lr 1e-3)")
     ap.add_argument("--rotate", type=int, default=4,
-                    help="independent (g, u, v) sets the steps rotate through; 4 keeps every step's operands out of the "
-                         "last-level cache (the default and the headline), 1 shows the cache-resident case")
+                    help="independent (g, u, v) sets and sets of other workers' payloads the steps rotate through "
+                         "(at least 2)")
     ap.add_argument("--profile-only", action="store_true",
-                    help="skip the CPU baseline and the event-instrumented pass (for rocprofv3 runs)")
+                    help="for rocprofv3 runs: the timed steps of the headline workload, a device copy of known size and "
+                         "the bare streaming kernel; no events, no CPU baseline, no extra blocks")
     return ap.parse_args()
 
 
-def make_gradient(S, name, gs, seed, worker, shared, scales):
-    g = S.correlated_gradient(gs, seed, worker, 0, shared, scales=scales)
-    if name == "lstm":      # the embedding gradient touches 700 seeded rows only
-        S.zero_inactive_embedding_rows(g, seed, worker, 0)
-    return g
-
-
-def cpu_baseline(name, gs, cfg_kw, n_workers, scales, seed):
-    """The oracle, as it stands, on a bounded sample of the same workload."""
-    import numpy as np
-    from oracle import dgc_oracle as O
-    from paper_1712_01887_amd import synthetic as S
-
-    cfg = O.OracleConfig(**{k: v for k, v in cfg_kw.items() if k != "flags"})   # its payload is always ascending
-    u = np.zeros(gs.numel, np.float32)
-    v = np.zeros(gs.numel, np.float32)
-    grads = [S.gradient(gs, seed, 0, it, scales) for it in range(4)]
-    O.compress(grads[0], u, v, gs.offsets, cfg, 0)                     # untimed: first touch of the buffers
-    t_comp = 0.0
-    iters = 0
-    res = None
-    while iters < 3 or (t_comp < 10.0 and iters < 400):       # about ten seconds of CPU work
-        t0 = time.perf_counter()
-        res = O.compress(grads[(iters + 1) % 4], u, v, gs.offsets, cfg, iters + 1)
-        t_comp += time.perf_counter() - t0
-        iters += 1
-    payload = O.flatten_payload(res)
-    dense = np.zeros(gs.numel, np.float32)
-    reps = 5
-    t0 = time.perf_counter()
-    for _ in range(reps):
-        O.decompress_accumulate(dense, [payload] * n_workers)
-        dense[payload[0]] = 0.0                                        # sparse clear, as the GPU step does
-    t_acc = (time.perf_counter() - t0) / reps
-    per_step = t_comp / iters + t_acc
-    return {
-        "value": gs.numel / per_step,
-        "unit": "elements/s",
-        "cores": 1,
-        "kind": "oracle",
-        "sample": f"{iters} compress iterations of the full {name} set "
-                  f"({t_comp / iters * 1e3:.0f} ms each) + accumulate/clear of {n_workers} payloads "
-                  f"({t_acc * 1e3:.1f} ms), numpy, single thread",
-    }
+RECEIVE_TEXT = {
+    "replace": "aggregate of {n} payloads written in place of the previous one",
+    "accumulate_clear": "accumulate {n} payloads + sparse clear",
+    "sgd_apply": "sparse SGD apply of {n} payloads",
+}
 
 
 def main():
@@ -253,213 +607,113 @@ def main():
         print("bench.py measures one GPU: the path has no collective and this build runs on a "
               "single MI355X; use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    name = args.workload
+    extras = name == "speech" and not (args.only_headline or args.profile_only)
+
+    # the oracle first: its all-core leg forks, which must happen before the GPU is initialised
+    cpu = None
+    if not (args.no_cpu_baseline or args.profile_only):
+        cpu = cpu_baseline(name, WORKLOADS[name][1], WORKLOADS[name][2])
 
     import torch
-    from paper_1712_01887_amd import binding as B
-    from paper_1712_01887_amd import synthetic as S
-
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
-    if args.workload == "speech_warmup":
-        run_warmup_schedule(args)
-        return
-    dev = "cuda"
-    ROTATE = max(1, args.rotate)
-    set_name, cfg_kw, n_workers, description = WORKLOADS[args.workload]
-    cfg_kw = dict(cfg_kw)
-    gs = getattr(S, set_name)()
-    n = gs.numel
-    seed = 2025
-    scales = S.tensor_scales(gs, seed)
-    if args.sample_block:
-        cfg_kw["sample_block"] = args.sample_block
-    if args.refine_alpha:
-        cfg_kw["refine_alpha"] = args.refine_alpha
-        description += f", re-threshold when more than {args.refine_alpha:g} k pass"
-    if args.sorted:
-        cfg_kw["flags"] = cfg_kw.get("flags", 0) | B.DGC_FLAG_SORTED_OUTPUT
-        description += ", sorted payload"
-    clip = cfg_kw.get("clip_threshold", 0.0) > 0.0
 
-    dgc = B.Dgc(B.make_config(**cfg_kw), gs.offsets)
-    layout = dgc.dgc_recommended_payload_layout(cfg_kw["density"])
-    dgc.set_layout(layout)
-
-    # ---- inputs, resident in HBM ----------------------------------------------
-    shared = S.gradient(gs, seed, 999, 0, scales)
-    g_pool = [torch.from_numpy(make_gradient(S, args.workload, gs, seed, r, shared, scales)).to(dev)
-              for r in range(ROTATE)]
-    u = [torch.zeros(n, device=dev) for _ in range(ROTATE)]
-    v = [torch.zeros(n, device=dev) for _ in range(ROTATE)]
-    fresh = [dgc.alloc_payload(dev) for _ in range(ROTATE)]
-    # N - 1 payloads of other workers: one compress each of a correlated stream
-    others = []
-    tu = torch.zeros(n, device=dev)
-    tv = torch.zeros(n, device=dev)
-    for w in range(n_workers - 1):
-        gw = torch.from_numpy(make_gradient(S, args.workload, gs, seed, 100 + w, shared, scales)).to(dev)
-        tu.zero_()
-        tv.zero_()
-        pl = dgc.alloc_payload(dev)
-        dgc.dgc_compress(gw, tu, tv, pl[0], pl[1], pl[2], pl[3], 0)
-        others.append(pl)
-    torch.cuda.synchronize()
-    del tu, tv, gw
-    dense = torch.zeros(n, device=dev)
-
-    # every argument marshalled once: worker r with gradient slot q
-    replace = args.receive == "replace"
-    if replace and ROTATE < 2:
-        print("--receive replace needs --rotate >= 2: the previous step's payload must stay intact", file=sys.stderr)
-        sys.exit(2)
-    prepared = {}
-    plists = [B.PayloadList([f[0]] + [o[0] for o in others], [f[1]] + [o[1] for o in others],
-                            [f[2]] + [o[2] for o in others]) for f in fresh]
-    for r in range(ROTATE):
-        for q in range(ROTATE):
-            prepared[(r, q)] = B.PreparedStep(dgc, g_pool[q], u[r], v[r], fresh[r], plists[r], dense,
-                                              previous=plists[(r - 1) % ROTATE])
-    for p in prepared.values():
-        p.receive = {"replace": p.replace, "accumulate_clear": p.accumulate_and_clear,
-                     "sgd_apply": p.sgd_apply}[args.receive]
-
-    def step(i):
-        r = i % ROTATE
-        it = i // ROTATE
-        p = prepared[(r, (r + it) % ROTATE)]
-        p.compress(it)
-        p.receive()
-
-    # ---- warm-up, then the timed region -------------------------------------------
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.warmup, args.warmup + args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed / args.steps * 1e3
-
+    extra_cfg = {"refine_alpha": args.refine_alpha} if args.refine_alpha else None
+    wl = Workload(name, args, extra_cfg)
+    description = wl.description + (f", re-threshold when more than {args.refine_alpha:g} k pass"
+                                    if args.refine_alpha else "")
     if args.profile_only:
-        # a plain device copy of known size (n floats in, n floats out) for scaling the
-        # FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc runs
-        for _ in range(3):
-            dense.copy_(g_pool[0])
-        dense.zero_()
-        for k in range(args.steps):               # the bare streaming kernel, for its duration in the same trace
-            r = k % ROTATE
-            B.dgc_profile_stream_ceiling(g_pool[(r + k // ROTATE) % ROTATE], u[r], v[r])
+        wl.run_steps(args.warmup)
         torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        wl.run_steps(args.steps)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / args.steps * 1e3
+        wl.profile_only_tail(args.steps)
+        print(json.dumps({"metric": "dense gradient elements/s for compress+decompress", "value": wl.n / (ms * 1e-3),
+                          "unit": "elements/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                          "ms_per_step": round(ms, 5), "config": {"workload": description}, "profile_only": True}))
+        return
 
-    # ---- the same steps again with HIP events on the launch stream ----------------------
-    roofline = None
-    breakdown = {}
-    if not args.profile_only:
-        dgc.dgc_profile_enable(args.steps)
-        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-        base = args.warmup + args.steps
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        for k in range(args.steps):
-            i = base + k
-            r = i % ROTATE
-            it = i // ROTATE
-            p = prepared[(r, (r + it) % ROTATE)]
-            ev[k][0].record()
-            p.compress(it)
-            ev[k][1].record()
-            p.receive()
-            ev[k][2].record()
-        torch.cuda.synchronize()
-        profiled_ms = (time.perf_counter() - t1) / args.steps * 1e3
-        calls, norm_ms, select_ms, stream_ms, emit_ms = dgc.dgc_profile_collect()
-        dgc.dgc_profile_disable()
-        stream_avg_ms = stream_ms / calls
-        achieved = BYTES_PER_ELEMENT * n / (stream_avg_ms * 1e-3) / 1e9
-        roofline = {
-            "bound": "hbm",
-            "kernel": "stream_kernel",
-            "achieved": round(achieved, 1),
-            "peak": HBM_PEAK_GBPS,
-            "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
-            "algorithmic_bytes": BYTES_PER_ELEMENT * n,
-            "avg_kernel_us": round(stream_avg_ms * 1e3, 2),
-        }
-        # the box's own ceiling for this traffic: the bare three-read / two-write kernel on the same
-        # rotating buffers, timed the same way (u and v are not needed any more)
-        cev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
-        for k in range(args.warmup + args.steps):
-            r = k % ROTATE
-            if k >= args.warmup:
-                cev[k - args.warmup][0].record()
-            B.dgc_profile_stream_ceiling(g_pool[(r + k // ROTATE) % ROTATE], u[r], v[r])
-            if k >= args.warmup:
-                cev[k - args.warmup][1].record()
-        torch.cuda.synchronize()
-        ceil_ms = sum(e[0].elapsed_time(e[1]) for e in cev) / args.steps
-        ceiling = BYTES_PER_ELEMENT * (n // 1024 * 1024) / (ceil_ms * 1e-3) / 1e9
-        roofline["practical_ceiling"] = {
-            "kernel": "ceiling_kernel (3 arrays read, 2 written, non-temporal, same tiling, no table, no mask)",
-            "achieved": round(ceiling, 1), "unit": "GB/s", "avg_kernel_us": round(ceil_ms * 1e3, 2),
-            "stream_kernel_frac_of_it": round(achieved / ceiling, 4)}
-        comp = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
-        acc = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
-        per_step = sorted(e[0].elapsed_time(e[2]) for e in ev)
-        breakdown = {
-            "step_us_median_by_events": round(per_step[len(per_step) // 2] * 1e3, 2),
-            "step_us_best_by_events": round(per_step[0] * 1e3, 2),
-            "compress_us": round(comp * 1e3, 2),
-            "norm_kernel_us": round(norm_ms / calls * 1e3, 2) if clip else None,
-            "select_kernel_us": round(select_ms / calls * 1e3, 2),
-            "stream_kernel_us": round(stream_avg_ms * 1e3, 2),
-            "emit_kernel_us": round(emit_ms / calls * 1e3, 2),
-            {"replace": "replace_us", "accumulate_clear": "accumulate_and_clear_us",
-             "sgd_apply": "sgd_apply_us"}[args.receive]: round(acc * 1e3, 2),
-            "ms_per_step_with_events": round(profiled_ms, 5),
-        }
-        if clip:
-            nb = 4 * n / (norm_ms / calls * 1e-3) / 1e9
-            breakdown["norm_kernel_GBps"] = round(nb, 1)
-
-    counts = max(1, int(fresh[0][2].sum().item()))   # (payload counters: untouched by the ceiling probe)
-    step_bytes = (BYTES_PER_ELEMENT + (4 if clip else 0)) * n
+    inputs = wl.inputs()
+    m = wl.measure(args.steps, args.warmup)
+    n = wl.n
+    step_bytes = (BYTES_PER_ELEMENT + (4 if wl.clip else 0)) * n
     out = {
         "metric": "dense gradient elements/s for compress+decompress",
-        "value": n / (ms_per_step * 1e-3),
+        "value": m["value"],
         "unit": "elements/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 5),
+        "ms_per_step": m["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": description + (f"; step = compress one worker + aggregate of {n_workers} payloads written in "
-                                       "place of the previous one" if replace else
-                                       f"; step = compress one worker + sparse SGD apply of {n_workers} payloads"
-                                       if args.receive == "sgd_apply" else
-                                       f"; step = compress one worker + accumulate {n_workers} payloads + sparse clear"),
+            "workload": description + "; step = compress one worker + " +
+                        RECEIVE_TEXT[args.receive].format(n=wl.n_workers),
             "elements": n,
-            "tensors": len(gs.sizes),
-            "workers_accumulated": n_workers,
-            "rotating_states": ROTATE,
-            "pairs_per_payload": counts,
+            "tensors": len(wl.gs.sizes),
+            "workers_accumulated": wl.n_workers,
+            "rotating_states": wl.rotate,
+            "pairs_per_payload": m["pairs_per_payload"],
         },
-        "algorithmic_GBps_whole_step": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
-        "compression_ratio": {"ours_8B_pairs": round(4.0 * n / (8 * counts), 1),
-                              "ours_6B_entries": round(4.0 * n / (6 * counts), 1),
-                              "paper_resnet50": 277, "paper_range": "270-600"},
-        "breakdown": breakdown,
-        "roofline": roofline,
+        "timed_region": {"passes_of_steps": m["passes"], "seconds": m["timed_seconds"],
+                         "ms_per_step_over_passes": m["ms_per_step_over_passes"]},
+        "algorithmic_GBps_whole_step": round(step_bytes / (m["ms_per_step"] * 1e-3) / 1e9, 1),
+        "compress_frac": m["compress_frac"],
+        "compress_call": m["compress_call"],
+        "compression_ratio": dict(m["compression_ratio"], paper_resnet50=277, paper_range="270-600"),
+        "breakdown": m["breakdown"],
+        "roofline": m["roofline"],
+        "source_hash": source_hash(),
     }
-    if not (args.no_cpu_baseline or args.profile_only):
-        out["cpu_baseline"] = cpu_baseline(args.workload, gs, cfg_kw, n_workers, scales, seed)
+    wl.close()
+    if extras:
+        # the same steps with the Section 5 re-threshold: what removing the sampled threshold's over-selection costs
+        wr = Workload("speech", args, {"refine_alpha": 2.0}, shared_inputs=inputs)
+        r = wr.measure(args.steps, args.warmup)
+        wr.close()
+        del wr
+        out["rethreshold"] = {
+            "what": "same workload with dgc_config.refine_alpha = 2: a tensor that lets through more than 2 k_j "
+                    "elements gets the exact top-k_j threshold among them (refine_kernel between stream and emit)",
+            "ms_per_step": r["ms_per_step"], "value": r["value"], "compress_frac": r["compress_frac"],
+            "pairs_per_payload": r["pairs_per_payload"], "compression_ratio": r["compression_ratio"],
+            "breakdown": r["breakdown"],
+        }
+        torch.cuda.empty_cache()
+        out["warmup_schedule"] = warmup_schedule_block(args, inputs[0], inputs[1])
+        del inputs, wl
+        torch.cuda.empty_cache()
+        # the ResNet-50-shaped set, same protocol
+        wres = Workload("resnet50", args)
+        rin = wres.inputs()
+        rm = wres.measure(args.steps, args.warmup)
+        wres.close()
+        wref = Workload("resnet50", args, {"refine_alpha": 2.0}, shared_inputs=rin)
+        rr = wref.measure(args.steps, args.warmup, kernel_breakdown=False)
+        wref.close()
+        out["resnet50"] = {
+            "workload": wres.description + "; step = compress one worker + " +
+                        RECEIVE_TEXT[args.receive].format(n=wres.n_workers),
+            "value": rm["value"], "unit": "elements/s", "ms_per_step": rm["ms_per_step"],
+            "timed_region": {"passes_of_steps": rm["passes"], "seconds": rm["timed_seconds"],
+                             "ms_per_step_over_passes": rm["ms_per_step_over_passes"]},
+            "compress_frac": rm["compress_frac"], "compress_call": rm["compress_call"],
+            "pairs_per_payload": rm["pairs_per_payload"],
+            "compression_ratio": dict(rm["compression_ratio"], paper_resnet50=277),
+            "breakdown": rm["breakdown"], "roofline": rm["roofline"],
+            "rethreshold": {"ms_per_step": rr["ms_per_step"], "value": rr["value"],
+                            "compress_frac": rr["compress_frac"], "pairs_per_payload": rr["pairs_per_payload"],
+                            "compression_ratio": rr["compression_ratio"], "breakdown": rr["breakdown"]},
+        }
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out))
 
 
