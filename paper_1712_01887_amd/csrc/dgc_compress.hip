@@ -508,14 +508,17 @@ __device__ __forceinline__ int64_t tile_element(int64_t tile, int lane, int q) {
   return tile * kWaveTile + (q >> 2) * 256 + lane * 4 + (q & 3);
 }
 
-// Mask bits of a lane's sixteen elements (`z`: their v') in a tile that is not wholly
-// inside one tensor.  `j0` is the tensor of the tile's first element.  The starts of the
-// tensors after it are fetched 64 at a time, one per lane (those inside the tile form a
-// prefix of the lanes because the offsets ascend) and handed round with readlane, so
-// that the tile is walked segment by segment, each with its tensor's threshold: one
-// round of loads per 64 tensors, however many tensors share the tile.
+// Mask bits of a lane's sixteen elements in a tile that is not wholly inside one tensor.  `zq`
+// points at the lane's column of the wavefront's v' in LDS (element q of the lane at zq[q * 64]).
+// `j0` is the tensor of the tile's first element.  The starts of the tensors after it are
+// fetched 64 at a time, one per lane (those inside the tile form a prefix of the lanes because
+// the offsets ascend) and handed round with readlane, so that the tile is walked segment by
+// segment, each with its tensor's threshold: one round of loads per 64 tensors, however many
+// tensors share the tile.  A few hundred tiles of a launch come here; the loops are kept rolled
+// and the values in LDS so that this path does not set the register allocation of the whole
+// kernel (unrolled over register-held values it cost the streaming pass a wavefront per SIMD).
 __device__ __forceinline__ uint32_t mixed_tile_mask(const StreamArgs& a, int64_t base, int lane, int32_t j0,
-                                                    const vec4 (&z)[kStreamUnroll]) {
+                                                    const float* zq) {
   constexpr int kElems = 4 * kStreamUnroll;
   const int32_t tile_end = base + kWaveTile <= a.n ? kWaveTile : (int32_t)(a.n - base);
   const int32_t lane4 = lane * 4;
@@ -536,22 +539,20 @@ __device__ __forceinline__ uint32_t mixed_tile_mask(const StreamArgs& a, int64_t
     const int cnt = __popcll(__ballot(rel < kWaveTile));
     for (int i = 0; i < cnt; ++i) {
       const int32_t seg_hi = __builtin_amdgcn_readlane(rel, i);
-      // element q of the lane sits at lane4 + off(q): the segment bounds are moved to the
-      // scalar side of the comparison so that no position has to be kept per element
-#pragma unroll
+#pragma unroll 1
       for (int q = 0; q < kElems; ++q) {
-        const int32_t off = (q >> 2) * 256 + (q & 3);
-        if (lane4 >= seg_lo - off && lane4 < seg_hi - off && fabsf(z[q >> 2][q & 3]) > seg_thr) cand |= 1u << q;
+        const int32_t p = (q >> 2) * 256 + lane4 + (q & 3);
+        if (p >= seg_lo && p < seg_hi && fabsf(zq[q * 64]) > seg_thr) cand |= 1u << q;
       }
       seg_lo = seg_hi;
       seg_thr = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int32_t)__float_as_uint(t), i));
     }
     if (cnt < 64) break;
   }
-#pragma unroll
+#pragma unroll 1
   for (int q = 0; q < kElems; ++q) {
-    const int32_t off = (q >> 2) * 256 + (q & 3);
-    if (lane4 >= seg_lo - off && lane4 < tile_end - off && fabsf(z[q >> 2][q & 3]) > seg_thr) cand |= 1u << q;
+    const int32_t p = (q >> 2) * 256 + lane4 + (q & 3);
+    if (p >= seg_lo && p < tile_end && fabsf(zq[q * 64]) > seg_thr) cand |= 1u << q;
   }
   return cand;
 }
@@ -578,8 +579,20 @@ __device__ __forceinline__ uint32_t mixed_tile_mask(const StreamArgs& a, int64_t
 // where a region overflows.  An element's position among the tile's selected ones is
 // rows before it + bits of its row in lower lanes (from the votes) + lower bits of its
 // nibble.  Tiles shared between tensors are left to the emit pass as before.
-template <bool NESTEROV, bool SCALED, bool STAGED>
+//
+// SLOTTED (densities up to 0.5 %, i.e. the 99.9 % sparsity the method runs at after its
+// warm-up): a tile holds one or two selected elements, seldom more than a handful.  A tile
+// that lies wholly inside one tensor and selects at most kSlotsPerTile elements parks their
+// index, v' and u' (which a full payload region needs to put back) in a record that takes the
+// place of the tile's mask words, in index order, and stores u and v masked: the emit pass copies
+// from the record and neither decodes a mask word nor reads or rewrites u and v for such a tile.  Tiles with more selected elements, and tiles shared between tensors, are
+// left to the emit pass as in the plain case (u', v' unmasked, mask bits set).
+enum StreamMode : int { kStreamPlain = 0, kStreamStaged = 1, kStreamSlotted = 2 };
+
+template <bool NESTEROV, bool SCALED, int MODE>
 __global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs a) {
+  constexpr bool STAGED = MODE == kStreamStaged;
+  __shared__ float mixed_z[kStreamWaves][4 * kStreamUnroll][64];  // for tiles shared between tensors only
   constexpr int U = kStreamUnroll;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: table reads go scalar
@@ -677,6 +690,83 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs a) {
     if (lane == 0) a.tile_count[tile] = (uint32_t)row_base;
     return;
   }
+  if (MODE == kStreamSlotted && thr == thr) {  // wholly inside one tensor (and so a whole tile)
+    uint32_t cand = 0;
+#pragma unroll
+    for (int q = 0; q < 4 * U; ++q)
+      if (fabsf(z[q >> 2][q & 3]) > thr) cand |= 1u << q;
+    // A row (one 16-byte vector per lane) without a selected element, which is most rows, goes out
+    // at once: how long a wavefront holds on to its data after the loads have come back is what
+    // the pass's throughput hangs on, and the bookkeeping below is long enough to show.
+    unsigned long long row_holders[U];
+#pragma unroll
+    for (int r = 0; r < U; ++r) {
+      row_holders[r] = __ballot(((cand >> (4 * r)) & 0xFu) != 0);
+      if (row_holders[r] == 0) {
+        __builtin_nontemporal_store(y[r], u4 + r * 64);
+        __builtin_nontemporal_store(z[r], v4 + r * 64);
+      }
+    }
+    int total = __popc(cand);
+    for (int d = 32; d >= 1; d >>= 1) total += __shfl_xor(total, d);
+    if (total > 0 && total <= kSlotsPerTile) {  // uniform
+      // The few selected elements are taken row by row, one at a time, everything about them in
+      // scalar registers (which lane, which of its four elements): the values are read from that
+      // lane, and the tile's record is put together across lanes 0 .. 31 (index of element p in
+      // lane p, its v' in lane 8 + p, its u' in lane 16 + p) and stored whole, as one 128-byte
+      // line.  (Scattered 4-byte stores from inside this pass cost 26 us on a 122 M-element set:
+      // every one is a partial write of a line; a record array of its own with a line for every
+      // tile that has a record, a stream of stores with holes in it, 7 us.)
+      const bool clear_u = a.factor_masking != 0;
+      int record = 0;
+      int pos = 0;
+#pragma unroll
+      for (int r = 0; r < U; ++r) {
+        unsigned long long holders = row_holders[r];
+        if (holders == 0) continue;
+        const uint32_t nib = (cand >> (4 * r)) & 0xFu;
+        do {
+          const int l = __ffsll((long long)holders) - 1;
+          holders &= holders - 1;
+          uint32_t w = (uint32_t)__builtin_amdgcn_readlane((int)nib, l);
+          do {
+            const int c = __ffs(w) - 1;  // uniform: the component is picked in every lane, then read from lane l
+            w &= w - 1;
+            const float zc = c == 0 ? z[r][0] : c == 1 ? z[r][1] : c == 2 ? z[r][2] : z[r][3];
+            const float yc = c == 0 ? y[r][0] : c == 1 ? y[r][1] : c == 2 ? y[r][2] : y[r][3];
+            const int zv = __builtin_amdgcn_readlane(__float_as_int(zc), l);
+            const int yv = __builtin_amdgcn_readlane(__float_as_int(yc), l);
+            const int e = (int32_t)(base + r * 256 + l * 4 + c);
+            if (lane == pos) record = e;
+            if (lane == kSlotsPerTile + pos) record = zv;
+            if (lane == 2 * kSlotsPerTile + pos) record = yv;
+            ++pos;
+          } while (w);
+        } while (holders);
+        // the mask applied to this row of u and v
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const bool sel = (nib >> c) & 1u;
+          z[r][c] = sel ? 0.0f : z[r][c];
+          if (clear_u) y[r][c] = sel ? 0.0f : y[r][c];
+        }
+      }
+      // the record takes the place of the tile's mask words (both are one 128-byte line per tile;
+      // the count says which of the two the line holds)
+      if (lane < kSlotRecord) reinterpret_cast<int32_t*>(a.mask)[tile * kSlotRecord + lane] = record;
+    } else {  // (an empty tile's line is written too: a stream of stores with holes in it runs slower)
+      a.mask[tile * 64 + lane] = (uint16_t)cand;
+    }
+#pragma unroll
+    for (int r = 0; r < U; ++r) {
+      if (row_holders[r] != 0) {
+        __builtin_nontemporal_store(y[r], u4 + r * 64);
+        __builtin_nontemporal_store(z[r], v4 + r * 64);
+      }
+    }
+    if (lane == 0) a.tile_count[tile] = (uint32_t)total;
+    return;
+  }
   // u' and v' go out first: once stored, u' need not be kept while the mask is worked out
   if (full) {
 #pragma unroll
@@ -703,7 +793,10 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs a) {
     for (int q = 0; q < 4 * U; ++q)
       if (fabsf(z[q >> 2][q & 3]) > thr) cand |= 1u << q;
   } else {
-    cand = mixed_tile_mask(a, base, lane, j0, z);
+    float* zq = &mixed_z[wave][0][lane];  // this lane's column: written and read by this lane only
+#pragma unroll
+    for (int q = 0; q < 4 * U; ++q) zq[q * 64] = z[q >> 2][q & 3];
+    cand = mixed_tile_mask(a, base, lane, j0, zq);
   }
   a.mask[tile * 64 + lane] = (uint16_t)cand;
   // bits set in the tile, for the index-ordered emit pass (measured: no cost here)
@@ -1025,6 +1118,37 @@ __device__ __forceinline__ uint32_t tensor_tile_word(const uint16_t* __restrict_
   return w;
 }
 
+// This thread's share of the sum of tile_count[b .. e): the counts are fetched four to a load
+// (the last workgroup of a 4.7 M-element tensor adds up 4600 of them: with one count per load
+// that was three rounds of loads in a row, 6 us of the emit pass on a 122 M-element set).
+template <int THREADS>
+__device__ __forceinline__ int tile_counts_partial(const uint32_t* __restrict__ tc, int64_t b, int64_t e, int tid) {
+  int sum = 0;
+  if (b >= e) return 0;
+  int64_t b4 = (b + 3) & ~(int64_t)3;  // first multiple of four at or above b
+  if (b4 > e) b4 = e;
+  int64_t e4 = e & ~(int64_t)3;
+  if (e4 < b4) e4 = b4;
+  // at most three counts before the aligned body and three behind it
+  if (tid < (int)(b4 - b)) sum += (int)tc[b + tid];
+  if (tid < (int)(e - e4)) sum += (int)tc[e4 + tid];
+  const uint4* __restrict__ tc4 = reinterpret_cast<const uint4*>(tc);  // the table starts on a 256-byte boundary
+  const int64_t q0 = b4 >> 2, q1 = e4 >> 2;
+  int64_t q = q0 + tid;
+  for (; q + 3 * THREADS < q1; q += 4 * THREADS) {  // four loads in flight per thread
+    uint4 c[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) c[k] = tc4[q + k * THREADS];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) sum += (int)(c[k].x + c[k].y + c[k].z + c[k].w);
+  }
+  for (; q < q1; q += THREADS) {
+    const uint4 c = tc4[q];
+    sum += (int)(c.x + c.y + c.z + c.w);
+  }
+  return sum;
+}
+
 // Moves the `in_win` elements listed in `list` to slots slot0, slot0 + 1, ... of the
 // tensor's region [region, region + cap): reads v', writes the pair, clears v and u.
 // Returns true if some element found the region full.
@@ -1067,7 +1191,6 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
   constexpr int kPerWave = kEmitTiles / kWaves;
   __shared__ int wave_tot[kWaves];
   __shared__ int pre_tot[kWaves];
-  __shared__ int block_base;
   __shared__ int32_t list[kEmitList];
 
   const int lane = threadIdx.x & 63;
@@ -1078,64 +1201,50 @@ __global__ __launch_bounds__(kEmitThreads) void emit_kernel(EmitArgs a) {
   const int64_t cap = a.out_offsets[j + 1] - region;
   const int64_t lo = blk.lo;
   const int64_t hi = blk.hi;
+  const int64_t t0 = lo / kWaveTile;
   const int64_t t1 = (hi - 1) / kWaveTile;
   const int64_t first = blk.first_tile;
 
+  // Everything the workgroup needs before it can place its elements is asked for at once: the
+  // mask words of its own tiles, and the mask-bit counts the streaming pass has left for the
+  // tiles of this tensor before them (every tile strictly between the tensor's first tile and
+  // this workgroup's lies wholly inside the tensor; the tensor's share of its first tile is
+  // recounted from the mask words).  A version that summed its own words first and only then,
+  // behind a barrier, asked for the counts had two memory round trips in a row here.
   uint32_t word[kPerWave];
-  int cnt = 0;
 #pragma unroll
   for (int i = 0; i < kPerWave; ++i) {
     const int64_t t = first + wave + i * kWaves;
-    const uint32_t w = t <= t1 ? tensor_tile_word(a.mask, t, lane, lo, hi) : 0u;
-    word[i] = w;
-    cnt += __popc(w);
+    word[i] = t <= t1 ? tensor_tile_word(a.mask, t, lane, lo, hi) : 0u;
   }
+  int pre = tile_counts_partial<kEmitThreads>(a.tile_count, t0 + 1, first, threadIdx.x);
+  if (first > t0 && wave == 0) pre += __popc(tensor_tile_word(a.mask, t0, lane, lo, hi));
+  int cnt = 0;
+#pragma unroll
+  for (int i = 0; i < kPerWave; ++i) cnt += __popc(word[i]);
   int incl = cnt;
   for (int d = 1; d < 64; d <<= 1) {
     const int t = __shfl_up(incl, d);
     if (lane >= d) incl += t;
   }
+  for (int d = 32; d >= 1; d >>= 1) pre += __shfl_xor(pre, d);
   if (lane == 63) wave_tot[wave] = incl;
+  if (lane == 0) pre_tot[wave] = pre;
   __syncthreads();
-  int before = 0, total = 0;
+  // Slots taken by the tensor's tiles before the workgroup's first one, and by the wavefronts
+  // before this one: no atomics, no tickets, the workgroups of a tensor fill its region in index
+  // order, so the region is the same on every run.
+  int before = 0, total = 0, base = 0;
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) {
     const int t = wave_tot[w];
     if (w < wave) before += t;
     total += t;
+    base += pre_tot[w];
   }
-  // Slots taken by the tiles of this tensor before the workgroup's first one: the counts
-  // the streaming pass has left (every tile strictly between the tensor's first tile and
-  // this workgroup's lies wholly inside the tensor), plus the tensor's share of its first
-  // tile, recounted from the mask words.  No atomics, no tickets: the workgroups of a
-  // tensor fill its region in index order, so the region is the same on every run.
-  {
-    const int64_t t0 = lo / kWaveTile;
-    int pre = 0;
-    const uint32_t* __restrict__ tc = a.tile_count;
-    int64_t t = t0 + 1 + threadIdx.x;
-    for (; t + 7 * kEmitThreads < first; t += 8 * kEmitThreads) {  // eight loads in flight per thread
-      uint32_t c[8];
-#pragma unroll
-      for (int k = 0; k < 8; ++k) c[k] = tc[t + k * kEmitThreads];
-#pragma unroll
-      for (int k = 0; k < 8; ++k) pre += (int)c[k];
-    }
-    for (; t < first; t += kEmitThreads) pre += (int)tc[t];
-    if (first > t0 && wave == 0) pre += __popc(tensor_tile_word(a.mask, t0, lane, lo, hi));
-    for (int d = 32; d >= 1; d >>= 1) pre += __shfl_xor(pre, d);
-    if (lane == 0) pre_tot[wave] = pre;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      int base = 0;
-      for (int w = 0; w < kWaves; ++w) base += pre_tot[w];
-      block_base = base;
-      if ((int)((first - t0) / kEmitTiles) == blk.tensor_blocks - 1) a.out_counts[j] = base + total;
-    }
-  }
+  if (threadIdx.x == 0 && (int)((first - t0) / kEmitTiles) == blk.tensor_blocks - 1) a.out_counts[j] = base + total;
   if (total == 0) return;
-  __syncthreads();
-  const int64_t base_slot = block_base;
+  const int64_t base_slot = base;
   const int my_first = before + (incl - cnt);  // position of this lane's first element in the workgroup
   bool overflow = false;
   // The elements to move are first listed in LDS in their slot order, kEmitList at a
@@ -1191,20 +1300,7 @@ __device__ __forceinline__ void emit_tiles(const EmitArgs& a, const EmitBlock& b
   // and is recounted from its mask words.
   const int64_t t0 = lo / kWaveTile;
   const int in_tensor = (int)((first - t0) / kEmitTiles);
-  int before = 0;
-  {
-    // eight loads in flight per thread: a big tensor has thousands of tiles before its last workgroups
-    const uint32_t* __restrict__ tc = a.tile_count;
-    int64_t t = t0 + 1 + threadIdx.x;
-    for (; t + 7 * kEmitThreads < first; t += 8 * kEmitThreads) {
-      uint32_t c[8];
-#pragma unroll
-      for (int k = 0; k < 8; ++k) c[k] = tc[t + k * kEmitThreads];
-#pragma unroll
-      for (int k = 0; k < 8; ++k) before += (int)c[k];
-    }
-    for (; t < first; t += kEmitThreads) before += (int)tc[t];
-  }
+  int before = tile_counts_partial<kEmitThreads>(a.tile_count, t0 + 1, first, threadIdx.x);
   if (first > t0 && wave == 0) before += __popc(tensor_tile_word(a.mask, t0, lane, lo, hi));
   static_assert(kPerWave % 2 == 0, "tile totals are reduced two to a register");
   {
@@ -1446,6 +1542,149 @@ __global__ __launch_bounds__(kEmitThreads) void emit_staged_kernel(EmitArgs a) {
   if (overflow) atomicOr(&a.state->flags, (uint32_t)DGC_DIAG_OVERFLOW);
 }
 
+// Emit pass after a SLOTTED streaming pass.  Thread (tile, slot) of the workgroup's 32 tiles x
+// 8 slots asks for its slot's index and value at once with the tile's count and the counts of
+// the tensor's tiles before the workgroup; a tile that lies wholly inside the tensor and selected
+// at most kSlotsPerTile elements is a straight copy (its u and v are masked already; an element
+// that finds the region full is put back).  The other tiles -- shared with a neighbour tensor, or
+// with more selected elements than slots -- are taken by the wavefront that holds them, one after
+// the other, from their mask words as in the plain pass: read v', write the pair, clear v and u.
+// Order inside the workgroup's part: tile by tile; inside a tile index order when it comes from
+// the tile's record, (lane, bit) order when it comes from the mask words.
+struct EmitSlotsShared {
+  uint16_t words[kEmitTiles * 64];  // mask words of the tiles that are not copied from slots
+  int cnt[kEmitTiles];              // elements of every tile that belong to this tensor
+  int pre_tot[kEmitThreads / 64];
+};
+
+__global__ __launch_bounds__(kEmitThreads) void emit_slots_kernel(EmitArgs a) {
+  constexpr int kWaves = kEmitThreads / 64;
+  constexpr int kTilesPerWave = 64 / kSlotsPerTile;
+  static_assert(kEmitTiles <= 32 && kTilesPerWave * kWaves == kEmitTiles, "tile counts are scanned by half a wavefront");
+  __shared__ EmitSlotsShared sh;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const EmitBlock blk = a.blocks[blockIdx.x];
+  const int j = blk.tensor;
+  const int64_t region = a.out_offsets[j];  // asked for early: needed late
+  const int64_t cap = a.out_offsets[j + 1] - region;
+  const int64_t lo = blk.lo;
+  const int64_t hi = blk.hi;
+  const int64_t t0 = lo / kWaveTile;
+  const int64_t t1 = (hi - 1) / kWaveTile;
+  const int64_t first = blk.first_tile;
+
+  const int tl = tid / kSlotsPerTile;  // this thread's tile of the part ...
+  const int s = tid % kSlotsPerTile;   // ... and slot of that tile
+  const int64_t t = first + tl;
+  const bool exists = t <= t1;
+  const bool inside = exists && t * kWaveTile >= lo && (t + 1) * kWaveTile <= hi;
+  const uint32_t c_own = exists ? a.tile_count[t] : 0u;
+  int32_t e_slot = 0;
+  float x_slot = 0.0f;
+  const int32_t* __restrict__ records = reinterpret_cast<const int32_t*>(a.mask);  // see the streaming pass
+  if (inside) {  // (a record only if the count says so; loaded before the count is known)
+    e_slot = records[t * kSlotRecord + s];
+    x_slot = __int_as_float(records[t * kSlotRecord + kSlotsPerTile + s]);
+  }
+  // Slots taken by the tensor's tiles before the workgroup's first one.  The tensor's first tile
+  // counts like the others when it lies wholly inside the tensor (its line may hold a record);
+  // shared with the tensor before, it has mask words, from which the tensor's share is recounted.
+  const bool first_shared = t0 * kWaveTile < lo;
+  int pre = tile_counts_partial<kEmitThreads>(a.tile_count, first_shared ? t0 + 1 : t0, first, tid);
+  if (first > t0 && first_shared && wave == 0) pre += __popc(tensor_tile_word(a.mask, t0, lane, lo, hi));
+  for (int d = 32; d >= 1; d >>= 1) pre += __shfl_xor(pre, d);
+  if (lane == 0) sh.pre_tot[wave] = pre;
+
+  const bool from_slots = inside && c_own <= (uint32_t)kSlotsPerTile;
+  // tiles of this wavefront that are taken from their mask words: one bit per tile, at the lane of its slot 0
+  const unsigned long long others = __ballot(exists && !from_slots && s == 0);
+  if (from_slots && s == 0) sh.cnt[tl] = (int)c_own;
+  if (!exists && s == 0) sh.cnt[tl] = 0;
+  for (unsigned long long m = others; m; m &= m - 1) {
+    const int k = wave * kTilesPerWave + (__ffsll((long long)m) - 1) / kSlotsPerTile;
+    const uint32_t w = tensor_tile_word(a.mask, first + k, lane, lo, hi);
+    sh.words[k * 64 + lane] = (uint16_t)w;
+    int c = __popc(w);
+    for (int d = 32; d >= 1; d >>= 1) c += __shfl_xor(c, d);
+    if (lane == 0) sh.cnt[k] = c;
+  }
+  __syncthreads();
+  int base = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) base += sh.pre_tot[w];
+  // where every tile starts in the part: each wavefront scans the 32 counts for itself
+  const int own = lane < kEmitTiles ? sh.cnt[lane] : 0;
+  int incl = own;
+  for (int d = 1; d < 32; d <<= 1) {
+    const int up = __shfl_up(incl, d);
+    if (lane >= d) incl += up;
+  }
+  const int total = __shfl(incl, kEmitTiles - 1);
+  if (tid == 0 && (int)((first - t0) / kEmitTiles) == blk.tensor_blocks - 1) a.out_counts[j] = base + total;
+  if (total == 0) return;
+  const int excl = incl - own;
+  int32_t* __restrict__ out_idx = a.out_idx + region;
+  float* __restrict__ out_val = a.out_val + region;
+  float* __restrict__ u = a.u;
+  float* __restrict__ v = a.v;
+  bool overflow = false;
+  {
+    const int tile_start = __shfl(excl, tl & 31);
+    if (from_slots && s < (int)c_own) {
+      const int64_t slot = (int64_t)base + tile_start + s;
+      if (slot < cap) {
+        out_idx[slot] = e_slot;
+        out_val[slot] = x_slot;
+      } else {  // region full: the element goes back to where the streaming pass took it from
+        overflow = true;
+        v[e_slot] = x_slot;
+        if (a.factor_masking) u[e_slot] = __int_as_float(records[t * kSlotRecord + 2 * kSlotsPerTile + s]);
+      }
+    }
+  }
+  for (unsigned long long m = others; m; m &= m - 1) {
+    const int k = wave * kTilesPerWave + (__ffsll((long long)m) - 1) / kSlotsPerTile;
+    const int64_t tk = first + k;
+    uint32_t w = sh.words[k * 64 + lane];
+    const int bits = __popc(w);
+    int lane_incl = bits;
+    for (int d = 1; d < 64; d <<= 1) {
+      const int up = __shfl_up(lane_incl, d);
+      if (lane >= d) lane_incl += up;
+    }
+    int64_t slot = (int64_t)base + __shfl(excl, k) + (lane_incl - bits);
+    // up to four elements of the lane at a time, their reads of v' in flight together
+    while (__ballot(w != 0)) {
+      int32_t e[4];
+      float x[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        e[i] = -1;
+        if (w) {
+          const int q = __ffs(w) - 1;
+          w &= w - 1;
+          if (slot + i < cap) e[i] = (int32_t)tile_element(tk, lane, q);
+          else overflow = true;  // region full: the element stays where it is
+        }
+        x[i] = e[i] >= 0 ? v[e[i]] : 0.0f;
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (e[i] >= 0) {
+          out_idx[slot + i] = e[i];
+          out_val[slot + i] = x[i];
+          v[e[i]] = 0.0f;
+          if (a.factor_masking) u[e[i]] = 0.0f;
+        }
+      }
+      slot += 4;
+    }
+  }
+  if (overflow) atomicOr(&a.state->flags, (uint32_t)DGC_DIAG_OVERFLOW);
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------------------
@@ -1476,29 +1715,26 @@ hipError_t launch_select(const SelectArgs& a, int32_t num_tensors, hipStream_t s
   return hipGetLastError();
 }
 
+template <bool NESTEROV, bool SCALED>
+static void launch_stream_mode(const StreamArgs& a, int mode, dim3 grid, dim3 block, hipStream_t stream) {
+  if (mode == kStreamStaged) hipLaunchKernelGGL((stream_kernel<NESTEROV, SCALED, kStreamStaged>), grid, block, 0, stream, a);
+  else if (mode == kStreamSlotted) hipLaunchKernelGGL((stream_kernel<NESTEROV, SCALED, kStreamSlotted>), grid, block, 0, stream, a);
+  else hipLaunchKernelGGL((stream_kernel<NESTEROV, SCALED, kStreamPlain>), grid, block, 0, stream, a);
+}
+
 hipError_t launch_stream(const StreamArgs& a, hipStream_t stream) {
   const int64_t tiles = ceil_div(a.n, kWaveTile);
   const int64_t blocks = ceil_div(tiles, kStreamWaves);
   // scale is known to be exactly 1 when neither the norm kernel nor an override supplies it
   const bool scaled = a.scale_from_state != 0 || a.scale_const != 1.0f;
   const dim3 grid((unsigned)blocks), block(kStreamThreads);
-  const bool staged = a.stage_v != nullptr;
+  const int mode = a.stage_v ? kStreamStaged : a.slotted ? kStreamSlotted : kStreamPlain;
   if (a.nesterov) {
-    if (staged) {
-      if (scaled) hipLaunchKernelGGL((stream_kernel<true, true, true>), grid, block, 0, stream, a);
-      else hipLaunchKernelGGL((stream_kernel<true, false, true>), grid, block, 0, stream, a);
-    } else {
-      if (scaled) hipLaunchKernelGGL((stream_kernel<true, true, false>), grid, block, 0, stream, a);
-      else hipLaunchKernelGGL((stream_kernel<true, false, false>), grid, block, 0, stream, a);
-    }
+    if (scaled) launch_stream_mode<true, true>(a, mode, grid, block, stream);
+    else launch_stream_mode<true, false>(a, mode, grid, block, stream);
   } else {
-    if (staged) {
-      if (scaled) hipLaunchKernelGGL((stream_kernel<false, true, true>), grid, block, 0, stream, a);
-      else hipLaunchKernelGGL((stream_kernel<false, false, true>), grid, block, 0, stream, a);
-    } else {
-      if (scaled) hipLaunchKernelGGL((stream_kernel<false, true, false>), grid, block, 0, stream, a);
-      else hipLaunchKernelGGL((stream_kernel<false, false, false>), grid, block, 0, stream, a);
-    }
+    if (scaled) launch_stream_mode<false, true>(a, mode, grid, block, stream);
+    else launch_stream_mode<false, false>(a, mode, grid, block, stream);
   }
   return hipGetLastError();
 }
@@ -1519,6 +1755,8 @@ hipError_t launch_refine(const RefineArgs& a, int32_t num_blocks, hipStream_t st
 hipError_t launch_emit(const EmitArgs& a, int32_t num_blocks, bool sorted, hipStream_t stream) {
   if (a.stage_v)
     hipLaunchKernelGGL(emit_staged_kernel, dim3((unsigned)num_blocks), dim3(kEmitThreads), 0, stream, a);
+  else if (a.slotted)
+    hipLaunchKernelGGL(emit_slots_kernel, dim3((unsigned)num_blocks), dim3(kEmitThreads), 0, stream, a);
   else if (sorted)
     hipLaunchKernelGGL(emit_sorted_kernel, dim3((unsigned)num_blocks), dim3(kEmitThreads), 0, stream, a);
   else

@@ -35,6 +35,15 @@ constexpr int kEmitElements = 32768;                  // elements per workgroup
 constexpr int kEmitTiles = kEmitElements / kWaveTile;
 static_assert(kEmitTiles % (kEmitThreads / 64) == 0, "tiles are dealt round-robin to wavefronts");
 constexpr int kEmitList = 4096;                       // elements listed in LDS at a time
+// Slots: at the densities the method runs at, a tile of 1024 elements holds one or two selected
+// elements.  The streaming pass parks up to kSlotsPerTile of them in a record (kSlotsPerTile
+// indices, their v', their u', padding) that it writes in place of the tile's mask words, and
+// masks u and v itself, so that the emit pass neither decodes mask words nor goes back to u
+// and v for such a tile.  One thread of the emit workgroup per slot of its part.
+constexpr int kSlotsPerTile = 8;
+constexpr int kSlotRecord = 32;  // 32-bit words per tile: the 128 bytes of the tile's 64 mask words
+static_assert(3 * kSlotsPerTile <= kSlotRecord, "index, v' and u' of every slot");
+static_assert(kEmitTiles * kSlotsPerTile == kEmitThreads, "one emit thread per slot of the workgroup's tiles");
 constexpr int kRefineThreads = 1024;                  // the re-threshold pass shares the emit work list
 // Per-tensor counters of the re-threshold pass live one per 128-byte line so that atomics
 // on different tensors do not serialise on a shared line.
@@ -159,6 +168,7 @@ struct StreamArgs {
   float* stage_v;              // device, n floats, or null: plain pass
   float* stage_u;              // device, n floats, or null: no region can overflow, or no factor masking
   int32_t factor_masking;
+  int32_t slotted;             // slotted pass (densities up to 0.5 %): records in place of mask words
 };
 
 struct EmitBlock {
@@ -199,6 +209,7 @@ struct EmitArgs {
   const uint32_t* tile_count;  // mask bits per tile, left by the streaming pass
   const float* stage_v;        // as in StreamArgs; null: the streaming pass was a plain one
   const float* stage_u;
+  int32_t slotted;             // as in StreamArgs
 };
 
 struct MergeBlock {
