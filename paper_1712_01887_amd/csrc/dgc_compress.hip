@@ -206,17 +206,39 @@ __device__ __forceinline__ void find_bin(const uint32_t* hist, uint32_t* wave_to
   members = sel[2];
 }
 
-// The `m` <= kSelectDirect keys in sh.surv: the one of descending rank `rank`.
+// The `m` <= kSelectThreads keys in sh.surv: the one of descending rank `rank`.  Every key is
+// compared with every other; the comparisons of one key are split over as many threads as the
+// workgroup has to spare (with one thread per key, three of sixteen wavefronts looped over 170
+// keys for 3 us while the others waited at the barrier), partial counts meet in LDS.
 __device__ __forceinline__ uint32_t rank_directly(SelectShared& sh, int tid, uint32_t m, uint32_t rank) {
-  if (tid < (int)m) {
-    const uint32_t x = sh.surv[tid];
+  uint32_t* above = sh.hist;                    // keys greater than key x
+  uint32_t* same = sh.hist + kSelectThreads;    // keys equal to it (itself included)
+  static_assert(kSelectBins >= 2 * kSelectThreads, "two counters per listed key");
+  above[tid] = 0;
+  same[tid] = 0;
+  __syncthreads();
+  const uint32_t width = (m + 63u) & ~63u;                      // threads per share: whole wavefronts
+  const uint32_t shares = width ? (uint32_t)kSelectThreads / width : 0u;
+  const uint32_t share = width ? (uint32_t)tid / width : 0u;
+  const uint32_t xi = width ? (uint32_t)tid % width : 0u;
+  if (share < shares && xi < m) {
+    const uint32_t per = (m + shares - 1u) / shares;
+    const uint32_t lo = share * per;
+    const uint32_t hi = lo + per < m ? lo + per : m;
+    const uint32_t x = sh.surv[xi];
     uint32_t greater = 0, equal = 0;
-    for (uint32_t i = 0; i < m; ++i) {
+    for (uint32_t i = lo; i < hi; ++i) {  // (every lane of a wavefront reads the same word)
       const uint32_t y = sh.surv[i];
       greater += y > x;
       equal += y == x;
     }
-    if (greater <= rank && rank < greater + equal) sh.result = x;  // ties write the same value
+    if (greater) atomicAdd(&above[xi], greater);
+    if (equal) atomicAdd(&same[xi], equal);
+  }
+  __syncthreads();
+  if (tid < (int)m) {
+    const uint32_t greater = above[tid], equal = same[tid];
+    if (greater <= rank && rank < greater + equal) sh.result = sh.surv[tid];  // ties write the same value
   }
   __syncthreads();
   return sh.result;
@@ -351,6 +373,49 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
     uint32_t key[kSelectRegKeys];
 #pragma unroll
     for (int i = 0; i < kSelectRegKeys; ++i) key[i] = kNoKey;
+    if (!plan.exact && a.block_shift >= 2) {
+      // Gather, sampled blocks of at least four elements: a thread takes four consecutive elements
+      // of a drawn block at a time (one 16-byte load per array; a block starts at a multiple of its
+      // size from the tensor's start, which need not be 16-byte aligned: dword-aligned vector loads),
+      // so that the draw's position is worked out once per four candidates and not once per
+      // candidate.  The kernel spends as much time issuing instructions as waiting for memory: 16
+      // wavefronts share a compute unit's four SIMDs.  Which thread holds which candidate does not
+      // matter: the rank is taken over all of them.
+      typedef float vec4u __attribute__((ext_vector_type(4), aligned(4)));
+      constexpr int kQuads = kSelectRegKeys / 4;       // per thread
+      constexpr int kQuadsInFlight = 4;
+      const int32_t quads = count >> 2;                // blocks are whole multiples of four elements
+      const int qshift = a.block_shift - 2;            // log2(quads per block)
+#pragma unroll
+      for (int r = 0; r < kQuads / kQuadsInFlight; ++r) {
+        if (r * kQuadsInFlight * kSelectThreads < quads) {  // uniform
+          vec4u gg[kQuadsInFlight], uu[kQuadsInFlight], vv[kQuadsInFlight];
+#pragma unroll
+          for (int q = 0; q < kQuadsInFlight; ++q) {
+            const int32_t qd = tid + (r * kQuadsInFlight + q) * kSelectThreads;
+            gg[q] = uu[q] = vv[q] = vec4u{0.0f, 0.0f, 0.0f, 0.0f};
+            if (qd < quads) {
+              const int64_t e = c.offset + c.position((qd >> qshift) << a.block_shift) + ((qd & ((1 << qshift) - 1)) << 2);
+              gg[q] = *reinterpret_cast<const vec4u*>(c.g + e);
+              uu[q] = *reinterpret_cast<const vec4u*>(c.u + e);
+              vv[q] = *reinterpret_cast<const vec4u*>(c.v + e);
+            }
+          }
+#pragma unroll
+          for (int q = 0; q < kQuadsInFlight; ++q) {
+            const int32_t qd = tid + (r * kQuadsInFlight + q) * kSelectThreads;
+            if (qd < quads) {
+#pragma unroll
+              for (int k = 0; k < 4; ++k) {
+                float u1, v1;
+                momentum_update(gg[q][k], uu[q][k], vv[q][k], c.m, c.scale, c.nesterov, u1, v1);
+                key[4 * (r * kQuadsInFlight + q) + k] = __float_as_uint(v1) & 0x7FFFFFFFu;
+              }
+            }
+          }
+        }
+      }
+    } else {
     // Gather: kSelectInFlight candidates per thread are loaded before any is used.
 #pragma unroll
     for (int r = 0; r < kSelectRegKeys / kSelectInFlight; ++r) {
@@ -377,6 +442,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
           }
         }
       }
+    }
     }
     // Gradients of one tensor share a few exponents, so a histogram over the leading key
     // bits of all candidates piles tens of thousands of LDS atomics on a handful of bins,
