@@ -48,17 +48,21 @@ def oracle_config(**kw) -> O.OracleConfig:
 def gather_payload(layout, out_idx, out_val, out_counts, sort: bool = True):
     """Host copy of a region-layout payload as per-tensor (indices, values), sorted by index
     unless `sort` is false (then in the order the library left them).  Waits for the device."""
-    idx = out_idx.cpu().numpy()
-    val = out_val.cpu().numpy()
     cnt = out_counts.cpu().numpy()
+    used = sum(min(int(cnt[j]), layout[j + 1] - layout[j]) for j in range(len(layout) - 1))
+    whole = 4 * used >= layout[-1] or len(layout) > 200    # else copy region by region (regions laid out for 25 %)
+    if whole:
+        idx = out_idx.cpu().numpy()
+        val = out_val.cpu().numpy()
     per_idx, per_val = [], []
     for j in range(len(layout) - 1):
         lo = layout[j]
         c = min(int(cnt[j]), layout[j + 1] - lo)
-        i = idx[lo:lo + c]
+        i = idx[lo:lo + c] if whole else out_idx[lo:lo + c].cpu().numpy()
+        x = val[lo:lo + c] if whole else out_val[lo:lo + c].cpu().numpy()
         order = np.argsort(i, kind="stable") if sort else np.arange(c)
         per_idx.append(i[order].copy())
-        per_val.append(val[lo:lo + c][order].copy())
+        per_val.append(x[order].copy())
     return per_idx, per_val, cnt
 
 

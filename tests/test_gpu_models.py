@@ -13,12 +13,12 @@ from tests.parity import Pair, say
 pytestmark = pytest.mark.gpu
 
 
-def test_resnet50_set_three_iterations():
+def test_resnet50_set_ten_iterations():
     gs = S.resnet50_set()
     scales = S.tensor_scales(gs, 31)
     p = Pair(gs.offsets, momentum=0.9, density=0.001, seed=31)
     total = 0
-    for it in range(3):
+    for it in range(10):
         say(f"[resnet50] iteration {it}")
         res = p.step(S.gradient(gs, 31, 0, it, scales), it, label=f"resnet50 it{it}")
         total = int(res.counts.sum())
@@ -58,19 +58,76 @@ def test_lstm_set_with_clipping_two_iterations():
     p.close()
 
 
-def test_speech_set_warmup_schedule_six_iterations():
+def test_speech_set_warmup_schedule_twenty_iterations():
+    """The whole configuration: densities 25 %, 6.25 %, 1.5625 %, 0.4 %, then 0.1 % held to iteration
+    19 (Section 4.1's sparsities), one worker of N = 8; thresholds, index sets and values of every
+    iteration, u and v at the ends of the ramp and of the run."""
     gs = S.speech_set()
     scales = S.tensor_scales(gs, 51)
     p = Pair(gs.offsets, layout_density=0.25, momentum=0.9, density=0.25, seed=51, num_workers=8)
-    for it in range(6):
+    for it in range(20):
         d = O.warmup_density(O.WARMUP_DENSITIES, it)
         p.dgc.dgc_set_iteration_density(it)
         p.ocfg.density = d
         say(f"[speech] iteration {it} density {d}")
-        res = p.step(S.gradient(gs, 51, 0, it, scales), it, check_state=(it in (0, 5)),
+        res = p.step(S.gradient(gs, 51, 0, it, scales), it, check_state=(it in (0, 4, 5, 19)),
                      label=f"speech it{it}")
         say(f"[speech] pairs={int(res.counts.sum())} expected~{int(d * gs.numel)}")
     p.close()
+
+
+def test_speech_set_receive_side_eight_workers():
+    """The receive side at the speech set's full size with N = 8: a warm-up density (6.25 %), then the
+    steady state (0.1 %) twice, so that the replacing merge runs both after a warm-up iteration (the
+    whole aggregate is rewritten) and after a steady-state one (only the previous and the new
+    indices are touched).  Accumulate, sparse clear and replace, bit for bit against the oracle's sum
+    with the workers added in order."""
+    import torch
+    gs = S.speech_set()
+    scales = S.tensor_scales(gs, 58)
+    N = 8
+    kw = dict(momentum=0.9, density=0.0625, seed=58, num_workers=N)
+    shared = S.gradient(gs, 58, 999, 0, scales)
+    grads = [S.correlated_gradient(gs, 58, w, 0, shared, scales=scales) for w in range(N)]
+    del shared
+    pairs = [Pair(gs.offsets, layout_density=0.0625, **kw) for _ in range(N)]
+    acc = B.Dgc(B.make_config(**kw), gs.offsets)
+    acc.set_layout(pairs[0].layout)
+    dense = torch.zeros(gs.numel, device="cuda")
+    previous = None
+    for it, d in enumerate([0.0625, 0.001, 0.001]):
+        payloads = []
+        for w, p in enumerate(pairs):
+            p.set_density(d)
+            say(f"[speech N=8] iteration {it} density {d} worker {w}")
+            res = p.step(grads[w], it, check_state=False, label=f"speech N=8 it{it} w{w}")
+            assert not res.overflow
+            payloads.append(O.flatten_payload(res))
+        expect = np.zeros(gs.numel, np.float32)
+        O.decompress_accumulate(expect, payloads)
+        lists = ([p.out_idx for p in pairs], [p.out_val for p in pairs], [p.out_counts for p in pairs])
+        acc.dgc_set_density(d)
+        if previous is None:
+            acc.dgc_decompress_accumulate_regions(dense, *lists)
+            assert np.array_equal(dense.cpu().numpy().view(np.uint32), expect.view(np.uint32)), "accumulate"
+            acc.dgc_dense_clear_regions(dense, lists[0], lists[2])
+            assert not dense.any().item(), "sparse clear"
+            acc.dgc_decompress_replace_regions(dense, *lists)
+        else:
+            acc.dgc_decompress_replace_regions(dense, *lists, previous[0], previous[1])
+        assert np.array_equal(dense.cpu().numpy().view(np.uint32), expect.view(np.uint32)), f"replace it{it}"
+        if it == 2:                                      # and the two-call way at 0.1 %, from a zero buffer
+            scratch = torch.zeros(gs.numel, device="cuda")
+            acc.dgc_decompress_accumulate_regions(scratch, *lists)
+            assert np.array_equal(scratch.cpu().numpy().view(np.uint32), expect.view(np.uint32)), "accumulate 0.1 %"
+            acc.dgc_dense_clear_regions(scratch, lists[0], lists[2])
+            assert not scratch.any().item(), "sparse clear 0.1 %"
+            del scratch
+        # the next iteration overwrites the workers' payload buffers: keep this one's index lists
+        previous = ([p.out_idx.clone() for p in pairs], [p.out_counts.clone() for p in pairs])
+    acc.close()
+    for p in pairs:
+        p.close()
 
 
 def test_literal_speech_set_two_iterations():

@@ -191,6 +191,61 @@ def test_capacity_overflow_keeps_conservation():
     p.close()
 
 
+# ---------------------------------------------------------------------------
+# Records in place of mask words (densities up to 0.5 %): tiles with a few selected elements
+# are copied from their record, tiles with more than eight and tiles shared between tensors are
+# taken from mask words, side by side in one part of a payload region.
+# ---------------------------------------------------------------------------
+def clustered_gradient(gs, seed, it, hot_tiles):
+    """Heavy-tailed noise plus, in the tiles listed, a run of large elements (more than a
+    record holds), a pair of large elements in the tile after each, and one in the tile before."""
+    g = S.gradient(gs, seed, 0, it, S.tensor_scales(gs, seed, fixed=1e-3))
+    rng = np.random.default_rng(seed * 100 + it)
+    n = gs.numel
+    for t in hot_tiles:
+        lo = t * 1024
+        if lo + 2048 > n or lo < 1024:
+            continue
+        many = rng.choice(1024, size=int(rng.integers(9, 200)), replace=False)
+        g[lo + many] = (1.0 + rng.random(many.size)).astype(np.float32) * rng.choice([-1.0, 1.0], many.size).astype(np.float32)
+        g[lo + 1024 + rng.choice(1024, size=2, replace=False)] = np.float32(3.0)
+        g[lo - 1 - int(rng.integers(0, 1000))] = np.float32(-2.5)
+    return g
+
+
+@pytest.mark.parametrize("flags", [0, B.DGC_FLAG_NESTEROV, B.DGC_FLAG_NO_FACTOR_MASKING])
+def test_records_and_mask_words_side_by_side(flags):
+    sizes = [300000, 1500, 1024 * 40, 77, 1024 * 33 + 5, 3, 250000]
+    gs = S.GradientSet("clustered", tuple(S.TensorSpec(f"t{i}", (s,)) for i, s in enumerate(sizes)))
+    p = Pair(gs.offsets, layout_density=0.01, momentum=0.9, density=0.001, flags=flags, seed=29)
+    hot = [3, 4, 50, 120, 121, 200, 290, 296, 300, 333, 334, 335, 500, 580]
+    for it in range(4):
+        res = p.step(clustered_gradient(gs, 61, it, hot), it, label=f"clustered flags={flags} it{it}")
+        assert not res.overflow
+        per_tile = np.bincount(np.concatenate(res.indices) // 1024)
+        assert (per_tile > 8).sum() >= 3 and ((per_tile >= 1) & (per_tile <= 8)).sum() >= 20   # both kinds of tile
+    p.close()
+
+
+@pytest.mark.parametrize("flags", [0, B.DGC_FLAG_NO_FACTOR_MASKING])
+def test_records_put_elements_back_when_a_region_is_full(flags):
+    """Regions far smaller than what passes: an element that finds its region full goes back to
+    where the streaming pass took it from (v' and u'), whether it came from a record or from mask
+    words.  Which elements those are depends on the order inside a part: invariants only."""
+    sizes = [200000, 1024 * 9, 50000, 1024 * 64 + 7]
+    gs = S.GradientSet("small-regions", tuple(S.TensorSpec(f"t{i}", (s,)) for i, s in enumerate(sizes)))
+    caps = [60, 3, 1, 20]
+    p = Pair(gs.offsets, capacities=caps, momentum=0.9, density=0.002, flags=flags, seed=31)
+    g = clustered_gradient(gs, 62, 0, [7, 100, 150, 250, 300])
+    u0 = (0.1 * S.gradient(gs, 62, 1, 0, S.tensor_scales(gs, 62, fixed=1e-3))).astype(np.float32)
+    v0 = (0.1 * S.gradient(gs, 62, 2, 0, S.tensor_scales(gs, 62, fixed=1e-3))).astype(np.float32)
+    p.set_state(u0, v0)
+    res = p.step(g, 0, label=f"records overflow flags={flags}")
+    assert res.overflow
+    check_overflow_invariants(p, g, u0, v0)
+    p.close()
+
+
 def test_warmup_schedule_changes_plan_between_iterations():
     gs = S.ragged_set(8, tensors=9, max_numel=200000)
     p = Pair(gs.offsets, layout_density=0.25, momentum=0.9, density=0.25, seed=13, sample_min=512,
