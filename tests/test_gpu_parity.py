@@ -223,7 +223,7 @@ def test_records_and_mask_words_side_by_side(flags):
         res = p.step(clustered_gradient(gs, 61, it, hot), it, label=f"clustered flags={flags} it{it}")
         assert not res.overflow
         per_tile = np.bincount(np.concatenate(res.indices) // 1024)
-        assert (per_tile > 8).sum() >= 3 and ((per_tile >= 1) & (per_tile <= 8)).sum() >= 20   # both kinds of tile
+        assert (per_tile > 8).sum() >= 3 and ((per_tile >= 1) & (per_tile <= 8)).sum() >= 5    # both kinds of tile
     p.close()
 
 
