@@ -231,8 +231,34 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
                         float* out_thr, uint64_t iteration, void* workspace,
                         size_t workspace_bytes, void* stream);
 
+/*
+ * For callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  dgc_compress with the workspace argument replaced
+ * by an array of 8 MiB that is part of the library (static device memory: every GPU the
+ * process uses holds its own copy until the process ends), which serves gradient sets of up
+ * to about 30 M elements (the ResNet-50-shaped set needs 6 MiB).  Same arguments, results and
+ * errors as dgc_compress otherwise, and
+ *   CAPACITY   dgc_workspace_bytes of the handle exceeds the array (dgc_last_error_string says
+ *              by how much): use dgc_compress with a workspace of the caller's;
+ *   HIP        the array's address could not be obtained.
+ * The call allocates nothing and frees nothing: it asks the runtime for the array's address the
+ * first time it runs on a device and launches the kernels of dgc_compress.  Like dgc_compress, it
+ * uploads the handle's tables (asynchronous host-to-device copies) on the handle's first call, after
+ * dgc_set_density or a change of payload layout, and whenever another handle has used the array
+ * in between -- calls that are refused (STATE) while the stream is being captured; every other
+ * call only launches kernels.  All calls on one GPU share that GPU's array, whatever their handle or
+ * stream: calls that may overlap in time on one GPU race, and the caller must order them.  The
+ * array keeps the last call's contents; what has to start at zero is cleared by the library.
+ * dgc_get_diagnostics with workspace = NULL reads the record of the last such call on the current
+ * device.
+ */
+dgc_status dgc_compress_static(dgc_handle* h, const float* g, float* u, float* v, int32_t* out_idx,
+                               float* out_val, const int64_t* out_offsets_host, int32_t* out_counts,
+                               float* out_thr, uint64_t iteration, void* stream);
+
 /* Copy norm, scale and flags of the last dgc_compress that used `workspace` to the
- * host.  Waits for `stream`. */
+ * host (workspace = NULL: of the last dgc_compress_static on the current device).  Waits for
+ * `stream`. */
 dgc_status dgc_get_diagnostics(dgc_handle* h, const void* workspace, dgc_diagnostics* out_host,
                                void* stream);
 

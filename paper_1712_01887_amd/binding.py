@@ -38,7 +38,7 @@ EXPORTS = [
     "dgc_config_default", "dgc_status_string", "dgc_create", "dgc_destroy", "dgc_invalidate_workspace",
     "dgc_set_scale_override", "dgc_set_density",
     "dgc_set_warmup_schedule", "dgc_set_warmup_stage_length", "dgc_set_iteration_density", "dgc_query_plan", "dgc_workspace_bytes", "dgc_workspace_bytes_warmup",
-    "dgc_recommended_payload_layout", "dgc_compress", "dgc_get_diagnostics",
+    "dgc_recommended_payload_layout", "dgc_compress", "dgc_compress_static", "dgc_get_diagnostics",
     "dgc_decompress_accumulate", "dgc_decompress_accumulate_regions", "dgc_decompress_replace_regions",
     "dgc_dense_clear_regions",
     "dgc_version", "dgc_last_error_string", "dgc_profile_enable", "dgc_profile_collect",
@@ -125,6 +125,8 @@ def load() -> C.CDLL:
     lib.dgc_recommended_payload_layout.argtypes = [vp, dbl, P(i64)]
     lib.dgc_compress.restype = i32
     lib.dgc_compress.argtypes = [vp, vp, vp, vp, vp, vp, P(i64), vp, vp, u64, vp, C.c_size_t, vp]
+    lib.dgc_compress_static.restype = i32
+    lib.dgc_compress_static.argtypes = [vp, vp, vp, vp, vp, vp, P(i64), vp, vp, u64, vp]
     lib.dgc_get_diagnostics.restype = i32
     lib.dgc_get_diagnostics.argtypes = [vp, vp, P(DgcDiagnostics), vp]
     lib.dgc_decompress_accumulate.restype = i32
@@ -308,9 +310,15 @@ class Dgc:
                                      self._layout_c, _ptr(out_counts), _ptr(out_thr), int(iteration),
                                      self._ws_ptr, self._ws_bytes, _stream()), "dgc_compress")
 
-    def dgc_get_diagnostics(self) -> DgcDiagnostics:
+    def dgc_compress_static(self, g, u, v, out_idx, out_val, out_counts, out_thr, iteration: int) -> None:
+        """dgc_compress on the library's static scratch array: no workspace, nothing allocated."""
+        _check(self.lib.dgc_compress_static(self._h, _ptr(g), _ptr(u), _ptr(v), _ptr(out_idx), _ptr(out_val),
+                                            self._layout_c, _ptr(out_counts), _ptr(out_thr), int(iteration),
+                                            _stream()), "dgc_compress_static")
+
+    def dgc_get_diagnostics(self, static: bool = False) -> DgcDiagnostics:
         d = DgcDiagnostics()
-        _check(self.lib.dgc_get_diagnostics(self._h, self._ws_ptr, C.byref(d), _stream()),
+        _check(self.lib.dgc_get_diagnostics(self._h, None if static else self._ws_ptr, C.byref(d), _stream()),
                "dgc_get_diagnostics")
         return d
 

@@ -88,11 +88,40 @@ void workspace_release_all(uint64_t id) {
     it = it->second == id ? g_workspace_owner.erase(it) : std::next(it);
 }
 
+// Scratch memory for callers that cannot allocate (dgc_compress_static): a workspace that is
+// part of the library's code object.  Every GPU the process uses holds its own copy at its own
+// address; in host code the array's name is only a handle for hipGetSymbolAddress, which is
+// asked once per device, with that device current, and whose answer is what host code passes
+// on (to the kernels, as the workspace pointer of dgc_compress).
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
 constexpr size_t kAlign = 256;
 constexpr double kMergeMaxDensity = 0.005;   // receive side: merge by element range in LDS up to here
 constexpr double kStagedMinDensity = 0.005;  // compress: staged streaming pass above this density
 constexpr int kProfEvents = 5;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// Device address of this device's copy of `scratch`; *known_only: do not ask the runtime, fail if
+// the address has not been asked for yet.
+dgc_status static_scratch(void** out, bool known_only) {
+  int dev = -1;
+  if (!hip_ok(hipGetDevice(&dev), "query the current device")) return DGC_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return DGC_ERR_CAPACITY;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    if (known_only) return DGC_ERR_STATE;
+    void* p = nullptr;
+    if (!hip_ok(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "address of the static scratch array")) return DGC_ERR_HIP;
+    if (!p) return DGC_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return DGC_OK;
+}
 
 bool valid_density(double d) { return d > 0.0 && d <= 1.0; }
 
@@ -658,6 +687,26 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   return DGC_OK;
 }
 
+dgc_status dgc_compress_static(dgc_handle* h, const float* g, float* u, float* v, int32_t* out_idx,
+                               float* out_val, const int64_t* out_offsets_host, int32_t* out_counts,
+                               float* out_thr, uint64_t iteration, void* stream) {
+  if (!h) return DGC_ERR_INVALID_ARG;
+  if (h->lay.total > kStaticScratchBytes) {
+    std::snprintf(g_last_error, sizeof(g_last_error),
+                  "dgc_compress_static: this gradient set needs a workspace of %zu bytes, the static array has %zu",
+                  h->lay.total, kStaticScratchBytes);
+    return DGC_ERR_CAPACITY;
+  }
+  void* ws = nullptr;
+  const dgc_status st = static_scratch(&ws, false);
+  if (st != DGC_OK) return st;
+  // The array keeps what the last call left in it.  What must start at zero (the state record,
+  // the re-threshold counters) is cleared, and every table uploaded again, whenever another handle
+  // has used the array since this one did: sync_workspace sees that in the owner registry.
+  return dgc_compress(h, g, u, v, out_idx, out_val, out_offsets_host, out_counts, out_thr, iteration, ws,
+                      kStaticScratchBytes, stream);
+}
+
 static void profile_release(dgc_handle* h) {
   for (hipEvent_t e : h->prof_events) (void)hipEventDestroy(e);
   h->prof_events.clear();
@@ -721,7 +770,13 @@ dgc_status dgc_profile_stream_ceiling(const float* a, float* b, float* c, int64_
 
 dgc_status dgc_get_diagnostics(dgc_handle* h, const void* workspace, dgc_diagnostics* out_host,
                                void* stream_) {
-  if (!h || !workspace || !out_host) return DGC_ERR_INVALID_ARG;
+  if (!h || !out_host) return DGC_ERR_INVALID_ARG;
+  if (!workspace) {  // the static array of dgc_compress_static on the current device
+    void* ws = nullptr;
+    const dgc_status st = static_scratch(&ws, true);
+    if (st != DGC_OK) return st == DGC_ERR_STATE ? DGC_ERR_INVALID_ARG : st;
+    workspace = ws;
+  }
   hipStream_t stream = static_cast<hipStream_t>(stream_);
   DeviceState s;
   if (!hip_ok(hipMemcpyAsync(&s, static_cast<const char*>(workspace) + h->lay.state, sizeof(s),

@@ -203,3 +203,18 @@ def test_wire_format_entry_points_validate_before_touching_the_device(dgc_lib):
     assert dgc_lib.dgc_profile_stream_ceiling(None, a, a, 10, None) == B.DGC_ERR_INVALID_ARG
     assert dgc_lib.dgc_profile_stream_ceiling(a, a + 4, a, 10, None) == B.DGC_ERR_ALIGNMENT
     d.close()
+
+
+def test_static_entry_point_refuses_a_set_beyond_its_array(dgc_lib):
+    """dgc_compress_static checks the workspace the set needs against its 8 MiB array before
+    anything touches the device."""
+    gs = S.speech_set()
+    d = B.Dgc(B.dgc_config_default(), gs.offsets)
+    assert d.dgc_workspace_bytes() > 8 << 20
+    layout = d.dgc_recommended_payload_layout(0.001)
+    arr = (C.c_int64 * len(layout))(*layout)
+    st = dgc_lib.dgc_compress_static(d._h, 256, 256, 256, 256, 256, arr, 256, 256, 0, None)
+    assert st == B.DGC_ERR_CAPACITY
+    assert b"8388608" in dgc_lib.dgc_last_error_string()
+    assert dgc_lib.dgc_compress_static(None, 256, 256, 256, 256, 256, arr, 256, 256, 0, None) == B.DGC_ERR_INVALID_ARG
+    d.close()
