@@ -60,12 +60,10 @@ constexpr int kFlatTensors = 1024;
 // whole number of emit workgroups' parts, which follow each other in index order in
 // every payload's region), finds the pairs of every payload that fall into it by search,
 // and adds them up in LDS.
-constexpr int kMergeThreads = 1024;
-constexpr int kMergeWaves = kMergeThreads / 64;
-constexpr int kMergeCap = 6144;          // pairs a workgroup takes into registers, slots of its LDS accumulator
+constexpr int kMergeMaxThreads = 1024;   // 512 threads when there are at most eight payloads
 constexpr int kMergeMaxRange = 131072;   // elements per workgroup at most (one bitmap bit each)
 constexpr int kMergeEmitBlocks = kMergeMaxRange / kEmitElements;  // emit workgroups' parts per range
-static_assert(kMergeCap % kMergeThreads == 0 && (kMergeMaxRange / 32) % kMergeThreads == 0, "dealt evenly to threads");
+static_assert((kMergeMaxRange / 128) % kMergeMaxThreads == 0, "dealt evenly to threads");
 
 // Receive side at warm-up densities: a workgroup owns one emit workgroup's part and keeps
 // the whole range of the dense vector in LDS.

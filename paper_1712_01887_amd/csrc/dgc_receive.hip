@@ -340,11 +340,12 @@ __device__ __forceinline__ int payload_of(const int32_t* begin, int num_payloads
   return w;
 }
 
+template <int CAP>
 struct MergeShared {
-  uint32_t bitmap[kMergeMaxRange / 32];
-  uint32_t prefix[kMergeMaxRange / 32];  // distinct indices before each bitmap word
-  float acc[kMergeCap];
-  uint32_t wave_sums[kMergeWaves];
+  alignas(16) uint32_t bitmap[kMergeMaxRange / 32];
+  uint32_t prefix[kMergeMaxRange / 128];  // distinct indices before each group of four bitmap words
+  float acc[CAP];
+  uint32_t wave_sums[kMergeMaxThreads / 64];
   int32_t begin[kMaxPayloads + 1];  // number of pairs of the payloads before w inside the range
   const int32_t* idx_at[kMaxPayloads];  // payload w's first pair inside the range
   const float* val_at[kMaxPayloads];
@@ -364,16 +365,39 @@ struct OldLists {
   const float* val_at[kMaxPayloads];  // unused
 };
 
-template <bool REPLACE>
-__global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __restrict__ dense, RegionPayloads p,
+// Number of the distinct index r (relative to the range) among those of the range: the indices
+// marked before its group of 128 bits, plus the marked bits below it inside the group.
+template <int CAP>
+__device__ __forceinline__ int merge_slot(const MergeShared<CAP>& sh, int32_t r) {
+  const uint4 g = reinterpret_cast<const uint4*>(sh.bitmap)[r >> 7];
+  const int word = (r >> 5) & 3;
+  const uint32_t own = word == 0 ? g.x : word == 1 ? g.y : word == 2 ? g.z : g.w;
+  uint32_t c = (uint32_t)__popc(own & ((1u << (r & 31)) - 1u));
+  c += word > 0 ? (uint32_t)__popc(g.x) : 0u;
+  c += word > 1 ? (uint32_t)__popc(g.y) : 0u;
+  c += word > 2 ? (uint32_t)__popc(g.z) : 0u;
+  return (int)(sh.prefix[r >> 7] + c);
+}
+
+// THREADS: 512 when there are at most eight payloads (one wavefront searches one payload's region,
+// and four workgroups of eight wavefronts fit a compute unit, LDS included: the 970 ranges of a
+// 122 M-element set then run all at once instead of in two rounds), 1024 otherwise.  kMergeCap:
+// pairs a workgroup takes into registers, slots of its LDS accumulator (a range with more takes
+// the slow way at the end of the kernel).
+template <bool REPLACE, int THREADS>
+__global__ __launch_bounds__(THREADS) void merge_regions_kernel(float* __restrict__ dense, RegionPayloads p,
                                                                       int32_t num_payloads, RegionPayloads old,
                                                                       int32_t num_old,
                                                                       const int64_t* __restrict__ out_offsets,
                                                                       const MergeBlock* __restrict__ blocks,
                                                                       float scale, int32_t scaled) {
+  constexpr int kMergeThreads = THREADS;
+  constexpr int kMergeWaves = THREADS / 64;
+  constexpr int kMergeCap = THREADS == 512 ? 4096 : 6144;
   constexpr int kPerThread = kMergeCap / kMergeThreads;
   constexpr int kWordsPerThread = kMergeMaxRange / 32 / kMergeThreads;
-  __shared__ MergeShared sh;
+  static_assert(kMergeCap % THREADS == 0 && kWordsPerThread % 4 == 0 && THREADS <= kMergeMaxThreads, "dealt evenly to threads");
+  __shared__ MergeShared<kMergeCap> sh;
   __shared__ OldLists was;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -474,7 +498,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
       for (int v = 0; v < wave; ++v) run += sh.wave_sums[v];
 #pragma unroll
       for (int k = 0; k < kWordsPerThread; ++k) {
-        sh.prefix[tid * kWordsPerThread + k] = run;
+        if ((k & 3) == 0) sh.prefix[(tid * kWordsPerThread + k) >> 2] = run;
         run += c[k];
       }
     }
@@ -484,8 +508,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
     for (int k = 0; k < kPerThread; ++k) {
       id[k] = -1;
       if (rel[k] >= 0) {
-        const uint32_t word = sh.bitmap[rel[k] >> 5];
-        id[k] = (int)(sh.prefix[rel[k] >> 5] + (uint32_t)__popc(word & ((1u << (rel[k] & 31)) - 1u)));
+        id[k] = merge_slot(sh, rel[k]);
         // pairs of several payloads with one index write the same
         sh.acc[id[k]] = from_zero ? 0.0f : dense[blk.begin + rel[k]];
       }
@@ -514,10 +537,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
       w = lo_w;
       src = q - sh.begin[w];
     };
-    auto slot_of = [&](int64_t r) {  // number of the distinct index r among those of the range
-      const uint32_t word = sh.bitmap[r >> 5];
-      return (int)(sh.prefix[r >> 5] + (uint32_t)__popc(word & ((1u << (r & 31)) - 1u)));
-    };
+    auto slot_of = [&](int64_t r) { return merge_slot(sh, (int32_t)r); };
     for (int q = tid; q < total; q += kMergeThreads) {
       int w;
       int src;
@@ -549,7 +569,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_regions_kernel(float* __r
       distinct = (int)all;
 #pragma unroll
       for (int k = 0; k < kWordsPerThread; ++k) {
-        sh.prefix[tid * kWordsPerThread + k] = run;
+        if ((k & 3) == 0) sh.prefix[(tid * kWordsPerThread + k) >> 2] = run;
         run += c[k];
       }
     }
@@ -1008,12 +1028,24 @@ hipError_t launch_merge_regions(float* dense, const RegionPayloads& p, int32_t n
                                 int32_t num_old, const int64_t* out_offsets_dev, const MergeBlock* blocks,
                                 int32_t num_blocks, bool scaled, float scale, hipStream_t stream) {
   if (num <= 0 || num_blocks <= 0) return hipSuccess;
-  if (old)  // dense becomes the sum (it holds the sum of `old` now)
-    hipLaunchKernelGGL(merge_regions_kernel<true>, dim3((unsigned)num_blocks), dim3(kMergeThreads), 0, stream, dense, p,
-                       num, *old, num_old, out_offsets_dev, blocks, scale, scaled ? 1 : 0);
-  else
-    hipLaunchKernelGGL(merge_regions_kernel<false>, dim3((unsigned)num_blocks), dim3(kMergeThreads), 0, stream, dense, p,
-                       num, p, 0, out_offsets_dev, blocks, scale, scaled ? 1 : 0);
+  const dim3 grid((unsigned)num_blocks);
+  const int sc = scaled ? 1 : 0;
+  const bool few = num <= 8 && num_old <= 8;  // one wavefront per payload in a workgroup of eight
+  if (old) {  // dense becomes the sum (it holds the sum of `old` now)
+    if (few)
+      hipLaunchKernelGGL((merge_regions_kernel<true, 512>), grid, dim3(512), 0, stream, dense, p, num, *old, num_old,
+                         out_offsets_dev, blocks, scale, sc);
+    else
+      hipLaunchKernelGGL((merge_regions_kernel<true, 1024>), grid, dim3(1024), 0, stream, dense, p, num, *old, num_old,
+                         out_offsets_dev, blocks, scale, sc);
+  } else {
+    if (few)
+      hipLaunchKernelGGL((merge_regions_kernel<false, 512>), grid, dim3(512), 0, stream, dense, p, num, p, 0,
+                         out_offsets_dev, blocks, scale, sc);
+    else
+      hipLaunchKernelGGL((merge_regions_kernel<false, 1024>), grid, dim3(1024), 0, stream, dense, p, num, p, 0,
+                         out_offsets_dev, blocks, scale, sc);
+  }
   return hipGetLastError();
 }
 
