@@ -588,6 +588,9 @@ def parse_args():
     ap.add_argument("--rotate", type=int, default=4,
                     help="independent (g, u, v) sets and sets of other workers' payloads the steps rotate through "
                          "(at least 2)")
+    ap.add_argument("--schedule-only", action="store_true",
+                    help="only the warm-up schedule block of the speech set (for rocprofv3 runs of the kernels that serve the "
+                         "densities above 0.5 %)")
     ap.add_argument("--profile-only", action="store_true",
                     help="for rocprofv3 runs: the timed steps of the headline workload, a device copy of known size and "
                          "the bare streaming kernel; no events, no CPU baseline, no extra blocks")
@@ -612,12 +615,27 @@ def main():
 
     # the oracle first: its all-core leg forks, which must happen before the GPU is initialised
     cpu = None
-    if not (args.no_cpu_baseline or args.profile_only):
+    if not (args.no_cpu_baseline or args.profile_only or args.schedule_only):
         cpu = cpu_baseline(name, WORKLOADS[name][1], WORKLOADS[name][2])
 
     import torch
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
+
+    if args.schedule_only:
+        from paper_1712_01887_amd import synthetic as S
+        gs = S.speech_set()
+        scales = S.tensor_scales(gs, SEED)
+        shared = S.gradient(gs, SEED, 999, 0, scales)
+        g_pool = [torch.from_numpy(make_gradient(S, "speech", gs, r, shared, scales)).to("cuda") for r in range(2)]
+        g_others = [torch.from_numpy(make_gradient(S, "speech", gs, 100 + w, shared, scales)).to("cuda") for w in range(7)]
+        del shared
+        block = warmup_schedule_block(args, g_pool, g_others)
+        print(json.dumps({"metric": "dense gradient elements/s for compress+decompress",
+                          "value": block["elements_per_s_over_the_schedule"], "unit": "elements/s", "n_gpus": 1,
+                          "steps": 20 * block["passes"], "warmup": 20, "ms_per_step": round(block["ms_per_20_iterations"] / 20, 5),
+                          "config": {"workload": block["what"]}, "warmup_schedule": block}))
+        return
 
     extra_cfg = {"refine_alpha": args.refine_alpha} if args.refine_alpha else None
     wl = Workload(name, args, extra_cfg)
