@@ -333,7 +333,7 @@ dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_
 
 extern "C" {
 
-int32_t dgc_version(void) { return 1000; }
+int32_t dgc_version(void) { return 1001; }
 
 const char* dgc_last_error_string(void) { return g_last_error; }
 
