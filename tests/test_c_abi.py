@@ -35,3 +35,27 @@ def test_c99_caller_builds_and_runs(tmp_path):
     assert small % 256 == 0 and big - small >= 8 * 300000   # two staging arrays behind the small workspace
     assert slots >= sum(O.topk_count(0.001, s) for s in (9408, 64, n2))
     assert m.group(7) and int(m.group(8)) >= 1
+
+
+def test_host_code_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The library's host code (plan and workspace-layout arithmetic, argument checks, the tables it
+    builds at dgc_create) compiled with -fsanitize=address,undefined for the host pass only, behind the
+    same C caller: any out-of-bounds table write, overflow or misaligned access there aborts the run."""
+    from paper_1712_01887_amd import build as b
+    clang = "/opt/rocm/lib/llvm/bin/clang"
+    if not os.path.exists(clang):
+        pytest.skip("no clang next to hipcc")
+    lib = str(tmp_path / "libdgc_san.so")
+    cmd = [a for a in b.command(lib) if a != "-O3"] + ["-O1", "-g"]
+    for flag in ("-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer"):
+        cmd += ["-Xarch_host", flag]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    exe = str(tmp_path / "c_abi_host_san")
+    subprocess.run([clang, "-std=c99", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-I",
+                    os.path.join(ROOT, "include"), os.path.join(ROOT, "tests", "c_abi_host.c"), "-o", exe, "-L",
+                    str(tmp_path), "-ldgc_san", f"-Wl,-rpath,{tmp_path}", "-Wl,-rpath,/opt/rocm/lib",
+                    "-Wl,--allow-shlib-undefined"], check=True, capture_output=True, text=True)
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=300,
+                         env=dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=1"))
+    assert run.returncode == 0, run.stderr[-2000:]
+    assert run.stdout.startswith("k=")
