@@ -194,7 +194,6 @@ void build_layout(dgc_handle* h) {
   l.tile_info = off;    off = align_up(off + sizeof(uint32_t) * tiles);
   l.tile_thr = off;     off = align_up(off + sizeof(float) * tiles);
   l.emit_blocks = off;  off = align_up(off + sizeof(EmitBlock) * h->emit_blocks.size());
-  l.refine_counters = off; off = align_up(off + sizeof(uint32_t) * kCounterStride * T);
   l.tile_count = off;   off = align_up(off + sizeof(uint32_t) * tiles);
   l.merge_blocks = off; off = align_up(off + sizeof(MergeBlock) * h->merge_blocks.size());
   l.part_blocks = off;  off = align_up(off + sizeof(MergeBlock) * h->part_blocks.size());
@@ -266,9 +265,6 @@ dgc_status sync_workspace(dgc_handle* h, void* ws, size_t ws_bytes, const int64_
     workspace_claim(ws, h->id);
     if (!hip_ok(launch_clear_words(at<uint32_t>(ws, h->lay.state), sizeof(DeviceState) / sizeof(uint32_t), stream),
                 "clear workspace state"))
-      return DGC_ERR_HIP;
-    if (!hip_ok(launch_clear_words(at<uint32_t>(ws, h->lay.refine_counters), (size_t)kCounterStride * T, stream),
-                "clear re-threshold counters"))
       return DGC_ERR_HIP;
     if (!hip_ok(hipMemcpyAsync(at<char>(ws, h->lay.offsets), h->offsets.data(),
                                sizeof(int64_t) * (T + 1), hipMemcpyHostToDevice, stream),
@@ -649,8 +645,6 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   // threshold, computed among the elements that passed
   if (c.refine_alpha > 0.0f) {
     RefineArgs ra{};
-    ra.blocks = at<EmitBlock>(workspace, h->lay.emit_blocks);
-    ra.counters = at<uint32_t>(workspace, h->lay.refine_counters);
     ra.plans = sa.plans;
     ra.v = v;
     ra.mask = ta.mask;
@@ -661,7 +655,7 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
     ra.thr = sa.thr;
     ra.out_thr = out_thr;
     ra.tile_count = ta.tile_count;
-    if (!hip_ok(launch_refine(ra, (int32_t)h->emit_blocks.size(), stream), "launch refine kernel"))
+    if (!hip_ok(launch_refine(ra, h->num_tensors, stream), "launch refine kernel"))
       return DGC_ERR_HIP;
   }
 

@@ -900,19 +900,50 @@ __global__ __launch_bounds__(kStreamThreads) void ceiling_kernel(const float* __
   }
 }
 
+// This thread's share of the sum of tile_count[b .. e): the counts are fetched four to a load
+// (the last workgroup of a 4.7 M-element tensor adds up 4600 of them: with one count per load
+// that was three rounds of loads in a row, 6 us of the emit pass on a 122 M-element set).
+template <int THREADS>
+__device__ __forceinline__ int tile_counts_partial(const uint32_t* __restrict__ tc, int64_t b, int64_t e, int tid) {
+  int sum = 0;
+  if (b >= e) return 0;
+  int64_t b4 = (b + 3) & ~(int64_t)3;  // first multiple of four at or above b
+  if (b4 > e) b4 = e;
+  int64_t e4 = e & ~(int64_t)3;
+  if (e4 < b4) e4 = b4;
+  // at most three counts before the aligned body and three behind it
+  if (tid < (int)(b4 - b)) sum += (int)tc[b + tid];
+  if (tid < (int)(e - e4)) sum += (int)tc[e4 + tid];
+  const uint4* __restrict__ tc4 = reinterpret_cast<const uint4*>(tc);  // the table starts on a 256-byte boundary
+  const int64_t q0 = b4 >> 2, q1 = e4 >> 2;
+  int64_t q = q0 + tid;
+  for (; q + 3 * THREADS < q1; q += 4 * THREADS) {  // four loads in flight per thread
+    uint4 c[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) c[k] = tc4[q + k * THREADS];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) sum += (int)(c[k].x + c[k].y + c[k].z + c[k].w);
+  }
+  for (; q < q1; q += THREADS) {
+    const uint4 c = tc4[q];
+    sum += (int)(c.x + c.y + c.z + c.w);
+  }
+  return sum;
+}
+
 // ---------------------------------------------------------------------------
 // Re-threshold on over-selection
 // (paper: Section 5 -- when far more elements pass than expected, a precise
 //  threshold is computed from those already selected)
 // ---------------------------------------------------------------------------
-// Runs between the streaming and the emit pass over the emit work list.  Every
-// workgroup counts the mask bits of its part of a tensor and adds them to the
-// tensor's counter with one 64-bit atomic that is also the arrival ticket.  The
-// workgroup that arrives last knows the tensor's total; only if that exceeds
-// refine_limit does it go on, alone: three histogram passes over |v'| of the
-// selected elements find the magnitude of descending rank k exactly, and a
-// last walk clears the mask bits of elements that do not exceed it.  What the
-// emit pass then extracts is the exact top k of the tensor.
+// Runs between the streaming and the emit pass, one workgroup per tensor.  The workgroup adds up
+// the mask-bit counts the streaming pass has left for the tensor's tiles; only if the total
+// exceeds refine_limit does it go on: three histogram passes over |v'| of the selected elements
+// find the magnitude of descending rank k exactly, and a last walk clears the mask bits of
+// elements that do not exceed it.  What the emit pass then extracts is the exact top k of the
+// tensor.  (A first version ran over the emit work list: every workgroup recounted its part's
+// mask words and took a ticket on the tensor's counter, the last to arrive went on; 17 us on the
+// 161-tensor set and 34 us on the 122 M-element set for what the per-tile counts already say.)
 struct RefineShared {
   uint32_t hist[kSelectBins];
   uint32_t wave_tot[kRefineThreads / 64];
@@ -943,30 +974,30 @@ __device__ __forceinline__ uint32_t tensor_mask_word(const uint16_t* mask, int64
 
 __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
   constexpr int kWaves = kRefineThreads / 64;
-  constexpr int kPerWave = kEmitTiles / kWaves;
   __shared__ RefineShared sh;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const EmitBlock blk = a.blocks[blockIdx.x];
-  const int j = blk.tensor;
+  const int j = blockIdx.x;
+  const TensorPlan plan = a.plans[j];
   const int64_t region = a.out_offsets[j];  // asked for early: needed late
   const int64_t cap = a.out_offsets[j + 1] - region;
-  const int64_t lo = blk.lo;
-  const int64_t hi = blk.hi;
+  const int64_t lo = plan.offset;
+  const int64_t hi = plan.offset + plan.n;
   const int64_t t0 = lo / kWaveTile;
   const int64_t t1 = (hi - 1) / kWaveTile;
-  const int64_t first = blk.first_tile;
 
-  int cnt = 0;
-#pragma unroll
-  for (int i = 0; i < kPerWave; ++i) {
-    const int64_t t = first + wave + i * kWaves;
-    if (t <= t1) {
-      int64_t tile;
-      int l;
-      cnt += __popc(tensor_mask_word(a.mask, t0, (t - t0) * 64 + lane, lo, hi, tile, l));
-    }
+  // How many elements of the tensor passed: the counts the streaming pass has left for the tiles
+  // that lie wholly inside the tensor, and the tensor's share of a first or last tile that it
+  // shares with a neighbour (or that is the ragged end of the set), recounted from the mask words.
+  const bool shared0 = t0 * kWaveTile < lo || (t0 == t1 && (t1 + 1) * kWaveTile > hi);
+  const bool shared1 = t1 != t0 && (t1 + 1) * kWaveTile > hi;
+  int cnt = tile_counts_partial<kRefineThreads>(a.tile_count, shared0 ? t0 + 1 : t0, shared1 ? t1 : t1 + 1, tid);
+  {
+    int64_t tile;
+    int l;
+    if (shared0 && wave == 0) cnt += __popc(tensor_mask_word(a.mask, t0, lane, lo, hi, tile, l));
+    if (shared1 && wave == 1) cnt += __popc(tensor_mask_word(a.mask, t0, (t1 - t0) * 64 + lane, lo, hi, tile, l));
   }
   for (int d = 32; d >= 1; d >>= 1) cnt += __shfl_down(cnt, d);
   if (lane == 0) sh.red[wave] = cnt;
@@ -974,16 +1005,8 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
   if (tid == 0) {
     int total = 0;
     for (int w = 0; w < kWaves; ++w) total += sh.red[w];
-    unsigned long long* ctr = reinterpret_cast<unsigned long long*>(a.counters + (size_t)j * kCounterStride);
-    const unsigned long long old = atomicAdd(ctr, (unsigned long long)(uint32_t)total | (1ull << 32));
-    int go = 0;
-    if ((uint32_t)(old >> 32) == (uint32_t)blk.tensor_blocks - 1u) {  // last arriver: the tensor's total is known
-      atomicExch(ctr, 0ull);
-      const uint32_t passed = (uint32_t)old + (uint32_t)total;
-      go = passed > (uint32_t)a.plans[j].refine_limit;
-      sh.passed = passed;
-    }
-    sh.go = go;
+    sh.passed = (uint32_t)total;
+    sh.go = (uint32_t)total > (uint32_t)plan.refine_limit;
   }
   __syncthreads();
   if (!sh.go) return;
@@ -1182,37 +1205,6 @@ __device__ __forceinline__ uint32_t tensor_tile_word(const uint16_t* __restrict_
     w &= keep;
   }
   return w;
-}
-
-// This thread's share of the sum of tile_count[b .. e): the counts are fetched four to a load
-// (the last workgroup of a 4.7 M-element tensor adds up 4600 of them: with one count per load
-// that was three rounds of loads in a row, 6 us of the emit pass on a 122 M-element set).
-template <int THREADS>
-__device__ __forceinline__ int tile_counts_partial(const uint32_t* __restrict__ tc, int64_t b, int64_t e, int tid) {
-  int sum = 0;
-  if (b >= e) return 0;
-  int64_t b4 = (b + 3) & ~(int64_t)3;  // first multiple of four at or above b
-  if (b4 > e) b4 = e;
-  int64_t e4 = e & ~(int64_t)3;
-  if (e4 < b4) e4 = b4;
-  // at most three counts before the aligned body and three behind it
-  if (tid < (int)(b4 - b)) sum += (int)tc[b + tid];
-  if (tid < (int)(e - e4)) sum += (int)tc[e4 + tid];
-  const uint4* __restrict__ tc4 = reinterpret_cast<const uint4*>(tc);  // the table starts on a 256-byte boundary
-  const int64_t q0 = b4 >> 2, q1 = e4 >> 2;
-  int64_t q = q0 + tid;
-  for (; q + 3 * THREADS < q1; q += 4 * THREADS) {  // four loads in flight per thread
-    uint4 c[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) c[k] = tc4[q + k * THREADS];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) sum += (int)(c[k].x + c[k].y + c[k].z + c[k].w);
-  }
-  for (; q < q1; q += THREADS) {
-    const uint4 c = tc4[q];
-    sum += (int)(c.x + c.y + c.z + c.w);
-  }
-  return sum;
 }
 
 // Moves the `in_win` elements listed in `list` to slots slot0, slot0 + 1, ... of the
@@ -1813,8 +1805,8 @@ hipError_t launch_ceiling(const float* a, float* b, float* c, int64_t n, hipStre
   return hipGetLastError();
 }
 
-hipError_t launch_refine(const RefineArgs& a, int32_t num_blocks, hipStream_t stream) {
-  hipLaunchKernelGGL(refine_kernel, dim3((unsigned)num_blocks), dim3(kRefineThreads), 0, stream, a);
+hipError_t launch_refine(const RefineArgs& a, int32_t num_tensors, hipStream_t stream) {
+  hipLaunchKernelGGL(refine_kernel, dim3((unsigned)num_tensors), dim3(kRefineThreads), 0, stream, a);
   return hipGetLastError();
 }
 

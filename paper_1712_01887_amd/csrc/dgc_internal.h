@@ -44,10 +44,7 @@ constexpr int kSlotsPerTile = 8;
 constexpr int kSlotRecord = 32;  // 32-bit words per tile: the 128 bytes of the tile's 64 mask words
 static_assert(3 * kSlotsPerTile <= kSlotRecord, "index, v' and u' of every slot");
 static_assert(kEmitTiles * kSlotsPerTile == kEmitThreads, "one emit thread per slot of the workgroup's tiles");
-constexpr int kRefineThreads = 1024;                  // the re-threshold pass shares the emit work list
-// Per-tensor counters of the re-threshold pass live one per 128-byte line so that atomics
-// on different tensors do not serialise on a shared line.
-constexpr int kCounterStride = 32;  // uint32 words
+constexpr int kRefineThreads = 1024;                  // the re-threshold pass: one workgroup per tensor
 
 // Receive side: pairs of one payload handled by one workgroup (kFlatPer per thread) and
 // tensors whose counts a workgroup stages in LDS at a time.
@@ -118,7 +115,7 @@ struct TensorPlan {
 };
 
 struct WorkspaceLayout {
-  size_t state, partials, offsets, out_offsets, plans, thr, tile_info, tile_thr, emit_blocks, refine_counters,
+  size_t state, partials, offsets, out_offsets, plans, thr, tile_info, tile_thr, emit_blocks,
       tile_count, merge_blocks, part_blocks, part_found, wire_first_block, wire_sums, mask, total,
       stage_v, stage_u, total_staged;  // staging arrays lie behind `total`: a workspace may end before them
 };
@@ -178,8 +175,6 @@ struct EmitBlock {
 };
 
 struct RefineArgs {
-  const EmitBlock* blocks;     // the emit work list
-  uint32_t* counters;          // device, kCounterStride words per tensor, zero between calls
   const TensorPlan* plans;
   const float* v;              // pre-mask v' as left by the streaming pass
   uint16_t* mask;
@@ -277,7 +272,7 @@ hipError_t launch_norm(const float* g, int64_t n, double* partials, hipStream_t 
 hipError_t launch_select(const SelectArgs& a, int32_t num_tensors, hipStream_t stream);
 hipError_t launch_stream(const StreamArgs& a, hipStream_t stream);
 hipError_t launch_ceiling(const float* a, float* b, float* c, int64_t n, hipStream_t stream);
-hipError_t launch_refine(const RefineArgs& a, int32_t num_blocks, hipStream_t stream);
+hipError_t launch_refine(const RefineArgs& a, int32_t num_tensors, hipStream_t stream);
 hipError_t launch_emit(const EmitArgs& a, int32_t num_blocks, bool sorted, hipStream_t stream);
 hipError_t launch_scatter_pairs(float* dense, int64_t n, const PairPayloads& p, int32_t first,
                                 int32_t num, int64_t max_count, ScatterMode mode, float scale,
