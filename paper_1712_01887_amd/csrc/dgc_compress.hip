@@ -206,39 +206,19 @@ __device__ __forceinline__ void find_bin(const uint32_t* hist, uint32_t* wave_to
   members = sel[2];
 }
 
-// The `m` <= kSelectThreads keys in sh.surv: the one of descending rank `rank`.  Every key is
-// compared with every other; the comparisons of one key are split over as many threads as the
-// workgroup has to spare (with one thread per key, three of sixteen wavefronts looped over 170
-// keys for 3 us while the others waited at the barrier), partial counts meet in LDS.
+// The `m` <= kSelectThreads keys in sh.surv: the one of descending rank `rank`.  (Splitting the
+// comparisons of one key over several threads, with the partial counts added in LDS, was measured:
+// no faster for the 100 to 200 keys that get here.)
 __device__ __forceinline__ uint32_t rank_directly(SelectShared& sh, int tid, uint32_t m, uint32_t rank) {
-  uint32_t* above = sh.hist;                    // keys greater than key x
-  uint32_t* same = sh.hist + kSelectThreads;    // keys equal to it (itself included)
-  static_assert(kSelectBins >= 2 * kSelectThreads, "two counters per listed key");
-  above[tid] = 0;
-  same[tid] = 0;
-  __syncthreads();
-  const uint32_t width = (m + 63u) & ~63u;                      // threads per share: whole wavefronts
-  const uint32_t shares = width ? (uint32_t)kSelectThreads / width : 0u;
-  const uint32_t share = width ? (uint32_t)tid / width : 0u;
-  const uint32_t xi = width ? (uint32_t)tid % width : 0u;
-  if (share < shares && xi < m) {
-    const uint32_t per = (m + shares - 1u) / shares;
-    const uint32_t lo = share * per;
-    const uint32_t hi = lo + per < m ? lo + per : m;
-    const uint32_t x = sh.surv[xi];
+  if (tid < (int)m) {
+    const uint32_t x = sh.surv[tid];
     uint32_t greater = 0, equal = 0;
-    for (uint32_t i = lo; i < hi; ++i) {  // (every lane of a wavefront reads the same word)
+    for (uint32_t i = 0; i < m; ++i) {
       const uint32_t y = sh.surv[i];
       greater += y > x;
       equal += y == x;
     }
-    if (greater) atomicAdd(&above[xi], greater);
-    if (equal) atomicAdd(&same[xi], equal);
-  }
-  __syncthreads();
-  if (tid < (int)m) {
-    const uint32_t greater = above[tid], equal = same[tid];
-    if (greater <= rank && rank < greater + equal) sh.result = sh.surv[tid];  // ties write the same value
+    if (greater <= rank && rank < greater + equal) sh.result = x;  // ties write the same value
   }
   __syncthreads();
   return sh.result;
