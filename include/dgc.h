@@ -213,8 +213,9 @@ dgc_status dgc_recommended_payload_layout(const dgc_handle* h, double density,
  *              mask.  Pairs [out_offsets[j], out_offsets[j] + min(count_j, capacity_j))
  *              are valid: the same pairs in the same order on every run, the parts of
  *              consecutive blocks of 32768 elements in index order, ascending throughout
- *              with DGC_FLAG_SORTED_OUTPUT (and whenever the staging arrays of
- *              dgc_workspace_bytes_warmup are in use).  An element that passed but found
+ *              with DGC_FLAG_SORTED_OUTPUT (and, as it happens, whenever the staging arrays of
+ *              dgc_workspace_bytes_warmup are in use, and up to a density of 0.5 % without the
+ *              re-threshold: only the flag is a promise).  An element that passed but found
  *              the region full is neither emitted nor cleared (it stays in u, v) and
  *              DGC_DIAG_OVERFLOW is raised; in an ascending region those are the highest
  *              indices.

@@ -630,9 +630,8 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   const bool sorted = (c.flags & DGC_FLAG_SORTED_OUTPUT) != 0;
   // At the densities the method runs at (Section 4.1: 99.9 % sparsity after the warm-up) a tile holds
   // one or two selected elements: the streaming pass parks them in the tile's slots and masks u and v
-  // itself, and the emit pass copies.  (Not with the re-threshold pass, see above; not when the payload
-  // is to ascend, which the slots' order inside a tile does not promise.)
-  const bool slotted = !staged && !sorted && c.refine_alpha <= 0.0f && c.density <= kStagedMinDensity;
+  // itself, and the emit pass copies, in index order.  (Not with the re-threshold pass, see above.)
+  const bool slotted = !staged && c.refine_alpha <= 0.0f && c.density <= kStagedMinDensity;
   if (staged) {
     ta.stage_v = at<float>(workspace, h->lay.stage_v);
     ta.stage_u = (factor_masking && h->layout_may_overflow) ? at<float>(workspace, h->lay.stage_u) : nullptr;

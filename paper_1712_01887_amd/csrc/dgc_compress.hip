@@ -1587,8 +1587,10 @@ __global__ __launch_bounds__(kEmitThreads) void emit_staged_kernel(EmitArgs a) {
 // that finds the region full is put back).  The other tiles -- shared with a neighbour tensor, or
 // with more selected elements than slots -- are taken by the wavefront that holds them, one after
 // the other, from their mask words as in the plain pass: read v', write the pair, clear v and u.
-// Order inside the workgroup's part: tile by tile; inside a tile index order when it comes from
-// the tile's record, (lane, bit) order when it comes from the mask words.
+// Order inside the workgroup's part: tile by tile, index order inside a tile (a record is in index
+// order, and the tiles taken from mask words are placed by the votes of their rows), so the
+// whole region ascends, and a full region keeps the lowest indices: this pass also serves
+// DGC_FLAG_SORTED_OUTPUT.
 struct EmitSlotsShared {
   uint16_t words[kEmitTiles * 64];  // mask words of the tiles that are not copied from slots
   int cnt[kEmitTiles];              // elements of every tile that belong to this tensor
@@ -1685,39 +1687,48 @@ __global__ __launch_bounds__(kEmitThreads) void emit_slots_kernel(EmitArgs a) {
   for (unsigned long long m = others; m; m &= m - 1) {
     const int k = wave * kTilesPerWave + (__ffsll((long long)m) - 1) / kSlotsPerTile;
     const int64_t tk = first + k;
-    uint32_t w = sh.words[k * 64 + lane];
-    const int bits = __popc(w);
-    int lane_incl = bits;
-    for (int d = 1; d < 64; d <<= 1) {
-      const int up = __shfl_up(lane_incl, d);
-      if (lane >= d) lane_incl += up;
-    }
-    int64_t slot = (int64_t)base + __shfl(excl, k) + (lane_incl - bits);
-    // up to four elements of the lane at a time, their reads of v' in flight together
-    while (__ballot(w != 0)) {
+    const uint32_t w = sh.words[k * 64 + lane];
+    const int64_t tile_slot = (int64_t)base + __shfl(excl, k);
+    // Index order inside the tile is row (one 16-byte vector per lane), lane, component: an element's
+    // position is the rows before it, plus the bits of its row in lower lanes (from the votes), plus
+    // the lower bits of its nibble.  A row's (up to four) elements of a lane are read together.
+    int row_base = 0;
+#pragma unroll
+    for (int r = 0; r < kStreamUnroll; ++r) {
+      const uint32_t nib = (w >> (4 * r)) & 0xFu;
+      if (__ballot(nib != 0) == 0) continue;  // nothing in this row of the tile
+      int lower = 0, row = 0;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const unsigned long long vote = __ballot((nib >> c) & 1u);
+        lower += (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(vote >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)vote, 0u));
+        row += __popcll(vote);
+      }
+      int pos = row_base + lower;
       int32_t e[4];
+      int64_t at[4];
       float x[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        e[i] = -1;
-        if (w) {
-          const int q = __ffs(w) - 1;
-          w &= w - 1;
-          if (slot + i < cap) e[i] = (int32_t)tile_element(tk, lane, q);
+      for (int c = 0; c < 4; ++c) {
+        e[c] = -1;
+        at[c] = tile_slot + pos;
+        if ((nib >> c) & 1u) {
+          if (at[c] < cap) e[c] = (int32_t)tile_element(tk, lane, 4 * r + c);
           else overflow = true;  // region full: the element stays where it is
+          ++pos;
         }
-        x[i] = e[i] >= 0 ? v[e[i]] : 0.0f;
+        x[c] = e[c] >= 0 ? v[e[c]] : 0.0f;
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        if (e[i] >= 0) {
-          out_idx[slot + i] = e[i];
-          out_val[slot + i] = x[i];
-          v[e[i]] = 0.0f;
-          if (a.factor_masking) u[e[i]] = 0.0f;
+      for (int c = 0; c < 4; ++c) {
+        if (e[c] >= 0) {
+          out_idx[at[c]] = e[c];
+          out_val[at[c]] = x[c];
+          v[e[c]] = 0.0f;
+          if (a.factor_masking) u[e[c]] = 0.0f;
         }
       }
-      slot += 4;
+      row_base += row;
     }
   }
   if (overflow) atomicOr(&a.state->flags, (uint32_t)DGC_DIAG_OVERFLOW);
