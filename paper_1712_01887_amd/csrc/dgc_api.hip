@@ -630,8 +630,8 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
   const bool sorted = (c.flags & DGC_FLAG_SORTED_OUTPUT) != 0;
   // At the densities the method runs at (Section 4.1: 99.9 % sparsity after the warm-up) a tile holds
   // one or two selected elements: the streaming pass parks them in the tile's slots and masks u and v
-  // itself, and the emit pass copies, in index order.  (Not with the re-threshold pass, see above.)
-  const bool slotted = !staged && c.refine_alpha <= 0.0f && c.density <= kStagedMinDensity;
+  // itself, and the emit pass copies, in index order.
+  const bool slotted = !staged && c.density <= kStagedMinDensity;
   if (staged) {
     ta.stage_v = at<float>(workspace, h->lay.stage_v);
     ta.stage_u = (factor_masking && h->layout_may_overflow) ? at<float>(workspace, h->lay.stage_u) : nullptr;
@@ -654,6 +654,10 @@ dgc_status dgc_compress(dgc_handle* h, const float* g, float* u, float* v, int32
     ra.thr = sa.thr;
     ra.out_thr = out_thr;
     ra.tile_count = ta.tile_count;
+    ra.slotted = ta.slotted;
+    ra.factor_masking = ta.factor_masking;
+    ra.u_out = u;
+    ra.v_out = v;
     if (!hip_ok(launch_refine(ra, h->num_tensors, stream), "launch refine kernel"))
       return DGC_ERR_HIP;
   }

@@ -810,7 +810,9 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs a) {
         __builtin_nontemporal_store(z[r], v4 + r * 64);
       }
     }
-    if (lane == 0) a.tile_count[tile] = (uint32_t)total;
+    // (the flag: this line holds mask words although the tile lies inside one tensor -- a count that
+    // the re-threshold pass lowers to kSlotsPerTile or less must not make the line pass for a record)
+    if (lane == 0) a.tile_count[tile] = (uint32_t)total | (total > kSlotsPerTile ? kTileCountHasMask : 0u);
     return;
   }
   // u' and v' go out first: once stored, u' need not be kept while the mask is worked out
@@ -880,7 +882,8 @@ __global__ __launch_bounds__(kStreamThreads) void ceiling_kernel(const float* __
   }
 }
 
-// This thread's share of the sum of tile_count[b .. e): the counts are fetched four to a load
+// This thread's share of the sum of tile_count[b .. e) (the counts proper: the flag of the slotted
+// pass is masked off): the counts are fetched four to a load
 // (the last workgroup of a 4.7 M-element tensor adds up 4600 of them: with one count per load
 // that was three rounds of loads in a row, 6 us of the emit pass on a 122 M-element set).
 template <int THREADS>
@@ -892,8 +895,8 @@ __device__ __forceinline__ int tile_counts_partial(const uint32_t* __restrict__ 
   int64_t e4 = e & ~(int64_t)3;
   if (e4 < b4) e4 = b4;
   // at most three counts before the aligned body and three behind it
-  if (tid < (int)(b4 - b)) sum += (int)tc[b + tid];
-  if (tid < (int)(e - e4)) sum += (int)tc[e4 + tid];
+  if (tid < (int)(b4 - b)) sum += (int)(tc[b + tid] & kTileCountMask);
+  if (tid < (int)(e - e4)) sum += (int)(tc[e4 + tid] & kTileCountMask);
   const uint4* __restrict__ tc4 = reinterpret_cast<const uint4*>(tc);  // the table starts on a 256-byte boundary
   const int64_t q0 = b4 >> 2, q1 = e4 >> 2;
   int64_t q = q0 + tid;
@@ -902,11 +905,12 @@ __device__ __forceinline__ int tile_counts_partial(const uint32_t* __restrict__ 
 #pragma unroll
     for (int k = 0; k < 4; ++k) c[k] = tc4[q + k * THREADS];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) sum += (int)(c[k].x + c[k].y + c[k].z + c[k].w);
+    for (int k = 0; k < 4; ++k)
+      sum += (int)((c[k].x & kTileCountMask) + (c[k].y & kTileCountMask) + (c[k].z & kTileCountMask) + (c[k].w & kTileCountMask));
   }
   for (; q < q1; q += THREADS) {
     const uint4 c = tc4[q];
-    sum += (int)(c.x + c.y + c.z + c.w);
+    sum += (int)((c.x & kTileCountMask) + (c.y & kTileCountMask) + (c.z & kTileCountMask) + (c.w & kTileCountMask));
   }
   return sum;
 }
@@ -992,21 +996,44 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
   if (!sh.go) return;
 
   // ---- exact threshold among the selected elements of tensor j (rare) ---------------
+  // After a slotted streaming pass a tile that lies wholly inside the tensor and selected 1 to
+  // kSlotsPerTile elements holds a record in place of its mask words (indices, v', u'), and u and
+  // v are masked there already; every other tile has mask words and u', v' as they were.
   const int64_t words = (t1 - t0 + 1) * 64;
   const int64_t passed = sh.passed;
   uint32_t prefix = 0;
-  uint32_t rank = (uint32_t)a.plans[j].k;
+  uint32_t rank = (uint32_t)plan.k;
   int consumed = 0;
   uint32_t* mask32 = reinterpret_cast<uint32_t*>(a.mask);
+  const int32_t* records = reinterpret_cast<const int32_t*>(a.mask);
+  auto is_record = [&](int64_t tile) {
+    if (!a.slotted || tile * kWaveTile < lo || (tile + 1) * kWaveTile > hi) return false;
+    const uint32_t c = a.tile_count[tile];  // (with the flag: mask words, whatever the count)
+    return c >= 1u && c <= (uint32_t)kSlotsPerTile;
+  };
+  constexpr uint32_t kFromRecord = 0x80000000u;  // list entry: the element sits in a record (indices are below 2^31)
 
   if (passed <= cap) {
     // The tensor's payload region is free until the emit pass: list the selected elements
-    // there, then their keys, so that everything after one walk over the mask is coalesced.
-    int32_t* list = a.out_idx + region;
+    // there, then their keys, so that everything after one walk over the tiles is coalesced.
+    uint32_t* list = reinterpret_cast<uint32_t*>(a.out_idx + region);
     uint32_t* keys = reinterpret_cast<uint32_t*>(a.out_val + region);
     if (tid == 0) sh.listed = 0;
     __syncthreads();
-    // eight mask words (16 bytes) per load, four loads in flight per thread
+    // records: one thread per tile (keys come with them)
+    if (a.slotted) {
+      for (int64_t tile = t0 + tid; tile <= t1; tile += kRefineThreads) {
+        if (!is_record(tile)) continue;
+        const int c = (int)a.tile_count[tile];
+        int pos = (int)atomicAdd(&sh.listed, (uint32_t)c);
+        for (int q = 0; q < c; ++q) {
+          list[pos] = (uint32_t)records[tile * kSlotRecord + q] | kFromRecord;
+          keys[pos] = (uint32_t)records[tile * kSlotRecord + kSlotsPerTile + q] & 0x7FFFFFFFu;
+          ++pos;
+        }
+      }
+    }
+    // mask words: eight (16 bytes) per load, four loads in flight per thread
     const uint4* mask128 = reinterpret_cast<const uint4*>(a.mask + t0 * 64);
     const int64_t chunks = words >> 3;
     for (int64_t c0 = tid; c0 < chunks; c0 += 4 * kRefineThreads) {
@@ -1020,6 +1047,7 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
       for (int k = 0; k < 4; ++k) {
         const int64_t c = c0 + k * kRefineThreads;
         if ((m[k].x | m[k].y | m[k].z | m[k].w) == 0) continue;
+        if (c < chunks && is_record(t0 + (c >> 3))) continue;  // that line is a record, taken above
         const uint32_t pair[4] = {m[k].x, m[k].y, m[k].z, m[k].w};
 #pragma unroll
         for (int h = 0; h < 8; ++h) {
@@ -1041,7 +1069,7 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
           while (w) {
             const int q = __ffs(w) - 1;
             w &= w - 1;
-            list[pos++] = (int32_t)tile_element(tile, l, q);
+            list[pos++] = (uint32_t)tile_element(tile, l, q);
           }
         }
       }
@@ -1049,16 +1077,18 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
     __syncthreads();
     const int count = (int)passed;
     for (int p0 = tid; p0 < count; p0 += 4 * kRefineThreads) {
+      uint32_t e[4];
       float x[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int p = p0 + q * kRefineThreads;
-        x[q] = p < count ? a.v[list[p]] : 0.0f;
+        e[q] = p < count ? list[p] : kFromRecord;
+        x[q] = (e[q] & kFromRecord) ? 0.0f : a.v[e[q]];
       }
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int p = p0 + q * kRefineThreads;
-        if (p < count) keys[p] = __float_as_uint(x[q]) & 0x7FFFFFFFu;
+        if (p < count && !(e[q] & kFromRecord)) keys[p] = __float_as_uint(x[q]) & 0x7FFFFFFFu;
       }
     }
     __syncthreads();
@@ -1083,8 +1113,9 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
     // Clear the mask bit of every selected element that does not exceed the new threshold.
     // A 16-bit mask word of a tile shared with a neighbour tensor also holds that tensor's
     // bits, and its re-threshold may run at the same time: atomic AND on the 32-bit word.
+    // (Elements in records are dropped tile by tile below.)
     for (int p = tid; p < count; p += kRefineThreads) {
-      if (!(keys[p] > prefix)) {
+      if (!(keys[p] > prefix) && !(list[p] & kFromRecord)) {
         const int64_t e = list[p];
         const int64_t tile = e / kWaveTile;
         const int r = (int)(e % kWaveTile);
@@ -1096,7 +1127,7 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
     }
   } else {
     // More passed than the payload region holds (the caller's capacity is below the
-    // over-selection): walk the mask in every pass and read v' element by element.
+    // over-selection): walk the tiles in every pass and read v' element by element.
 #pragma unroll 1
     for (int pass = 0; pass < 3; ++pass) {
       const int bits = pass == 2 ? 9 : 11;
@@ -1104,7 +1135,18 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
       const uint32_t digit_mask = (1u << bits) - 1u;
       for (int i = tid; i < kSelectBins; i += kRefineThreads) sh.hist[i] = 0;
       __syncthreads();
+      if (a.slotted) {
+        for (int64_t tile = t0 + tid; tile <= t1; tile += kRefineThreads) {
+          if (!is_record(tile)) continue;
+          const int c = (int)a.tile_count[tile];
+          for (int q = 0; q < c; ++q) {
+            const uint32_t key = (uint32_t)records[tile * kSlotRecord + kSlotsPerTile + q] & 0x7FFFFFFFu;
+            if (pass == 0 || (key >> (shift + bits)) == prefix) atomicAdd(&sh.hist[(key >> shift) & digit_mask], 1u);
+          }
+        }
+      }
       for (int64_t wi = tid; wi < words; wi += kRefineThreads) {
+        if (is_record(t0 + (wi >> 6))) continue;
         int64_t tile;
         int l;
         uint32_t w = tensor_mask_word(a.mask, t0, wi, lo, hi, tile, l);
@@ -1124,6 +1166,7 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
       consumed += bits;
     }
     for (int64_t wi = tid; wi < words; wi += kRefineThreads) {
+      if (is_record(t0 + (wi >> 6))) continue;
       int64_t tile;
       int l;
       uint32_t w = tensor_mask_word(a.mask, t0, wi, lo, hi, tile, l);
@@ -1139,6 +1182,36 @@ __global__ __launch_bounds__(kRefineThreads) void refine_kernel(RefineArgs a) {
         atomicAnd(&mask32[h >> 1], ~(drop << (16 * (int)(h & 1))));
         atomicSub(&a.tile_count[tile], (uint32_t)__popc(drop));
       }
+    }
+  }
+  // Records: an element that does not exceed the new threshold goes back to where the streaming
+  // pass took it from (v', and u' under factor masking), the others close ranks in the record, in
+  // their order.  One thread per tile: a record belongs to this tensor alone.  (Whether a tile has
+  // a record is read off its count, which this loop changes: each tile is looked at once, by one
+  // thread, and a count that falls to zero makes the emit pass skip the tile.)
+  if (a.slotted) {
+    __syncthreads();  // every walk over records and counts above is over
+    int32_t* rec = reinterpret_cast<int32_t*>(a.mask);
+    for (int64_t tile = t0 + tid; tile <= t1; tile += kRefineThreads) {
+      if (!is_record(tile)) continue;
+      const int c = (int)a.tile_count[tile];
+      int32_t* r = rec + tile * kSlotRecord;
+      int kept = 0;
+      for (int q = 0; q < c; ++q) {
+        const int32_t e = r[q];
+        const int32_t xv = r[kSlotsPerTile + q];
+        const int32_t xu = r[2 * kSlotsPerTile + q];
+        if (((uint32_t)xv & 0x7FFFFFFFu) > prefix) {
+          r[kept] = e;
+          r[kSlotsPerTile + kept] = xv;
+          r[2 * kSlotsPerTile + kept] = xu;
+          ++kept;
+        } else {
+          a.v_out[e] = __int_as_float(xv);
+          if (a.factor_masking) a.u_out[e] = __int_as_float(xu);
+        }
+      }
+      if (kept != c) a.tile_count[tile] = (uint32_t)kept;
     }
   }
   if (tid == 0) {
@@ -1620,7 +1693,8 @@ __global__ __launch_bounds__(kEmitThreads) void emit_slots_kernel(EmitArgs a) {
   const int64_t t = first + tl;
   const bool exists = t <= t1;
   const bool inside = exists && t * kWaveTile >= lo && (t + 1) * kWaveTile <= hi;
-  const uint32_t c_own = exists ? a.tile_count[t] : 0u;
+  const uint32_t c_raw = exists ? a.tile_count[t] : 0u;
+  const uint32_t c_own = c_raw & kTileCountMask;
   int32_t e_slot = 0;
   float x_slot = 0.0f;
   const int32_t* __restrict__ records = reinterpret_cast<const int32_t*>(a.mask);  // see the streaming pass
@@ -1637,7 +1711,7 @@ __global__ __launch_bounds__(kEmitThreads) void emit_slots_kernel(EmitArgs a) {
   for (int d = 32; d >= 1; d >>= 1) pre += __shfl_xor(pre, d);
   if (lane == 0) sh.pre_tot[wave] = pre;
 
-  const bool from_slots = inside && c_own <= (uint32_t)kSlotsPerTile;
+  const bool from_slots = inside && c_raw <= (uint32_t)kSlotsPerTile;  // (a flagged count is a large number)
   // tiles of this wavefront that are taken from their mask words: one bit per tile, at the lane of its slot 0
   const unsigned long long others = __ballot(exists && !from_slots && s == 0);
   if (from_slots && s == 0) sh.cnt[tl] = (int)c_own;

@@ -42,6 +42,10 @@ constexpr int kEmitList = 4096;                       // elements listed in LDS 
 // and v for such a tile.  One thread of the emit workgroup per slot of its part.
 constexpr int kSlotsPerTile = 8;
 constexpr int kSlotRecord = 32;  // 32-bit words per tile: the 128 bytes of the tile's 64 mask words
+// Per-tile count of the slotted pass: the top bit says that the tile's line holds mask words although
+// the tile lies wholly inside one tensor (it selected more elements than a record holds).
+constexpr uint32_t kTileCountHasMask = 0x80000000u;
+constexpr uint32_t kTileCountMask = 0x7FFFFFFFu;
 static_assert(3 * kSlotsPerTile <= kSlotRecord, "index, v' and u' of every slot");
 static_assert(kEmitTiles * kSlotsPerTile == kEmitThreads, "one emit thread per slot of the workgroup's tiles");
 constexpr int kRefineThreads = 1024;                  // the re-threshold pass: one workgroup per tensor
@@ -185,6 +189,10 @@ struct RefineArgs {
   float* thr;
   float* out_thr;              // may be null
   uint32_t* tile_count;        // kept in step with the mask bits the pass clears
+  int32_t slotted;             // the streaming pass was a slotted one: records in place of some tiles' mask words
+  int32_t factor_masking;
+  float* u_out;                // u and v, to put back what is dropped from a record
+  float* v_out;
 };
 
 struct EmitArgs {
