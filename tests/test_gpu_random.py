@@ -81,6 +81,8 @@ def test_random_large_configuration(seed):
     kw = dict(momentum=0.9, density=0.001, seed=int(rng.integers(0, 2 ** 40)), flags=flags, num_workers=3)
     if rng.random() < 0.4:
         kw.update(clip_threshold=float(rng.choice([0.5, 50.0])))
+    if seed % 2:                                          # the re-threshold on records and mask words side by side
+        kw.update(refine_alpha=float(1.0 + seed % 3))
     workers = [Pair(offsets, layout_density=0.25, warmup_workspace=warm, **kw) for _ in range(3)]
     shared = rng.standard_t(3, n).astype(np.float32)
     densities = [float(rng.choice([0.001, 0.004, 0.02, 0.1])) for _ in range(3)]
