@@ -270,6 +270,7 @@ __device__ __forceinline__ uint32_t select_in_registers(SelectShared& sh, const 
   return prefix;
 }
 
+template <bool NESTEROV>
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   __shared__ SelectShared sh;
   const int tid = threadIdx.x;
@@ -334,7 +335,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   c.exact = plan.exact;
   c.m = a.momentum;
   c.scale = scale;
-  c.nesterov = a.nesterov != 0;
+  c.nesterov = NESTEROV;
   {
     uint32_t h = mix32(a.seed_lo ^ 0x9E3779B9u);
     h = mix32(h ^ a.seed_hi);
@@ -353,14 +354,17 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
     uint32_t key[kSelectRegKeys];
 #pragma unroll
     for (int i = 0; i < kSelectRegKeys; ++i) key[i] = kNoKey;
+    // The gather is written without branches around the loads and without conditional stores into
+    // key[]: a candidate beyond the count reads candidate 0 instead and its key is replaced by the
+    // empty mark afterwards.  (With `if (p < count)` around them the compiler copied the whole
+    // register array at every such branch: some 400 moves per thread in a kernel that spends as
+    // much time issuing instructions as waiting for memory, 16 wavefronts sharing four SIMDs.)
     if (!plan.exact && a.block_shift >= 2) {
-      // Gather, sampled blocks of at least four elements: a thread takes four consecutive elements
-      // of a drawn block at a time (one 16-byte load per array; a block starts at a multiple of its
-      // size from the tensor's start, which need not be 16-byte aligned: dword-aligned vector loads),
-      // so that the draw's position is worked out once per four candidates and not once per
-      // candidate.  The kernel spends as much time issuing instructions as waiting for memory: 16
-      // wavefronts share a compute unit's four SIMDs.  Which thread holds which candidate does not
-      // matter: the rank is taken over all of them.
+      // Sampled blocks of at least four elements: a thread takes four consecutive elements of a
+      // drawn block at a time (one 16-byte load per array; a block starts at a multiple of its size
+      // from the tensor's start, which need not be 16-byte aligned: dword-aligned vector loads), so
+      // that the draw's position is worked out once per four candidates.  Which thread holds which
+      // candidate does not matter: the rank is taken over all of them.
       typedef float vec4u __attribute__((ext_vector_type(4), aligned(4)));
       constexpr int kQuads = kSelectRegKeys / 4;       // per thread
       constexpr int kQuadsInFlight = 4;
@@ -368,61 +372,52 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       const int qshift = a.block_shift - 2;            // log2(quads per block)
 #pragma unroll
       for (int r = 0; r < kQuads / kQuadsInFlight; ++r) {
-        if (r * kQuadsInFlight * kSelectThreads < quads) {  // uniform
+        if (r == 0 || r * kQuadsInFlight * kSelectThreads < quads) {  // uniform
           vec4u gg[kQuadsInFlight], uu[kQuadsInFlight], vv[kQuadsInFlight];
 #pragma unroll
           for (int q = 0; q < kQuadsInFlight; ++q) {
             const int32_t qd = tid + (r * kQuadsInFlight + q) * kSelectThreads;
-            gg[q] = uu[q] = vv[q] = vec4u{0.0f, 0.0f, 0.0f, 0.0f};
-            if (qd < quads) {
-              const int64_t e = c.offset + c.position((qd >> qshift) << a.block_shift) + ((qd & ((1 << qshift) - 1)) << 2);
-              gg[q] = *reinterpret_cast<const vec4u*>(c.g + e);
-              uu[q] = *reinterpret_cast<const vec4u*>(c.u + e);
-              vv[q] = *reinterpret_cast<const vec4u*>(c.v + e);
-            }
+            const int32_t qq = qd < quads ? qd : 0;
+            const int64_t e = c.offset + c.position((qq >> qshift) << a.block_shift) + ((qq & ((1 << qshift) - 1)) << 2);
+            gg[q] = *reinterpret_cast<const vec4u*>(c.g + e);
+            uu[q] = *reinterpret_cast<const vec4u*>(c.u + e);
+            vv[q] = *reinterpret_cast<const vec4u*>(c.v + e);
           }
 #pragma unroll
           for (int q = 0; q < kQuadsInFlight; ++q) {
-            const int32_t qd = tid + (r * kQuadsInFlight + q) * kSelectThreads;
-            if (qd < quads) {
+            const bool ok = tid + (r * kQuadsInFlight + q) * kSelectThreads < quads;
 #pragma unroll
-              for (int k = 0; k < 4; ++k) {
-                float u1, v1;
-                momentum_update(gg[q][k], uu[q][k], vv[q][k], c.m, c.scale, c.nesterov, u1, v1);
-                key[4 * (r * kQuadsInFlight + q) + k] = __float_as_uint(v1) & 0x7FFFFFFFu;
-              }
+            for (int k = 0; k < 4; ++k) {
+              float u1, v1;
+              momentum_update(gg[q][k], uu[q][k], vv[q][k], c.m, c.scale, NESTEROV, u1, v1);
+              key[4 * (r * kQuadsInFlight + q) + k] = ok ? (__float_as_uint(v1) & 0x7FFFFFFFu) : kNoKey;
             }
           }
         }
       }
     } else {
-    // Gather: kSelectInFlight candidates per thread are loaded before any is used.
+      // one candidate per load: kSelectInFlight of them are loaded before any is used
 #pragma unroll
-    for (int r = 0; r < kSelectRegKeys / kSelectInFlight; ++r) {
-      if (r * kSelectInFlight * kSelectThreads < count) {  // uniform
-        float gg[kSelectInFlight], uu[kSelectInFlight], vv[kSelectInFlight];
+      for (int r = 0; r < kSelectRegKeys / kSelectInFlight; ++r) {
+        if (r == 0 || r * kSelectInFlight * kSelectThreads < count) {  // uniform
+          float gg[kSelectInFlight], uu[kSelectInFlight], vv[kSelectInFlight];
 #pragma unroll
-        for (int q = 0; q < kSelectInFlight; ++q) {
-          const int32_t p = tid + (r * kSelectInFlight + q) * kSelectThreads;
-          gg[q] = uu[q] = vv[q] = 0.0f;
-          if (p < count) {
-            const int64_t e = c.offset + c.position(p);
+          for (int q = 0; q < kSelectInFlight; ++q) {
+            const int32_t p = tid + (r * kSelectInFlight + q) * kSelectThreads;
+            const int64_t e = c.offset + c.position(p < count ? p : 0);
             gg[q] = c.g[e];
             uu[q] = c.u[e];
             vv[q] = c.v[e];
           }
-        }
 #pragma unroll
-        for (int q = 0; q < kSelectInFlight; ++q) {
-          const int32_t p = tid + (r * kSelectInFlight + q) * kSelectThreads;
-          if (p < count) {
+          for (int q = 0; q < kSelectInFlight; ++q) {
+            const bool ok = tid + (r * kSelectInFlight + q) * kSelectThreads < count;
             float u1, v1;
-            momentum_update(gg[q], uu[q], vv[q], c.m, c.scale, c.nesterov, u1, v1);
-            key[r * kSelectInFlight + q] = __float_as_uint(v1) & 0x7FFFFFFFu;
+            momentum_update(gg[q], uu[q], vv[q], c.m, c.scale, NESTEROV, u1, v1);
+            key[r * kSelectInFlight + q] = ok ? (__float_as_uint(v1) & 0x7FFFFFFFu) : kNoKey;
           }
         }
       }
-    }
     }
     // Gradients of one tensor share a few exponents, so a histogram over the leading key
     // bits of all candidates piles tens of thousands of LDS atomics on a handful of bins,
@@ -1834,7 +1829,10 @@ hipError_t launch_norm(const float* g, int64_t n, double* partials, hipStream_t 
 }
 
 hipError_t launch_select(const SelectArgs& a, int32_t num_tensors, hipStream_t stream) {
-  hipLaunchKernelGGL(select_kernel, dim3((unsigned)num_tensors), dim3(kSelectThreads), 0, stream, a);
+  if (a.nesterov)
+    hipLaunchKernelGGL(select_kernel<true>, dim3((unsigned)num_tensors), dim3(kSelectThreads), 0, stream, a);
+  else
+    hipLaunchKernelGGL(select_kernel<false>, dim3((unsigned)num_tensors), dim3(kSelectThreads), 0, stream, a);
   return hipGetLastError();
 }
 
