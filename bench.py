@@ -287,6 +287,10 @@ class Workload:
             self.description += ", sorted payload"
         if cfg_extra:
             self.cfg_kw.update(cfg_extra)
+        self.density_override = bool(getattr(args, "density", None))
+        if self.density_override:
+            self.cfg_kw["density"] = args.density
+            self.description += f", every step at density {args.density:g}"
         self.clip = self.cfg_kw.get("clip_threshold", 0.0) > 0.0
         self.gs = gs = getattr(S, set_name)()
         self.n = n = gs.numel
@@ -294,7 +298,8 @@ class Workload:
         self.receive = args.receive
         dev = "cuda"
         self.stream = int(torch.cuda.current_stream().cuda_stream)
-        self.dgc = dgc = B.Dgc(B.make_config(**self.cfg_kw), gs.offsets)
+        # above 0.5 % the workspace gets the staging arrays of the warm-up streaming pass
+        self.dgc = dgc = B.Dgc(B.make_config(**self.cfg_kw), gs.offsets, warmup_workspace=self.cfg_kw["density"] > 0.005)
         dgc.set_layout(dgc.dgc_recommended_payload_layout(self.cfg_kw["density"]))
         if shared_inputs is not None:                     # same inputs as another Workload on the same set
             self.g_pool, self.g_others = shared_inputs
@@ -420,7 +425,7 @@ class Workload:
                 "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                "traffic": measured_traffic(self.name),
+                "traffic": None if self.density_override else measured_traffic(self.name),
                 "algorithmic_bytes": BYTES_PER_ELEMENT * n,
                 "avg_kernel_us": round(stream_avg_ms * 1e3, 2),
             }
@@ -579,6 +584,9 @@ def parse_args():
     ap.add_argument("--sample-block", type=int, default=None, help="override dgc_config.sample_block")
     ap.add_argument("--refine-alpha", type=float, default=None,
                     help="switch the Section 5 re-threshold on in the headline (dgc_config.refine_alpha)")
+    ap.add_argument("--density", type=float, default=None,
+                    help="run every step of the workload at this density instead of 0.1 %% (one of the warm-up "
+                         "densities, held as during a warm-up epoch; with --only-headline or --profile-only)")
     ap.add_argument("--sorted", action="store_true",
                     help="emit every tensor's pairs in ascending index order (DGC_FLAG_SORTED_OUTPUT)")
     ap.add_argument("--receive", choices=["replace", "accumulate_clear", "sgd_apply"], default="replace",
@@ -611,7 +619,7 @@ def main():
               "single MI355X; use --gpus 1", file=sys.stderr)
         sys.exit(2)
     name = args.workload
-    extras = name == "speech" and not (args.only_headline or args.profile_only)
+    extras = name == "speech" and not (args.only_headline or args.profile_only or args.density)
 
     # the oracle first: its all-core leg forks, which must happen before the GPU is initialised
     cpu = None

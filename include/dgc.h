@@ -294,8 +294,10 @@ dgc_status dgc_decompress_accumulate(dgc_handle* h, float* dense, int64_t n, int
  * order inside a part is free, the indices of one payload are distinct).  The payloads are
  * merged by element range in on-chip memory, workers added in the order given, without
  * float atomics, which gives the result of the plain definition bit for bit at every
- * density: up to 0.5 % a workgroup touches only the elements that occur in a range of up to
- * 131072; above (the warm-up densities of Section 4) it keeps one part's whole range of
+ * density: up to 0.5 %, as long as the payloads together let expect no more than 6144 pairs
+ * in 131072 elements (density x payloads x 131072 x 1.25), a workgroup touches only the
+ * elements that occur in a range of up to 131072; otherwise (the warm-up densities of
+ * Section 4, or many payloads) it keeps one part's whole range of
  * `dense` on chip, after a launch that finds every payload's pairs of every part.  A
  * region laid out otherwise gives wrong sums (never an access out of bounds); for
  * arbitrary pair lists there is dgc_decompress_accumulate.
@@ -314,11 +316,11 @@ dgc_status dgc_decompress_accumulate_regions(dgc_handle* h, float* dense, int32_
  * provided that `dense` is zero outside the indices of the `previous` payloads (typically
  * those of the previous call, whose index and count arrays must still be intact;
  * num_previous = 0: `dense` is zero everywhere, as before the first iteration).  One launch
- * does what dgc_dense_clear_regions followed by dgc_decompress_accumulate_regions does: up
- * to a density of 0.5 % the sums start from zero instead of the scattered contents of
- * `dense`, and indices of the previous payloads that do not recur are set to zero; above
- * (and in the call that follows one above it, whose previous payloads are long), the whole
- * of `dense` is written once and read never, and `previous` is ignored.
+ * does what dgc_dense_clear_regions followed by dgc_decompress_accumulate_regions does: where
+ * a workgroup touches only the elements that occur (see above) the sums start from zero instead
+ * of the scattered contents of `dense`, and indices of the previous payloads that do not recur
+ * are set to zero; otherwise (and in the call that follows such a call, whose previous payloads
+ * are long), the whole of `dense` is written once and read never, and `previous` is ignored.
  * Workers are added in the order given; the result is bit for bit that of clearing and
  * accumulating.  Arguments and the regions' layout as for dgc_decompress_accumulate_regions;
  * the previous payloads have the same layout.
@@ -335,8 +337,8 @@ dgc_status dgc_decompress_replace_regions(dgc_handle* h, float* dense, int32_t n
 /*
  * dense[idx] = 0 for every pair of the given region-layout payloads: returns a
  * dense aggregate to all-zero after it has been consumed at the cost of the
- * payload size instead of a full fill.  Arguments as above.  Above a density of 0.5 %
- * the regions must be as dgc_compress writes them (see above): the indices of a part are
+ * payload size instead of a full fill.  Arguments as above.  Above a density of 0.5 % (or with
+ * many payloads, see above) the regions must be as dgc_compress writes them: the indices of a part are
  * marked in a bitmap on chip and every 64-byte sector with a marked element is written
  * once, whole (its other elements are read and written back unchanged).
  */

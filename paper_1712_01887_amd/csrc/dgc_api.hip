@@ -34,7 +34,7 @@ struct dgc_handle {
   std::vector<MergeBlock> merge_blocks;  // work list of the receive side: ranges of several emit parts
   std::vector<MergeBlock> part_blocks;   // the same with one emit part per range (warm-up densities)
   bool layout_may_overflow = true;       // some region of the registered layout is smaller than its tensor
-  double last_replace_density = 0.0;     // density at the last dgc_decompress_replace_regions call
+  int64_t last_replace_expected = 0;     // pairs per range the payloads of the last dgc_decompress_replace_regions call let expect
   WorkspaceLayout lay{};
   // what the bound workspace currently holds
   void* ws = nullptr;
@@ -697,9 +697,9 @@ dgc_status dgc_compress_static(dgc_handle* h, const float* g, float* u, float* v
   void* ws = nullptr;
   const dgc_status st = static_scratch(&ws, false);
   if (st != DGC_OK) return st;
-  // The array keeps what the last call left in it.  What must start at zero (the state record,
-  // the re-threshold counters) is cleared, and every table uploaded again, whenever another handle
-  // has used the array since this one did: sync_workspace sees that in the owner registry.
+  // The array keeps what the last call left in it.  What must start at zero (the state record)
+  // is cleared, and every table uploaded again, whenever another handle has used the array since
+  // this one did: sync_workspace sees that in the owner registry.
   return dgc_compress(h, g, u, v, out_idx, out_val, out_offsets_host, out_counts, out_thr, iteration, ws,
                       kStaticScratchBytes, stream);
 }
@@ -889,11 +889,17 @@ static dgc_status scatter_regions(dgc_handle* h, float* dense, int32_t num_paylo
   // workgroup merges the pairs of a range of up to 128 Ki elements in LDS and touches only
   // the elements that occur; at warm-up densities a workgroup keeps one emit part's whole
   // range of `dense` in LDS.
-  // (Replacing an aggregate that was built at a warm-up density: its index lists are long, and
+  // Pairs a range of kMergeMaxRange elements can expect (the sampled threshold lets through up to a
+  // quarter more than the density on the inputs seen so far): the range kernel wants them, and the
+  // previous payloads' indices when it replaces, in its registers and accumulator, and takes a much
+  // slower way when they do not fit.  (Replacing an aggregate whose index lists are that long:
   // writing the whole of `dense` once, which needs none of them, is the cheaper way.)
-  const bool few = h->cfg.density <= kMergeMaxDensity &&
-                   !(replace && num_old > 0 && h->last_replace_density > kMergeMaxDensity);
-  if (replace) h->last_replace_density = h->cfg.density;
+  const int64_t expected_new = (int64_t)std::ceil(1.25 * h->cfg.density * (double)kMergeMaxRange * (double)num_payloads);
+  const int64_t expected_old = (replace && num_old > 0) ? h->last_replace_expected : 0;
+  const int64_t expected_pairs = expected_new > expected_old ? expected_new : expected_old;
+  const bool fits = h->cfg.density <= kMergeMaxDensity && expected_new <= kMergeCapLarge;
+  const bool few = fits && expected_old <= kMergeCapLarge;
+  if (replace) h->last_replace_expected = fits ? expected_new : (int64_t)kMergeCapLarge + 1;
   const MergeBlock* parts = at<MergeBlock>(workspace, h->lay.part_blocks);
   const int32_t num_parts = (int32_t)h->part_blocks.size();
   void* found = at<char>(workspace, h->lay.part_found);
@@ -915,7 +921,7 @@ static dgc_status scatter_regions(dgc_handle* h, float* dense, int32_t num_paylo
   } else if (few) {
     if (!hip_ok(launch_merge_regions(dense, p, num_payloads, replace ? &was : nullptr, num_old, oo,
                                      at<MergeBlock>(workspace, h->lay.merge_blocks), (int32_t)h->merge_blocks.size(),
-                                     sgd, scale, stream),
+                                     expected_pairs, sgd, scale, stream),
                 "launch merge kernel"))
       return DGC_ERR_HIP;
   } else if (!hip_ok(launch_merge_parts(dense, p, num_payloads, oo, parts, num_parts, found, replace, sgd, scale,

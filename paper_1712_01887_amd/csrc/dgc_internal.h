@@ -64,6 +64,10 @@ constexpr int kFlatTensors = 1024;
 constexpr int kMergeMaxThreads = 1024;   // 512 threads when there are at most eight payloads
 constexpr int kMergeMaxRange = 131072;   // elements per workgroup at most (one bitmap bit each)
 constexpr int kMergeEmitBlocks = kMergeMaxRange / kEmitElements;  // emit workgroups' parts per range
+// pairs of a range a workgroup takes into registers and its LDS accumulator (512 and 1024 threads);
+// a range with more takes a slower way through the same kernel
+constexpr int kMergeCapSmall = 4096;
+constexpr int kMergeCapLarge = 6144;
 static_assert((kMergeMaxRange / 128) % kMergeMaxThreads == 0, "dealt evenly to threads");
 
 // Receive side at warm-up densities: a workgroup owns one emit workgroup's part and keeps
@@ -292,7 +296,8 @@ hipError_t launch_scatter_regions(float* dense, int64_t n, const RegionPayloads&
 
 hipError_t launch_merge_regions(float* dense, const RegionPayloads& p, int32_t num, const RegionPayloads* old,
                                 int32_t num_old, const int64_t* out_offsets_dev, const MergeBlock* blocks,
-                                int32_t num_blocks, bool scaled, float scale, hipStream_t stream);
+                                int32_t num_blocks, int64_t expected_pairs, bool scaled, float scale,
+                                hipStream_t stream);
 hipError_t launch_merge_parts(float* dense, const RegionPayloads& p, int32_t num, const int64_t* out_offsets_dev,
                               const MergeBlock* parts, int32_t num_parts, void* found, bool replace, bool scaled,
                               float scale, hipStream_t stream);

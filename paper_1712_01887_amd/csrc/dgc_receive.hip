@@ -393,7 +393,7 @@ __global__ __launch_bounds__(THREADS) void merge_regions_kernel(float* __restric
                                                                       float scale, int32_t scaled) {
   constexpr int kMergeThreads = THREADS;
   constexpr int kMergeWaves = THREADS / 64;
-  constexpr int kMergeCap = THREADS == 512 ? 4096 : 6144;
+  constexpr int kMergeCap = THREADS == 512 ? kMergeCapSmall : kMergeCapLarge;
   constexpr int kPerThread = kMergeCap / kMergeThreads;
   constexpr int kWordsPerThread = kMergeMaxRange / 32 / kMergeThreads;
   static_assert(kMergeCap % THREADS == 0 && kWordsPerThread % 4 == 0 && THREADS <= kMergeMaxThreads, "dealt evenly to threads");
@@ -1026,11 +1026,13 @@ hipError_t launch_scatter_regions(float* dense, int64_t n, const RegionPayloads&
 
 hipError_t launch_merge_regions(float* dense, const RegionPayloads& p, int32_t num, const RegionPayloads* old,
                                 int32_t num_old, const int64_t* out_offsets_dev, const MergeBlock* blocks,
-                                int32_t num_blocks, bool scaled, float scale, hipStream_t stream) {
+                                int32_t num_blocks, int64_t expected_pairs, bool scaled, float scale,
+                                hipStream_t stream) {
   if (num <= 0 || num_blocks <= 0) return hipSuccess;
   const dim3 grid((unsigned)num_blocks);
   const int sc = scaled ? 1 : 0;
-  const bool few = num <= 8 && num_old <= 8;  // one wavefront per payload in a workgroup of eight
+  // one wavefront per payload in a workgroup of eight, if the pairs a range can expect fit its accumulator
+  const bool few = num <= 8 && num_old <= 8 && expected_pairs <= kMergeCapSmall;
   if (old) {  // dense becomes the sum (it holds the sum of `old` now)
     if (few)
       hipLaunchKernelGGL((merge_regions_kernel<true, 512>), grid, dim3(512), 0, stream, dense, p, num, *old, num_old,

@@ -17,7 +17,7 @@ SORTED = B.DGC_FLAG_SORTED_OUTPUT
 
 
 def _run(gs, N, densities, seed, flags=0, scales=None, layout_density=None, warm=False, workers_per_iteration=None,
-         reverse_previous=False, **extra):
+         reverse_previous=False, reshape=None, **extra):
     """One Pair per worker and per parity of the iteration (so that the previous payloads stay
     intact); every iteration replaces the aggregate and is compared with the oracle."""
     import torch
@@ -40,8 +40,10 @@ def _run(gs, N, densities, seed, flags=0, scales=None, layout_density=None, warm
         for w in range(active):
             p = workers[w][it % 2]
             p.set_density(d)
-            res = p.step(S.correlated_gradient(gs, seed, w, it, shared[it], scales=scales), it, check_state=False,
-                         label=f"replace it{it} w{w}")
+            g = S.correlated_gradient(gs, seed, w, it, shared[it], scales=scales)
+            if reshape is not None:
+                reshape(g)
+            res = p.step(g, it, check_state=False, label=f"replace it{it} w{w}")
             assert not res.overflow
             payloads.append(O.flatten_payload(res))
             current.append(p)
@@ -66,7 +68,12 @@ def _run(gs, N, densities, seed, flags=0, scales=None, layout_density=None, warm
 @pytest.mark.parametrize("flags", [0, SORTED])
 @pytest.mark.parametrize("N,densities", [(1, [0.001, 0.001, 0.001]), (4, [0.002, 0.002, 0.002]),
                                          (16, [0.001, 0.001]), (3, [0.0625, 0.0625, 0.0625]),
-                                         (6, [0.25, 0.0625, 0.002, 0.001, 0.25])])
+                                         (6, [0.25, 0.0625, 0.002, 0.001, 0.25]),
+                                         # 0.4 % of eight workers: more pairs per range than the 512-thread form holds
+                                         (8, [0.004, 0.004, 0.001]),
+                                         # 0.4 % of sixteen: more than any form holds, whole ranges are rewritten,
+                                         # also in the first call at 0.1 %, whose previous payloads are long
+                                         (16, [0.004, 0.004, 0.001, 0.001])])
 def test_replace_equals_a_fresh_sum(N, densities, flags):
     gs = S.ragged_set(41, tensors=12, max_numel=400000)
     _run(gs, N, densities, 200 + N, flags=flags, layout_density=max(0.04, max(densities)), sample_min=1024,
@@ -74,10 +81,16 @@ def test_replace_equals_a_fresh_sum(N, densities, flags):
 
 
 def test_replace_with_more_pairs_than_a_workgroup_holds():
-    """48 payloads at 0.5 %: ranges whose new or previous pairs outgrow registers and
-    accumulator take the general path (previous indices cleared first)."""
+    """Eight payloads at 0.4 % whose large elements all sit at the front of their tensors: the first
+    range of a tensor gets several times the pairs the density lets expect, more than registers and
+    accumulator hold, and takes the general path (previous indices cleared first)."""
     gs = S.ragged_set(42, tensors=10, max_numel=400000)
-    _run(gs, 48, [0.005, 0.005], 77, layout_density=0.04, sample_min=1024, sample_max=8192)
+
+    def front_heavy(g):
+        for a, b in zip(gs.offsets[:-1], gs.offsets[1:]):
+            g[a:a + min(60000, (b - a) // 4)] *= np.float32(1000.0)
+
+    _run(gs, 8, [0.004, 0.004, 0.004], 77, layout_density=0.04, sample_min=1024, sample_max=8192, reshape=front_heavy)
 
 
 def test_replace_with_the_previous_payloads_in_another_order():
