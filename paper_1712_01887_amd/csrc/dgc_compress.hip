@@ -1609,6 +1609,35 @@ __global__ __launch_bounds__(kEmitThreads) void emit_staged_kernel(EmitArgs a) {
     const float* __restrict__ stage_u = a.stage_u ? a.stage_u + t * kWaveTile : nullptr;
     int32_t* __restrict__ tile_idx = out_idx + ((int64_t)sh.block_base + sh.tile_base[tl]);
     // the indices: an element's slot is rows before it + bits of its row in lower lanes + lower bits of its nibble
+    if (staged && tile_total < 256 && room == tile_total) {
+      // Fewer than 256 elements, all with a slot (at 1.6 % a tile selects 16): the counts of the
+      // lane's four rows ride in the bytes of one word (no byte can overflow), one scan over the
+      // lanes gives every row's "bits in lower lanes", the rows' totals shifted up by one, two and
+      // three bytes the "rows before it", and a lane walks its own bits, lowest first: two or
+      // three rounds instead of sixteen votes.
+      uint32_t x = w - ((w >> 1) & 0x5555u);
+      x = (x & 0x3333u) + ((x >> 2) & 0x3333u);  // a count per nibble
+      const uint32_t cnt = (x & 0xFu) | ((x & 0xF0u) << 4) | ((x & 0xF00u) << 8) | ((x & 0xF000u) << 12);
+      uint32_t incl = cnt;
+      for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t up = __shfl_up(incl, d);
+        if (lane >= d) incl += up;
+      }
+      const uint32_t tot = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+      uint32_t at = (incl - cnt) + ((tot << 8) + (tot << 16) + (tot << 24));  // next slot of each of the lane's rows
+      const int32_t e_lane = (int32_t)tile_element(t, lane, 0);
+      uint32_t rem = w;
+      while (__ballot(rem != 0u)) {
+        if (rem != 0u) {
+          const int b = __ffs((int)rem) - 1;  // bit 4 r + c
+          const int r8 = (b >> 2) * 8;
+          tile_idx[(at >> r8) & 0xFFu] = e_lane + (b >> 2) * 256 + (b & 3);
+          at += 1u << r8;
+          rem &= rem - 1u;
+        }
+      }
+      continue;
+    }
     int row_base = 0;
 #pragma unroll
     for (int r = 0; r < kRows; ++r) {
