@@ -1696,6 +1696,7 @@ struct EmitSlotsShared {
 
 __global__ __launch_bounds__(kEmitThreads) void emit_slots_kernel(EmitArgs a) {
   constexpr int kWaves = kEmitThreads / 64;
+  constexpr int kEmitWalk = 6;  // selected elements of one lane the short way takes
   constexpr int kTilesPerWave = 64 / kSlotsPerTile;
   static_assert(kEmitTiles <= 32 && kTilesPerWave * kWaves == kEmitTiles, "tile counts are scanned by half a wavefront");
   __shared__ EmitSlotsShared sh;
@@ -1788,8 +1789,65 @@ __global__ __launch_bounds__(kEmitThreads) void emit_slots_kernel(EmitArgs a) {
     const uint32_t w = sh.words[k * 64 + lane];
     const int64_t tile_slot = (int64_t)base + __shfl(excl, k);
     // Index order inside the tile is row (one 16-byte vector per lane), lane, component: an element's
-    // position is the rows before it, plus the bits of its row in lower lanes (from the votes), plus
-    // the lower bits of its nibble.  A row's (up to four) elements of a lane are read together.
+    // position is the rows before it, plus the bits of its row in lower lanes, plus the lower bits of
+    // its nibble.
+    int most = __popc(w);  // bits of the lane that has most
+    for (int d = 32; d >= 1; d >>= 1) {
+      const int o = __shfl_xor(most, d);
+      most = o > most ? o : most;
+    }
+    most = __builtin_amdgcn_readfirstlane(most);  // the same in every lane: branches on it are scalar
+    const int tile_count = __shfl(own, k);
+    if (tile_count < 256 && most <= kEmitWalk) {
+      // The usual case (a tile shared between tensors, or a dozen elements in one tile): positions
+      // from one packed scan (the counts of the lane's four rows in the bytes of a word, as in the
+      // staged pass), and every lane walks its own bits: all of the tile's reads of v are on their
+      // way before the first store, one round trip to memory per tile instead of one per row.
+      uint32_t xw = w - ((w >> 1) & 0x5555u);
+      xw = (xw & 0x3333u) + ((xw >> 2) & 0x3333u);  // a count per nibble
+      const uint32_t cnt = (xw & 0xFu) | ((xw & 0xF0u) << 4) | ((xw & 0xF00u) << 8) | ((xw & 0xF000u) << 12);
+      uint32_t inc = cnt;
+      for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t up = __shfl_up(inc, d);
+        if (lane >= d) inc += up;
+      }
+      const uint32_t tot = (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+      uint32_t next = (inc - cnt) + ((tot << 8) + (tot << 16) + (tot << 24));  // next position of each of the lane's rows
+      const int32_t e_lane = (int32_t)tile_element(tk, lane, 0);
+      uint32_t rem = w;
+      int32_t e[kEmitWalk];
+      int ps[kEmitWalk];
+      float x[kEmitWalk];
+#pragma unroll
+      for (int i = 0; i < kEmitWalk; ++i) {
+        e[i] = -1;
+        ps[i] = 0;
+        x[i] = 0.0f;
+        if (i < most) {
+          if (rem != 0u) {
+            const int b = __ffs((int)rem) - 1;  // bit 4 r + c
+            const int r8 = (b >> 2) * 8;
+            ps[i] = (int)((next >> r8) & 0xFFu);
+            next += 1u << r8;
+            rem &= rem - 1u;
+            if (tile_slot + ps[i] < cap) e[i] = e_lane + (b >> 2) * 256 + (b & 3);
+            else overflow = true;  // region full: the element stays where it is
+          }
+          if (e[i] >= 0) x[i] = v[e[i]];
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < kEmitWalk; ++i) {
+        if (i < most && e[i] >= 0) {
+          out_idx[tile_slot + ps[i]] = e[i];
+          out_val[tile_slot + ps[i]] = x[i];
+          v[e[i]] = 0.0f;
+          if (a.factor_masking) u[e[i]] = 0.0f;
+        }
+      }
+      continue;
+    }
+    // Otherwise row by row, positions from votes; a row's (up to four) elements of a lane are read together.
     int row_base = 0;
 #pragma unroll
     for (int r = 0; r < kStreamUnroll; ++r) {
