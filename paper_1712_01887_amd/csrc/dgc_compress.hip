@@ -912,8 +912,8 @@ __device__ __forceinline__ int tile_counts_partial(const uint32_t* __restrict__ 
 
 // ---------------------------------------------------------------------------
 // Re-threshold on over-selection
-// (paper: Section 5 -- when far more elements pass than expected, a precise
-//  threshold is computed from those already selected)
+// (paper: Section 5 -- the exact threshold among the elements that passed, for a
+//  tensor that let too many pass)
 // ---------------------------------------------------------------------------
 // Runs between the streaming and the emit pass, one workgroup per tensor.  The workgroup adds up
 // the mask-bit counts the streaming pass has left for the tensor's tiles; only if the total
@@ -1677,9 +1677,10 @@ __global__ __launch_bounds__(kEmitThreads) void emit_staged_kernel(EmitArgs a) {
   if (overflow) atomicOr(&a.state->flags, (uint32_t)DGC_DIAG_OVERFLOW);
 }
 
-// Emit pass after a SLOTTED streaming pass.  Thread (tile, slot) of the workgroup's 32 tiles x
-// 8 slots asks for its slot's index and value at once with the tile's count and the counts of
-// the tensor's tiles before the workgroup; a tile that lies wholly inside the tensor and selected
+// Emit pass after a SLOTTED streaming pass.  Four threads per tile of the workgroup's 32 tiles,
+// two slots each: a thread asks for its slots' indices and values at once with the tile's count
+// and the counts of the tensor's tiles before the workgroup (two wavefronts per workgroup: the
+// parts of a 122 M-element set are all resident at once); a tile that lies wholly inside the tensor and selected
 // at most kSlotsPerTile elements is a straight copy (its u and v are masked already; an element
 // that finds the region full is put back).  The other tiles -- shared with a neighbour tensor, or
 // with more selected elements than slots -- are taken by the wavefront that holds them, one after
@@ -1691,13 +1692,16 @@ __global__ __launch_bounds__(kEmitThreads) void emit_staged_kernel(EmitArgs a) {
 struct EmitSlotsShared {
   uint16_t words[kEmitTiles * 64];  // mask words of the tiles that are not copied from slots
   int cnt[kEmitTiles];              // elements of every tile that belong to this tensor
-  int pre_tot[kEmitThreads / 64];
+  int pre_tot[kEmitSlotThreads / 64];
 };
 
-__global__ __launch_bounds__(kEmitThreads) void emit_slots_kernel(EmitArgs a) {
-  constexpr int kWaves = kEmitThreads / 64;
+__global__ __launch_bounds__(kEmitSlotThreads) void emit_slots_kernel(EmitArgs a) {
+  constexpr int kWaves = kEmitSlotThreads / 64;
+  constexpr int kLanesPerTile = kEmitSlotThreads / kEmitTiles;
+  constexpr int kPerLane = kSlotsPerTile / kLanesPerTile;
+  static_assert(kPerLane == 2 && kLanesPerTile * kPerLane == kSlotsPerTile, "a thread takes two neighbouring slots");
   constexpr int kEmitWalk = 6;  // selected elements of one lane the short way takes
-  constexpr int kTilesPerWave = 64 / kSlotsPerTile;
+  constexpr int kTilesPerWave = 64 / kLanesPerTile;
   static_assert(kEmitTiles <= 32 && kTilesPerWave * kWaves == kEmitTiles, "tile counts are scanned by half a wavefront");
   __shared__ EmitSlotsShared sh;
   const int tid = threadIdx.x;
@@ -1713,36 +1717,36 @@ __global__ __launch_bounds__(kEmitThreads) void emit_slots_kernel(EmitArgs a) {
   const int64_t t1 = (hi - 1) / kWaveTile;
   const int64_t first = blk.first_tile;
 
-  const int tl = tid / kSlotsPerTile;  // this thread's tile of the part ...
-  const int s = tid % kSlotsPerTile;   // ... and slot of that tile
+  const int tl = tid / kLanesPerTile;             // this thread's tile of the part ...
+  const int s = (tid % kLanesPerTile) * kPerLane;  // ... and the first of its two slots of that tile
   const int64_t t = first + tl;
   const bool exists = t <= t1;
   const bool inside = exists && t * kWaveTile >= lo && (t + 1) * kWaveTile <= hi;
   const uint32_t c_raw = exists ? a.tile_count[t] : 0u;
   const uint32_t c_own = c_raw & kTileCountMask;
-  int32_t e_slot = 0;
-  float x_slot = 0.0f;
+  int2 e_slot = make_int2(0, 0);
+  int2 x_slot = make_int2(0, 0);  // bits of the values
   const int32_t* __restrict__ records = reinterpret_cast<const int32_t*>(a.mask);  // see the streaming pass
   if (inside) {  // (a record only if the count says so; loaded before the count is known)
-    e_slot = records[t * kSlotRecord + s];
-    x_slot = __int_as_float(records[t * kSlotRecord + kSlotsPerTile + s]);
+    e_slot = *reinterpret_cast<const int2*>(records + t * kSlotRecord + s);
+    x_slot = *reinterpret_cast<const int2*>(records + t * kSlotRecord + kSlotsPerTile + s);
   }
   // Slots taken by the tensor's tiles before the workgroup's first one.  The tensor's first tile
   // counts like the others when it lies wholly inside the tensor (its line may hold a record);
   // shared with the tensor before, it has mask words, from which the tensor's share is recounted.
   const bool first_shared = t0 * kWaveTile < lo;
-  int pre = tile_counts_partial<kEmitThreads>(a.tile_count, first_shared ? t0 + 1 : t0, first, tid);
+  int pre = tile_counts_partial<kEmitSlotThreads>(a.tile_count, first_shared ? t0 + 1 : t0, first, tid);
   if (first > t0 && first_shared && wave == 0) pre += __popc(tensor_tile_word(a.mask, t0, lane, lo, hi));
   for (int d = 32; d >= 1; d >>= 1) pre += __shfl_xor(pre, d);
   if (lane == 0) sh.pre_tot[wave] = pre;
 
   const bool from_slots = inside && c_raw <= (uint32_t)kSlotsPerTile;  // (a flagged count is a large number)
-  // tiles of this wavefront that are taken from their mask words: one bit per tile, at the lane of its slot 0
+  // tiles of this wavefront that are taken from their mask words: one bit per tile, at its first lane
   const unsigned long long others = __ballot(exists && !from_slots && s == 0);
   if (from_slots && s == 0) sh.cnt[tl] = (int)c_own;
   if (!exists && s == 0) sh.cnt[tl] = 0;
   for (unsigned long long m = others; m; m &= m - 1) {
-    const int k = wave * kTilesPerWave + (__ffsll((long long)m) - 1) / kSlotsPerTile;
+    const int k = wave * kTilesPerWave + (__ffsll((long long)m) - 1) / kLanesPerTile;
     const uint32_t w = tensor_tile_word(a.mask, first + k, lane, lo, hi);
     sh.words[k * 64 + lane] = (uint16_t)w;
     int c = __popc(w);
@@ -1771,20 +1775,25 @@ __global__ __launch_bounds__(kEmitThreads) void emit_slots_kernel(EmitArgs a) {
   bool overflow = false;
   {
     const int tile_start = __shfl(excl, tl & 31);
-    if (from_slots && s < (int)c_own) {
-      const int64_t slot = (int64_t)base + tile_start + s;
-      if (slot < cap) {
-        out_idx[slot] = e_slot;
-        out_val[slot] = x_slot;
-      } else {  // region full: the element goes back to where the streaming pass took it from
-        overflow = true;
-        v[e_slot] = x_slot;
-        if (a.factor_masking) u[e_slot] = __int_as_float(records[t * kSlotRecord + 2 * kSlotsPerTile + s]);
+#pragma unroll
+    for (int q = 0; q < kPerLane; ++q) {
+      const int32_t e_q = q == 0 ? e_slot.x : e_slot.y;
+      const float x_q = __int_as_float(q == 0 ? x_slot.x : x_slot.y);
+      if (from_slots && s + q < (int)c_own) {
+        const int64_t slot = (int64_t)base + tile_start + s + q;
+        if (slot < cap) {
+          out_idx[slot] = e_q;
+          out_val[slot] = x_q;
+        } else {  // region full: the element goes back to where the streaming pass took it from
+          overflow = true;
+          v[e_q] = x_q;
+          if (a.factor_masking) u[e_q] = __int_as_float(records[t * kSlotRecord + 2 * kSlotsPerTile + s + q]);
+        }
       }
     }
   }
   for (unsigned long long m = others; m; m &= m - 1) {
-    const int k = wave * kTilesPerWave + (__ffsll((long long)m) - 1) / kSlotsPerTile;
+    const int k = wave * kTilesPerWave + (__ffsll((long long)m) - 1) / kLanesPerTile;
     const int64_t tk = first + k;
     const uint32_t w = sh.words[k * 64 + lane];
     const int64_t tile_slot = (int64_t)base + __shfl(excl, k);
@@ -1964,7 +1973,7 @@ hipError_t launch_emit(const EmitArgs& a, int32_t num_blocks, bool sorted, hipSt
   if (a.stage_v)
     hipLaunchKernelGGL(emit_staged_kernel, dim3((unsigned)num_blocks), dim3(kEmitThreads), 0, stream, a);
   else if (a.slotted)
-    hipLaunchKernelGGL(emit_slots_kernel, dim3((unsigned)num_blocks), dim3(kEmitThreads), 0, stream, a);
+    hipLaunchKernelGGL(emit_slots_kernel, dim3((unsigned)num_blocks), dim3(kEmitSlotThreads), 0, stream, a);
   else if (sorted)
     hipLaunchKernelGGL(emit_sorted_kernel, dim3((unsigned)num_blocks), dim3(kEmitThreads), 0, stream, a);
   else

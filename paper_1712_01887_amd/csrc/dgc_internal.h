@@ -47,7 +47,8 @@ constexpr int kSlotRecord = 32;  // 32-bit words per tile: the 128 bytes of the 
 constexpr uint32_t kTileCountHasMask = 0x80000000u;
 constexpr uint32_t kTileCountMask = 0x7FFFFFFFu;
 static_assert(3 * kSlotsPerTile <= kSlotRecord, "index, v' and u' of every slot");
-static_assert(kEmitTiles * kSlotsPerTile == kEmitThreads, "one emit thread per slot of the workgroup's tiles");
+constexpr int kEmitSlotThreads = 128;  // emit pass over records: two slots per thread
+static_assert(kEmitTiles * kSlotsPerTile == 2 * kEmitSlotThreads, "two slots of the workgroup's tiles per emit thread");
 constexpr int kRefineThreads = 1024;                  // the re-threshold pass: one workgroup per tensor
 
 // Receive side: pairs of one payload handled by one workgroup (kFlatPer per thread) and
