@@ -151,7 +151,7 @@ def load() -> C.CDLL:
     lib.dgc_decode_accumulate.restype = i32
     lib.dgc_decode_accumulate.argtypes = [vp, vp, i64, i32, P(vp), P(vp), P(i64), vp, vp, C.c_size_t, vp]
     lib.dgc_profile_stream_ceiling.restype = i32
-    lib.dgc_profile_stream_ceiling.argtypes = [vp, vp, vp, i64, vp]
+    lib.dgc_profile_stream_ceiling.argtypes = [vp, vp, vp, i64, i32, vp]
     lib.dgc_profile_enable.restype = i32
     lib.dgc_profile_enable.argtypes = [vp, i32]
     lib.dgc_profile_collect.restype = i32
@@ -201,9 +201,10 @@ def _ptr_array(tensors) -> "C.Array":
     return (C.c_void_p * len(tensors))(*[_ptr(t) for t in tensors])
 
 
-def dgc_profile_stream_ceiling(a, b, c) -> None:
+def dgc_profile_stream_ceiling(a, b, c, groups_per_cu: int = 0) -> None:
     """One launch of the bare three-read / two-write kernel over a, b, c (same length)."""
-    _check(load().dgc_profile_stream_ceiling(_ptr(a), _ptr(b), _ptr(c), int(a.numel()), _stream()),
+    _check(load().dgc_profile_stream_ceiling(_ptr(a), _ptr(b), _ptr(c), int(a.numel()), int(groups_per_cu),
+                                             _stream()),
            "dgc_profile_stream_ceiling")
 
 

@@ -757,10 +757,12 @@ dgc_status dgc_profile_disable(dgc_handle* h) {
   return DGC_OK;
 }
 
-dgc_status dgc_profile_stream_ceiling(const float* a, float* b, float* c, int64_t n, void* stream) {
+dgc_status dgc_profile_stream_ceiling(const float* a, float* b, float* c, int64_t n, int32_t groups_per_cu,
+                                      void* stream) {
   if (!a || !b || !c || n < 0 || n >= (int64_t)1 << 31) return DGC_ERR_INVALID_ARG;
+  if (groups_per_cu < 0 || groups_per_cu > 16) return DGC_ERR_INVALID_ARG;
   if (!aligned(a, 16) || !aligned(b, 16) || !aligned(c, 16)) return DGC_ERR_ALIGNMENT;
-  if (!hip_ok(launch_ceiling(a, b, c, n, static_cast<hipStream_t>(stream)), "launch ceiling kernel"))
+  if (!hip_ok(launch_ceiling(a, b, c, n, groups_per_cu, static_cast<hipStream_t>(stream)), "launch ceiling kernel"))
     return DGC_ERR_HIP;
   return DGC_OK;
 }

@@ -1932,11 +1932,21 @@ hipError_t launch_select(const SelectArgs& a, int32_t num_tensors, hipStream_t s
   return hipGetLastError();
 }
 
+// Dynamic LDS that nothing uses: it caps the workgroups a compute unit holds at `groups`.
+constexpr size_t kStreamStaticLds = sizeof(float) * kStreamWaves * 4 * kStreamUnroll * 64;  // mixed_z of stream_kernel
+static size_t stream_lds_pad(int groups, size_t static_lds) {
+  const size_t per = kLdsPerComputeUnit / (size_t)groups - 2048;  // (2 KB of slack for the allocation granule)
+  const size_t limit = 64 * 1024;                                  // a workgroup's LDS without a function attribute
+  const size_t want = per < limit ? per : limit;
+  return want > static_lds ? want - static_lds : 0;
+}
+
 template <bool NESTEROV, bool SCALED>
-static void launch_stream_mode(const StreamArgs& a, int mode, dim3 grid, dim3 block, hipStream_t stream) {
-  if (mode == kStreamStaged) hipLaunchKernelGGL((stream_kernel<NESTEROV, SCALED, kStreamStaged>), grid, block, 0, stream, a);
-  else if (mode == kStreamSlotted) hipLaunchKernelGGL((stream_kernel<NESTEROV, SCALED, kStreamSlotted>), grid, block, 0, stream, a);
-  else hipLaunchKernelGGL((stream_kernel<NESTEROV, SCALED, kStreamPlain>), grid, block, 0, stream, a);
+static void launch_stream_mode(const StreamArgs& a, int mode, int groups, dim3 grid, dim3 block, hipStream_t stream) {
+  const size_t pad = stream_lds_pad(groups, kStreamStaticLds);
+  if (mode == kStreamStaged) hipLaunchKernelGGL((stream_kernel<NESTEROV, SCALED, kStreamStaged>), grid, block, pad, stream, a);
+  else if (mode == kStreamSlotted) hipLaunchKernelGGL((stream_kernel<NESTEROV, SCALED, kStreamSlotted>), grid, block, pad, stream, a);
+  else hipLaunchKernelGGL((stream_kernel<NESTEROV, SCALED, kStreamPlain>), grid, block, pad, stream, a);
 }
 
 hipError_t launch_stream(const StreamArgs& a, hipStream_t stream) {
@@ -1946,21 +1956,24 @@ hipError_t launch_stream(const StreamArgs& a, hipStream_t stream) {
   const bool scaled = a.scale_from_state != 0 || a.scale_const != 1.0f;
   const dim3 grid((unsigned)blocks), block(kStreamThreads);
   const int mode = a.stage_v ? kStreamStaged : a.slotted ? kStreamSlotted : kStreamPlain;
+  // right after the norm pass part of g comes from the last-level cache, and more wavefronts pay
+  const int groups = a.scale_from_state ? kStreamGroupsAfterNorm : kStreamResidentGroups;
   if (a.nesterov) {
-    if (scaled) launch_stream_mode<true, true>(a, mode, grid, block, stream);
-    else launch_stream_mode<true, false>(a, mode, grid, block, stream);
+    if (scaled) launch_stream_mode<true, true>(a, mode, groups, grid, block, stream);
+    else launch_stream_mode<true, false>(a, mode, groups, grid, block, stream);
   } else {
-    if (scaled) launch_stream_mode<false, true>(a, mode, grid, block, stream);
-    else launch_stream_mode<false, false>(a, mode, grid, block, stream);
+    if (scaled) launch_stream_mode<false, true>(a, mode, groups, grid, block, stream);
+    else launch_stream_mode<false, false>(a, mode, groups, grid, block, stream);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_ceiling(const float* a, float* b, float* c, int64_t n, hipStream_t stream) {
+hipError_t launch_ceiling(const float* a, float* b, float* c, int64_t n, int groups, hipStream_t stream) {
   const int64_t tiles = n / kWaveTile;
   if (tiles < 1) return hipSuccess;
-  hipLaunchKernelGGL(ceiling_kernel, dim3((unsigned)ceil_div(tiles, kStreamWaves)), dim3(kStreamThreads), 0, stream,
-                     a, b, c, tiles);
+  if (groups < 1) groups = kStreamResidentGroups;
+  hipLaunchKernelGGL(ceiling_kernel, dim3((unsigned)ceil_div(tiles, kStreamWaves)), dim3(kStreamThreads),
+                     stream_lds_pad(groups, 0), stream, a, b, c, tiles);
   return hipGetLastError();
 }
 

@@ -22,8 +22,15 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 #endif
 constexpr int kStreamUnroll = DGC_STREAM_UNROLL;
 constexpr int kWaveTile = 64 * 4 * kStreamUnroll;  // elements per wavefront
-constexpr int kStreamThreads = 256;                 // 4 wavefronts per workgroup
+constexpr int kStreamThreads = 128;                 // 2 wavefronts per workgroup
 constexpr int kStreamWaves = kStreamThreads / 64;
+// Workgroups of the streaming pass a compute unit holds at a time.  The pass is faster with few
+// wavefronts in flight than with the 32 a compute unit could hold (six per compute unit move 5 %
+// more bytes per second than 32: fewer streams for the memory side to interleave), so every
+// launch asks for as much LDS as leaves room for this many workgroups in a compute unit's 160 KB.
+constexpr int kStreamResidentGroups = 3;
+constexpr int kStreamGroupsAfterNorm = 6;  // with clipping on: see launch_stream
+constexpr size_t kLdsPerComputeUnit = (size_t)160 * 1024;
 // Tile table: one int32 per wave tile = index of the tensor that holds the tile's
 // first element, with the top bit set when the tile is not wholly inside one
 // tensor or is the ragged last tile (such tiles look up every element's tensor).
@@ -284,7 +291,7 @@ int32_t norm_blocks(int64_t n);  // partial sums launch_norm leaves
 hipError_t launch_norm(const float* g, int64_t n, double* partials, hipStream_t stream);
 hipError_t launch_select(const SelectArgs& a, int32_t num_tensors, hipStream_t stream);
 hipError_t launch_stream(const StreamArgs& a, hipStream_t stream);
-hipError_t launch_ceiling(const float* a, float* b, float* c, int64_t n, hipStream_t stream);
+hipError_t launch_ceiling(const float* a, float* b, float* c, int64_t n, int groups, hipStream_t stream);
 hipError_t launch_refine(const RefineArgs& a, int32_t num_tensors, hipStream_t stream);
 hipError_t launch_emit(const EmitArgs& a, int32_t num_blocks, bool sorted, hipStream_t stream);
 hipError_t launch_scatter_pairs(float* dense, int64_t n, const PairPayloads& p, int32_t first,

@@ -200,8 +200,9 @@ def test_wire_format_entry_points_validate_before_touching_the_device(dgc_lib):
     assert dec(d._h, a, 10, 1, ptrs, ptrs, huge, None, a, 1 << 24, None) == B.DGC_ERR_CAPACITY
     odd = (C.c_void_p * 1)(a + 1)
     assert dec(d._h, a, 10, 1, odd, ptrs, cnt, None, a, 1 << 24, None) == B.DGC_ERR_ALIGNMENT
-    assert dgc_lib.dgc_profile_stream_ceiling(None, a, a, 10, None) == B.DGC_ERR_INVALID_ARG
-    assert dgc_lib.dgc_profile_stream_ceiling(a, a + 4, a, 10, None) == B.DGC_ERR_ALIGNMENT
+    assert dgc_lib.dgc_profile_stream_ceiling(None, a, a, 10, 0, None) == B.DGC_ERR_INVALID_ARG
+    assert dgc_lib.dgc_profile_stream_ceiling(a, a, a, 10, 17, None) == B.DGC_ERR_INVALID_ARG
+    assert dgc_lib.dgc_profile_stream_ceiling(a, a + 4, a, 10, 0, None) == B.DGC_ERR_ALIGNMENT
     d.close()
 
 
