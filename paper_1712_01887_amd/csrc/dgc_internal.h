@@ -81,7 +81,7 @@ static_assert((kMergeMaxRange / 128) % kMergeMaxThreads == 0, "dealt evenly to t
 // Receive side at warm-up densities: a workgroup owns one emit workgroup's part and keeps
 // the whole range of the dense vector in LDS.
 constexpr int kPartThreads = 1024;
-constexpr int kPartPer = 8;  // pairs a thread holds per round
+constexpr int kPartPer = 4;  // pairs a thread holds per round (8: 5 to 15 % slower at every warm-up density; 2: slower at 25 %)
 constexpr int kPartRound = kPartThreads * kPartPer;
 constexpr int kPartClearThreads = 256;
 static_assert(kEmitElements <= 65536 && kEmitElements % kPartThreads == 0 &&
