@@ -52,7 +52,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0           # MI355X published peak
 BYTES_PER_ELEMENT = 20           # streaming pass: read g, u, v; write u, v (fp32)
-CEILING_GROUPS = (2, 3, 4, 8)     # resident workgroups per compute unit the bare streaming kernel is timed with
+CEILING_GROUPS = (2, 3, 4, 6, 16)  # resident wavefronts per compute unit the bare streaming kernel is timed with
 MIN_TIMED_SECONDS = 0.2          # the timed region is repeated until it has run this long
 SEED = 2025
 WARMUP_DENSITIES = (0.25, 0.0625, 0.015625, 0.004, 0.001)
@@ -440,7 +440,7 @@ class Workload:
                 breakdown["norm_kernel_GBps"] = round(4 * n / (norm_ms / calls * 1e-3) / 1e9, 1)
             # the box's own ceiling for this traffic: the bare three-read / two-write kernel on the same
             # rotating buffers, timed the same way (it overwrites u and v: last use of this workload's state).
-            # How fast such a kernel runs depends on how many of its workgroups a compute unit holds at a
+            # How fast such a kernel runs depends on how many of its wavefronts a compute unit holds at a
             # time: several residencies are timed and the fastest is the ceiling.
             R = self.rotate
             shapes = {}
@@ -460,10 +460,10 @@ class Workload:
             ceiling = BYTES_PER_ELEMENT * (n // 1024 * 1024) / (ceil_ms * 1e-3) / 1e9
             roofline["practical_ceiling"] = {
                 "kernel": "ceiling_kernel (3 arrays read, 2 written, non-temporal, same tiling, no table, no mask), the "
-                          "fastest of several numbers of resident workgroups per compute unit",
+                          "fastest of several numbers of resident wavefronts per compute unit",
                 "achieved": round(ceiling, 1), "unit": "GB/s", "avg_kernel_us": round(ceil_ms * 1e3, 2),
-                "workgroups_per_cu": best,
-                "avg_kernel_us_by_workgroups_per_cu": {str(g): round(t * 1e3, 2) for g, t in shapes.items()},
+                "wavefronts_per_cu": best,
+                "avg_kernel_us_by_wavefronts_per_cu": {str(g): round(t * 1e3, 2) for g, t in shapes.items()},
                 "stream_kernel_frac_of_it": round(achieved / ceiling, 4)}
         counts = max(1, int(self.fresh[0][2].sum().item()))
         out["pairs_per_payload"] = counts

@@ -433,9 +433,9 @@ dgc_status dgc_profile_disable(dgc_handle* h);
  * whole tiles of 1024 elements; three arrays read, two written, 20 bytes per element).
  * What it reaches on a given box is the practical ceiling the streaming pass is compared
  * with besides the nominal HBM peak.  a, b, c: device, n floats, 16-byte aligned.
- * groups_per_cu: workgroups (of two wavefronts) a compute unit may hold at a time, 1 to 16; how
- * many bytes per second such a kernel moves depends on it, so a harness tries several and takes
- * the fastest; 0 = as many as the streaming pass itself is launched with.
+ * groups_per_cu: workgroups (of one wavefront each) a compute unit may hold at a time, 2 to 16;
+ * how many bytes per second such a kernel moves depends on it, so a harness tries several and
+ * takes the fastest; 0 = as many wavefronts as the streaming pass itself keeps on a compute unit.
  */
 dgc_status dgc_profile_stream_ceiling(const float* a, float* b, float* c, int64_t n, int32_t groups_per_cu,
                                       void* stream);

@@ -852,11 +852,11 @@ __global__ __launch_bounds__(kStreamThreads) void stream_kernel(StreamArgs a) {
 // non-temporal, one wave tile per wavefront) with next to no arithmetic, no table and no
 // mask.  What this kernel reaches on a box is the ceiling the streaming pass can be held
 // against besides the nominal HBM peak.  Whole tiles only.
-__global__ __launch_bounds__(kStreamThreads) void ceiling_kernel(const float* __restrict__ a, float* __restrict__ b,
-                                                                 float* __restrict__ c, int64_t tiles) {
+__global__ __launch_bounds__(64) void ceiling_kernel(const float* __restrict__ a, float* __restrict__ b,
+                                                     float* __restrict__ c, int64_t tiles) {
   constexpr int U = kStreamUnroll;
-  const int lane = threadIdx.x & 63;
-  const int64_t tile = (int64_t)blockIdx.x * kStreamWaves + (threadIdx.x >> 6);
+  const int lane = threadIdx.x;
+  const int64_t tile = blockIdx.x;  // one wavefront per workgroup: the residency is set in wavefronts
   if (tile >= tiles) return;
   const vec4* a4 = reinterpret_cast<const vec4*>(a + tile * kWaveTile) + lane;
   vec4* b4 = reinterpret_cast<vec4*>(b + tile * kWaveTile) + lane;
@@ -1971,9 +1971,8 @@ hipError_t launch_stream(const StreamArgs& a, hipStream_t stream) {
 hipError_t launch_ceiling(const float* a, float* b, float* c, int64_t n, int groups, hipStream_t stream) {
   const int64_t tiles = n / kWaveTile;
   if (tiles < 1) return hipSuccess;
-  if (groups < 1) groups = kStreamResidentGroups;
-  hipLaunchKernelGGL(ceiling_kernel, dim3((unsigned)ceil_div(tiles, kStreamWaves)), dim3(kStreamThreads),
-                     stream_lds_pad(groups, 0), stream, a, b, c, tiles);
+  if (groups < 1) groups = kStreamResidentGroups * kStreamWaves;
+  hipLaunchKernelGGL(ceiling_kernel, dim3((unsigned)tiles), dim3(64), stream_lds_pad(groups, 0), stream, a, b, c, tiles);
   return hipGetLastError();
 }
 
